@@ -1,0 +1,245 @@
+/*
+ * depsync -- fine-grained synchronisation of dependent tiled kernels on one MI355X (gfx950).
+ *
+ * C ABI of the library.  A "chain" is a producer kernel followed by a consumer kernel whose
+ * one input is the producer's output (Section III of the paper, Fig. 4a: the host function
+ * MLP(BS, H, X, W1, XW1, W2, XW12)).  Instead of letting the whole producer finish before
+ * the consumer starts, both are launched on two streams of the same GPU and every consumer
+ * tile waits, through semaphores in device memory, only for the producer tiles it reads
+ * (Sections III-A to III-D).  A synchronisation policy maps producer tiles to semaphores
+ * (Section III-E).
+ *
+ * Conventions
+ *  - Every function returns an int status: DEPSYNC_OK (0) or a negative DEPSYNC_E* code.
+ *    Nothing throws or aborts across this boundary.
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The library never frees
+ *    or reallocates them and keeps no reference after the call returns.
+ *  - Calls that enqueue work are asynchronous.  On return, work enqueued later on
+ *    stream_producer is ordered after the whole chain (the library forks the consumer
+ *    stream off the producer stream with an event and joins it back).
+ *  - Streams are hipStream_t handles passed as void*; NULL means the default stream for
+ *    stream_producer and "use the policy's own internal stream" for stream_consumer.
+ *  - Semaphores, the tile-dispatch counter and the status block live in a small workspace
+ *    owned by the sync_policy_t object.  One policy object must not be used by two chains
+ *    that can run concurrently; calls using one policy must be enqueued in host-call order.
+ *  - Element type is 16-bit (bf16 or fp16) with fp32 accumulation; the intermediate and the
+ *    output are rounded to the 16-bit type with round-to-nearest-even.
+ *  - Every row must start on a 16-byte boundary: base pointers 16-byte aligned and leading
+ *    dimensions multiples of 8 elements; inner (K) dimensions multiples of 64.  Violations
+ *    return DEPSYNC_EINVAL.
+ */
+#ifndef DEPSYNC_H
+#define DEPSYNC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- status codes ------------------------------------------------------------------ */
+#define DEPSYNC_OK 0
+#define DEPSYNC_EINVAL (-1)   /* null pointer, bad shape, bad alignment, bad enum          */
+#define DEPSYNC_ENOMEM (-2)   /* workspace allocation failed                               */
+#define DEPSYNC_EHIP (-3)     /* a HIP call failed; see depsync_last_hip_error()           */
+#define DEPSYNC_ETIMEOUT (-4) /* a bounded wait (spin_limit) expired; see depsync_last_status */
+#define DEPSYNC_ENOTIMPL (-5) /* valid request this build does not implement               */
+
+/* Synchronisation policies (Section III-E and Section IV-B). */
+typedef enum {
+    DEPSYNC_ROWSYNC = 0,    /* all column tiles of a producer row share a semaphore       */
+    DEPSYNC_TILESYNC = 1,   /* one semaphore per producer tile                            */
+    DEPSYNC_STRIDEDSYNC = 2 /* producer tiles at a fixed stride share a semaphore         */
+} depsync_policy_kind;
+
+/* How the two kernels of a chain are ordered. */
+typedef enum {
+    DEPSYNC_MODE_FINE = 0,       /* two streams, per-tile semaphores (the paper's method)  */
+    DEPSYNC_MODE_STREAMSYNC = 1, /* the same kernels on one stream (the paper's baseline)  */
+    DEPSYNC_MODE_PLAIN = 2       /* the same tile code with the sync hooks compiled out,
+                                    one stream, hardware block order                        */
+} depsync_mode;
+
+/* What sits between the two GeMMs. */
+typedef enum {
+    DEPSYNC_MID_NONE = 0,
+    DEPSYNC_MID_GELU = 1,        /* Fig. 2a; exact erf form                                 */
+    DEPSYNC_MID_RELU = 2,
+    DEPSYNC_MID_SWIGLU = 3,      /* Fig. 3: silu(gate) * up, fused into the producer tile   */
+    DEPSYNC_MID_CAUSAL_ATTN = 4  /* Fig. 2b, prompt phase: a third, middle kernel           */
+} depsync_mid;
+
+typedef enum { DEPSYNC_BF16 = 0, DEPSYNC_FP16 = 1 } depsync_dtype;
+
+/* Macro-tile shapes (rows x columns of the output computed by one workgroup). */
+typedef enum {
+    DEPSYNC_TILE_AUTO = 0,
+    DEPSYNC_TILE_256x256 = 1,
+    DEPSYNC_TILE_256x128 = 2,
+    DEPSYNC_TILE_128x256 = 3,
+    DEPSYNC_TILE_128x128 = 4,
+    DEPSYNC_TILE_64x128 = 5,
+    DEPSYNC_TILE_64x64 = 6,
+    DEPSYNC_TILE__COUNT = 7
+} depsync_tile;
+
+/* Policy flags. */
+#define DEPSYNC_FLAG_NO_REORDER 1u    /* do NOT load the independent operand before the wait
+                                         (switches off the reordering of Section IV-C)       */
+#define DEPSYNC_FLAG_COUNT 2u         /* count posts / waits / polling waits in the status   */
+#define DEPSYNC_FLAG_REVERSE_ORDER 4u /* debug: hand producer tiles out in reverse order     */
+#define DEPSYNC_FLAG_HW_ORDER 8u      /* FINE/STREAMSYNC: take the tile from the hardware
+                                         block index, no dispatch counter ("avoid custom tile
+                                         order", Section IV-C).  Only legal when producer and
+                                         consumer tiles all fit on the GPU at once; otherwise
+                                         DEPSYNC_EINVAL.                                      */
+
+typedef struct {
+    uint32_t stride;      /* STRIDEDSYNC on a GeMM chain: distance, in producer column tiles,
+                             between tiles that share a semaphore; 0 = derive from the chain  */
+    uint32_t count;       /* STRIDEDSYNC: tiles per semaphore; 0 = derive                     */
+    uint32_t flags;       /* DEPSYNC_FLAG_*                                                   */
+    uint32_t spin_limit;  /* 0 = wait without bound; otherwise give up after this many polls,
+                             record DEPSYNC_ETIMEOUT in the status and skip the tile's stores */
+    uint32_t delay_tile;  /* debug: producer tile (row-major index) + 1 to delay; 0 = none    */
+    uint32_t delay_iters; /* debug: s_sleep iterations the delayed tile spends before its post */
+} depsync_policy_params;
+
+typedef struct sync_policy sync_policy_t;
+
+typedef struct {
+    int32_t timed_out;       /* number of tiles whose bounded wait expired                    */
+    int32_t first_timeout;   /* dispatch ticket of the first such tile, -1 if none            */
+    uint32_t posts;          /* with DEPSYNC_FLAG_COUNT: semaphore increments                 */
+    uint32_t waits;          /* with DEPSYNC_FLAG_COUNT: semaphore waits executed             */
+    uint32_t polling_waits;  /* ... of which the first read did not already satisfy the wait  */
+    uint32_t launches;       /* chains enqueued with this policy since create/reset           */
+} depsync_status;
+
+/* What the library decided for a chain (for reports; filled by depsync_*_chain_plan). */
+typedef struct {
+    int32_t tile_prod, tile_mid, tile_cons;   /* depsync_tile ids (tile_mid: attention only)  */
+    int32_t prod_grid_x, prod_grid_y;         /* column tiles, row tiles of the producer      */
+    int32_t mid_grid_x, mid_grid_y;
+    int32_t cons_grid_x, cons_grid_y;
+    int32_t n_prod, n_mid, n_cons;            /* tiles per stage                              */
+    int32_t n_sems;                           /* semaphores used                              */
+    int32_t slots;                            /* workgroups resident at once (CUs x occupancy) */
+    int32_t waves_streamsync, waves_fine;     /* ceil(P/slots)+ceil(C/slots), ceil((P+C)/slots) */
+    double flops;                             /* algorithmic flops of the chain               */
+    double bytes;                             /* algorithmic bytes: every operand once        */
+} depsync_plan_info;
+
+/*
+ * GeMM -> (pointwise | attention) -> GeMM (Fig. 2a, Fig. 2b, Fig. 3).
+ *   H = mid(X W1)        X[M x K1], W1 mathematically [K1 x N1w]
+ *   Y = H' W2            W2 mathematically [K2 x N2]
+ * Weights are passed TRANSPOSED, i.e. as row-major [N x K] arrays (the layout in which
+ * torch.nn.Linear stores its weight), so that both MFMA operands are contiguous along K.
+ *   mid = NONE/GELU/RELU : N1w = N1, H[M x N1] is the intermediate, K2 = N1.
+ *   mid = SWIGLU         : W1t has 2*N1 rows: gate rows [0,N1), up rows [N1,2*N1);
+ *                          H[M x N1] = silu(gate) * up, K2 = N1.
+ *   mid = CAUSAL_ATTN    : N1 = 3*heads*head_dim, H = QKV[M x N1] with column blocks
+ *                          Q | K | V, head h at columns h*head_dim inside each block;
+ *                          T[M x heads*head_dim] = per-head causal softmax(QK^T/sqrt(d)) V
+ *                          over each of `batch` sequences of `seq` rows (M = batch*seq);
+ *                          K2 = heads*head_dim, Y = T W2.
+ */
+typedef struct {
+    int32_t M, K1, N1, N2;
+    int32_t dtype;               /* depsync_dtype                                            */
+    int32_t mid;                 /* depsync_mid                                              */
+    const void* X;   int64_t ldx;   /* [M x K1]                                              */
+    const void* W1t; int64_t ldw1;  /* [N1 (2*N1 for SWIGLU) x K1]                           */
+    void* H;         int64_t ldh;   /* [M x N1]   intermediate, written then read            */
+    const void* W2t; int64_t ldw2;  /* [N2 x K2]                                             */
+    void* Y;         int64_t ldy;   /* [M x N2]                                              */
+    void* T;         int64_t ldt;   /* CAUSAL_ATTN only: [M x heads*head_dim]                */
+    int32_t batch, seq, heads, head_dim; /* CAUSAL_ATTN only                                 */
+    int32_t tile_prod, tile_cons;   /* depsync_tile; 0 = chosen by the library               */
+} depsync_gemm_chain_desc;
+
+/*
+ * Conv2D -> ReLU -> Conv2D by implicit GeMM (Section IV-B "Conv2D"): 3x3, stride 1, zero
+ * padding 1, cross-correlation, NHWC activations, weights [K][3][3][C] (C contiguous):
+ *   mid[b,y,x,k] = relu(sum_{r,s,c} in[b,y+r-1,x+s-1,c] w1[k,r,s,c]);  out = conv(mid, w2).
+ * C and K1 must be multiples of 64.
+ */
+typedef struct {
+    int32_t B, H, W, C, K1, K2;
+    int32_t dtype;
+    const void* in;   /* [B,H,W,C]   */
+    const void* w1;   /* [K1,3,3,C]  */
+    void* mid;        /* [B,H,W,K1]  */
+    const void* w2;   /* [K2,3,3,K1] */
+    void* out;        /* [B,H,W,K2]  */
+    int32_t tile_prod, tile_cons;
+} depsync_conv_chain_desc;
+
+/* ---- policy objects (CuStage + policy of Fig. 4; init of Section III-D) ------------- */
+
+/* Create a policy and its workspace on the current device.  params may be NULL.          */
+int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* params,
+                       sync_policy_t** out);
+/* Synchronises the device, then frees the workspace.                                      */
+int sync_policy_destroy(sync_policy_t* pol);
+/* Re-zero semaphores, dispatch counter and status on `stream` (a fill kernel, safe under
+ * graph capture) and restart the launch epoch.  Needed only after DEPSYNC_ETIMEOUT.       */
+int dep_chain_reset(sync_policy_t* pol, void* stream);
+/* Synchronises the policy's streams, then copies the status block to the host.  Returns
+ * DEPSYNC_ETIMEOUT if a bounded wait expired since the last reset.                        */
+int depsync_last_status(sync_policy_t* pol, depsync_status* out);
+
+/* ---- chains -------------------------------------------------------------------------- */
+
+/* Enqueue the GeMM chain.  Section III, Fig. 4a.                                          */
+int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync_mode mode,
+                   void* stream_producer, void* stream_consumer);
+/* Enqueue the Conv2D chain.  Section IV-B.                                                */
+int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync_mode mode,
+                   void* stream_producer, void* stream_consumer);
+/* Dry run: validate the descriptor and report tiles, grids, wave counts, flops and bytes
+ * without touching the device workspace.  n_cu <= 0 reads the CU count from the current
+ * device (which then must exist).                                                          */
+int depsync_gemm_chain_plan(const depsync_gemm_chain_desc* d, const sync_policy_t* pol,
+                            int n_cu, depsync_plan_info* out);
+int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_t* pol,
+                            int n_cu, depsync_plan_info* out);
+
+/* ---- host mirrors of the device index arithmetic (Fig. 4b; Section II-A) -------------- */
+
+/* Linear position of tile (x,y) in row-major order: y*grid_x + x.                         */
+int depsync_row_major(int tile_x, int tile_y, int grid_x, int grid_y);
+/* Semaphore index of producer tile (x,y); stride is used by STRIDEDSYNC only.             */
+int depsync_policy_sem(depsync_policy_kind kind, int tile_x, int tile_y, int grid_x,
+                       int grid_y, int stride);
+/* Value the semaphore holds when everything mapped to it has posted once.                 */
+int depsync_policy_value(depsync_policy_kind kind, int grid_x, int grid_y, int stride);
+/* waves = ceil(tiles / (occupancy * n_cu)); *utilization = tiles / (waves * occupancy * n_cu). */
+int depsync_wave_model(int n_tiles, int occupancy, int n_cu, int* waves, double* utilization);
+/* Number of semaphore waits a GeMM chain performs under a policy when every consumer tile
+ * reads full producer rows (Section III-E).                                                */
+int depsync_sync_count(depsync_policy_kind kind, int prod_grid_x, int prod_grid_y,
+                       int cons_grid_x, int cons_grid_y, int prod_rows_per_cons_row);
+
+/* The planner's schedule model: makespan of gx1*gy1 producer tiles of duration d1 followed by
+ * gx2*gy2 consumer tiles of duration d2 on `slots` workgroup slots, row-major issue order;
+ * consumer row y reads producer rows [y*r - halo, (y+1)*r - 1 + halo] with r = ceil(gy1/gy2).
+ * stream_sync != 0 models the kernel-boundary barrier (Fig. 1b), 0 the per-tile waits (Fig. 1c). */
+double depsync_simulate_chain(int slots, int gx1, int gy1, double d1, int gx2, int gy2, double d2,
+                              int halo, int stream_sync);
+
+/* ---- misc ------------------------------------------------------------------------------ */
+const char* depsync_strerror(int status);
+/* Last HIP error code seen by this thread's failing call (0 if none).                      */
+int depsync_last_hip_error(void);
+/* Rows and columns of a depsync_tile id; DEPSYNC_EINVAL for AUTO or unknown ids.           */
+int depsync_tile_shape(int tile, int* rows, int* cols);
+/* CU count and shader clock (kHz) of the current device.                                   */
+int depsync_device_info(int* n_cu, int* clock_khz);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DEPSYNC_H */

@@ -1,0 +1,320 @@
+"""Thin Python binding of libdepsync.so (argument marshalling only).
+
+Every step of a chain runs in the library's HIP kernels; this module only turns torch
+tensors into device pointers and streams into hipStream_t handles, and mirrors the names of
+include/depsync.h.  There is no fallback: if the shared library is missing or a call fails,
+an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libdepsync.so")
+
+# enums of include/depsync.h
+ROWSYNC, TILESYNC, STRIDEDSYNC = 0, 1, 2
+MODE_FINE, MODE_STREAMSYNC, MODE_PLAIN = 0, 1, 2
+MID_NONE, MID_GELU, MID_RELU, MID_SWIGLU, MID_CAUSAL_ATTN = 0, 1, 2, 3, 4
+BF16, FP16 = 0, 1
+TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128, TILE_64x128, TILE_64x64 = range(7)
+FLAG_NO_REORDER, FLAG_COUNT, FLAG_REVERSE_ORDER, FLAG_HW_ORDER = 1, 2, 4, 8
+OK, EINVAL, ENOMEM, EHIP, ETIMEOUT, ENOTIMPL = 0, -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "sync_policy_create", "sync_policy_destroy", "dep_chain_reset", "depsync_last_status",
+    "dep_gemm_chain", "dep_conv_chain", "depsync_gemm_chain_plan", "depsync_conv_chain_plan",
+    "depsync_row_major", "depsync_policy_sem", "depsync_policy_value", "depsync_wave_model",
+    "depsync_sync_count", "depsync_simulate_chain", "depsync_strerror", "depsync_last_hip_error",
+    "depsync_tile_shape", "depsync_device_info",
+]
+
+
+class DepsyncError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        msg = _lib().depsync_strerror(status).decode()
+        if status == EHIP:
+            msg += f" [hip error {_lib().depsync_last_hip_error()}]"
+        super().__init__(f"{what}: {msg} ({status})")
+
+
+class PolicyParams(ctypes.Structure):
+    _fields_ = [("stride", ctypes.c_uint32), ("count", ctypes.c_uint32), ("flags", ctypes.c_uint32),
+                ("spin_limit", ctypes.c_uint32), ("delay_tile", ctypes.c_uint32),
+                ("delay_iters", ctypes.c_uint32)]
+
+
+class Status(ctypes.Structure):
+    _fields_ = [("timed_out", ctypes.c_int32), ("first_timeout", ctypes.c_int32),
+                ("posts", ctypes.c_uint32), ("waits", ctypes.c_uint32),
+                ("polling_waits", ctypes.c_uint32), ("launches", ctypes.c_uint32)]
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [("tile_prod", ctypes.c_int32), ("tile_mid", ctypes.c_int32), ("tile_cons", ctypes.c_int32),
+                ("prod_grid_x", ctypes.c_int32), ("prod_grid_y", ctypes.c_int32),
+                ("mid_grid_x", ctypes.c_int32), ("mid_grid_y", ctypes.c_int32),
+                ("cons_grid_x", ctypes.c_int32), ("cons_grid_y", ctypes.c_int32),
+                ("n_prod", ctypes.c_int32), ("n_mid", ctypes.c_int32), ("n_cons", ctypes.c_int32),
+                ("n_sems", ctypes.c_int32), ("slots", ctypes.c_int32),
+                ("waves_streamsync", ctypes.c_int32), ("waves_fine", ctypes.c_int32),
+                ("flops", ctypes.c_double), ("bytes", ctypes.c_double)]
+
+    def as_dict(self):
+        return {k: getattr(self, k) for k, _ in self._fields_}
+
+
+class GemmChainDesc(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int32), ("K1", ctypes.c_int32), ("N1", ctypes.c_int32), ("N2", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("mid", ctypes.c_int32),
+                ("X", ctypes.c_void_p), ("ldx", ctypes.c_int64),
+                ("W1t", ctypes.c_void_p), ("ldw1", ctypes.c_int64),
+                ("H", ctypes.c_void_p), ("ldh", ctypes.c_int64),
+                ("W2t", ctypes.c_void_p), ("ldw2", ctypes.c_int64),
+                ("Y", ctypes.c_void_p), ("ldy", ctypes.c_int64),
+                ("T", ctypes.c_void_p), ("ldt", ctypes.c_int64),
+                ("batch", ctypes.c_int32), ("seq", ctypes.c_int32), ("heads", ctypes.c_int32),
+                ("head_dim", ctypes.c_int32),
+                ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32)]
+
+
+class ConvChainDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32), ("C", ctypes.c_int32),
+                ("K1", ctypes.c_int32), ("K2", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("inp", ctypes.c_void_p), ("w1", ctypes.c_void_p), ("mid", ctypes.c_void_p),
+                ("w2", ctypes.c_void_p), ("out", ctypes.c_void_p),
+                ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32)]
+
+
+_LIB = None
+
+
+def _lib() -> ctypes.CDLL:
+    global _LIB
+    if _LIB is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2305_13450_amd.build or "
+                "__graft_entry__.build()); there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32 = ctypes.c_void_p, ctypes.c_int
+        L.sync_policy_create.argtypes = [i32, ctypes.POINTER(PolicyParams), ctypes.POINTER(vp)]
+        L.sync_policy_destroy.argtypes = [vp]
+        L.dep_chain_reset.argtypes = [vp, vp]
+        L.depsync_last_status.argtypes = [vp, ctypes.POINTER(Status)]
+        L.dep_gemm_chain.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, vp, vp]
+        L.dep_conv_chain.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, vp, vp]
+        L.depsync_gemm_chain_plan.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
+        L.depsync_conv_chain_plan.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
+        L.depsync_row_major.argtypes = [i32] * 4
+        L.depsync_policy_sem.argtypes = [i32] * 6
+        L.depsync_policy_value.argtypes = [i32] * 4
+        L.depsync_wave_model.argtypes = [i32, i32, i32, ctypes.POINTER(i32), ctypes.POINTER(ctypes.c_double)]
+        L.depsync_sync_count.argtypes = [i32] * 6
+        L.depsync_simulate_chain.argtypes = [i32, i32, i32, ctypes.c_double, i32, i32, ctypes.c_double, i32, i32]
+        L.depsync_simulate_chain.restype = ctypes.c_double
+        L.depsync_strerror.argtypes = [i32]
+        L.depsync_strerror.restype = ctypes.c_char_p
+        L.depsync_last_hip_error.argtypes = []
+        L.depsync_tile_shape.argtypes = [i32, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.depsync_device_info.argtypes = [ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        _LIB = L
+    return _LIB
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise DepsyncError(status, what)
+
+
+def _stream_handle(stream) -> Optional[int]:
+    """torch.cuda.Stream | raw handle | None -> hipStream_t as an integer (None = NULL)."""
+    if stream is None:
+        return None
+    if hasattr(stream, "cuda_stream"):
+        return int(stream.cuda_stream) or None
+    return int(stream) or None
+
+
+def _dtype_code(t) -> int:
+    import torch
+    if t.dtype == torch.bfloat16:
+        return BF16
+    if t.dtype == torch.float16:
+        return FP16
+    raise TypeError(f"unsupported element type {t.dtype}")
+
+
+def _dev2d(t, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    if t.dim() != 2 or t.stride(1) != 1:
+        raise ValueError(f"{name} must be 2-D with contiguous rows")
+    return t.data_ptr(), t.stride(0)
+
+
+class SyncPolicy:
+    """Owner of a sync_policy_t (policy kind + semaphore workspace)."""
+
+    def __init__(self, kind: int, stride: int = 0, count: int = 0, flags: int = 0, spin_limit: int = 0,
+                 delay_tile: int = 0, delay_iters: int = 0):
+        self.kind = kind
+        params = PolicyParams(stride, count, flags, spin_limit, delay_tile, delay_iters)
+        h = ctypes.c_void_p()
+        _check(_lib().sync_policy_create(kind, ctypes.byref(params), ctypes.byref(h)), "sync_policy_create")
+        self._h = h
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise RuntimeError("policy already destroyed")
+        return self._h
+
+    def destroy(self):
+        if self._h is not None:
+            _check(_lib().sync_policy_destroy(self._h), "sync_policy_destroy")
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+    def reset(self, stream=None):
+        _check(_lib().dep_chain_reset(self.handle, _stream_handle(stream)), "dep_chain_reset")
+
+    def status(self, raise_on_timeout: bool = True) -> Status:
+        st = Status()
+        rc = _lib().depsync_last_status(self.handle, ctypes.byref(st))
+        if rc == ETIMEOUT and not raise_on_timeout:
+            return st
+        _check(rc, "depsync_last_status")
+        return st
+
+
+def sync_policy_create(kind: int, **params) -> SyncPolicy:
+    return SyncPolicy(kind, **params)
+
+
+def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, head_dim=0) -> GemmChainDesc:
+    d = GemmChainDesc()
+    d.X, d.ldx = _dev2d(X, "X")
+    d.W1t, d.ldw1 = _dev2d(W1t, "W1t")
+    d.H, d.ldh = _dev2d(H, "H")
+    d.W2t, d.ldw2 = _dev2d(W2t, "W2t")
+    d.Y, d.ldy = _dev2d(Y, "Y")
+    d.M, d.K1 = X.shape
+    d.N1 = H.shape[1]
+    d.N2 = Y.shape[1]
+    d.dtype = _dtype_code(X)
+    for t in (W1t, H, W2t, Y):
+        if t.dtype != X.dtype:
+            raise TypeError("all tensors of a chain must share one element type")
+    d.mid = mid
+    if T is not None:
+        d.T, d.ldt = _dev2d(T, "T")
+    d.batch, d.seq, d.heads, d.head_dim = batch, seq, heads, head_dim
+    d.tile_prod = d.tile_cons = tile
+    rows1 = 2 * d.N1 if mid == MID_SWIGLU else d.N1
+    k2 = heads * head_dim if mid == MID_CAUSAL_ATTN else d.N1
+    if tuple(W1t.shape) != (rows1, d.K1) or tuple(W2t.shape) != (d.N2, k2) or H.shape[0] != d.M or Y.shape[0] != d.M:
+        raise ValueError("operand shapes do not form a chain")
+    return d
+
+
+def dep_gemm_chain(X, W1t, H, W2t, Y, policy: SyncPolicy, mode: int = MODE_FINE, mid: int = MID_GELU,
+                   tile: int = TILE_AUTO, stream_producer=None, stream_consumer=None, T=None,
+                   batch: int = 0, seq: int = 0, heads: int = 0, head_dim: int = 0) -> None:
+    """Enqueue Y = mid(X W1) W2 with W1t = W1^T [N1 x K1] and W2t = W2^T [N2 x K2] (row-major)."""
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T, batch, seq, heads, head_dim)
+    _check(_lib().dep_gemm_chain(ctypes.byref(d), policy.handle, mode, _stream_handle(stream_producer),
+                                 _stream_handle(stream_consumer)), "dep_gemm_chain")
+
+
+def gemm_chain_plan(X, W1t, H, W2t, Y, policy: Optional[SyncPolicy], mid: int = MID_GELU, tile: int = TILE_AUTO,
+                    n_cu: int = 0, **attn) -> PlanInfo:
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, tile, **attn)
+    info = PlanInfo()
+    _check(_lib().depsync_gemm_chain_plan(ctypes.byref(d), policy.handle if policy else None, n_cu,
+                                          ctypes.byref(info)), "depsync_gemm_chain_plan")
+    return info
+
+
+def _conv_desc(x, w1, mid, w2, out, tile) -> ConvChainDesc:
+    for t, name in ((x, "x"), (w1, "w1"), (mid, "mid"), (w2, "w2"), (out, "out")):
+        if not t.is_cuda or not t.is_contiguous() or t.dim() != 4:
+            raise ValueError(f"{name} must be a contiguous 4-D device tensor")
+        if t.dtype != x.dtype:
+            raise TypeError("all tensors of a chain must share one element type")
+    d = ConvChainDesc()
+    d.B, d.H, d.W, d.C = x.shape
+    d.K1, d.K2 = w1.shape[0], w2.shape[0]
+    if (tuple(w1.shape) != (d.K1, 3, 3, d.C) or tuple(w2.shape) != (d.K2, 3, 3, d.K1)
+            or tuple(mid.shape) != (d.B, d.H, d.W, d.K1) or tuple(out.shape) != (d.B, d.H, d.W, d.K2)):
+        raise ValueError("operand shapes do not form a conv chain")
+    d.dtype = _dtype_code(x)
+    d.inp, d.w1, d.mid, d.w2, d.out = x.data_ptr(), w1.data_ptr(), mid.data_ptr(), w2.data_ptr(), out.data_ptr()
+    d.tile_prod = d.tile_cons = tile
+    return d
+
+
+def dep_conv_chain(x, w1, mid, w2, out, policy: SyncPolicy, mode: int = MODE_FINE, tile: int = TILE_AUTO,
+                   stream_producer=None, stream_consumer=None) -> None:
+    """Enqueue out = conv3x3(relu(conv3x3(x, w1)), w2); NHWC activations, [K,3,3,C] weights."""
+    d = _conv_desc(x, w1, mid, w2, out, tile)
+    _check(_lib().dep_conv_chain(ctypes.byref(d), policy.handle, mode, _stream_handle(stream_producer),
+                                 _stream_handle(stream_consumer)), "dep_conv_chain")
+
+
+def conv_chain_plan(x, w1, mid, w2, out, policy: Optional[SyncPolicy], tile: int = TILE_AUTO, n_cu: int = 0) -> PlanInfo:
+    d = _conv_desc(x, w1, mid, w2, out, tile)
+    info = PlanInfo()
+    _check(_lib().depsync_conv_chain_plan(ctypes.byref(d), policy.handle if policy else None, n_cu,
+                                          ctypes.byref(info)), "depsync_conv_chain_plan")
+    return info
+
+
+# ---- host mirrors -------------------------------------------------------------------------
+
+def row_major(tile_x, tile_y, grid_x, grid_y) -> int:
+    return _lib().depsync_row_major(tile_x, tile_y, grid_x, grid_y)
+
+
+def policy_sem(kind, tile_x, tile_y, grid_x, grid_y, stride=0) -> int:
+    return _lib().depsync_policy_sem(kind, tile_x, tile_y, grid_x, grid_y, stride)
+
+
+def policy_value(kind, grid_x, grid_y, stride=0) -> int:
+    return _lib().depsync_policy_value(kind, grid_x, grid_y, stride)
+
+
+def wave_model(n_tiles, occupancy, n_cu):
+    w, u = ctypes.c_int(), ctypes.c_double()
+    _check(_lib().depsync_wave_model(n_tiles, occupancy, n_cu, ctypes.byref(w), ctypes.byref(u)), "depsync_wave_model")
+    return w.value, u.value
+
+
+def sync_count(kind, prod_grid, cons_grid, prod_rows_per_cons_row=1) -> int:
+    return _lib().depsync_sync_count(kind, prod_grid[0], prod_grid[1], cons_grid[0], cons_grid[1],
+                                     prod_rows_per_cons_row)
+
+
+def simulate_chain(slots, prod_grid, d1, cons_grid, d2, halo=0, stream_sync=False) -> float:
+    return _lib().depsync_simulate_chain(slots, prod_grid[0], prod_grid[1], d1, cons_grid[0], cons_grid[1], d2,
+                                         halo, int(stream_sync))
+
+
+def tile_shape(tile):
+    r, c = ctypes.c_int(), ctypes.c_int()
+    _check(_lib().depsync_tile_shape(tile, ctypes.byref(r), ctypes.byref(c)), "depsync_tile_shape")
+    return r.value, c.value
+
+
+def device_info():
+    n, k = ctypes.c_int(), ctypes.c_int()
+    _check(_lib().depsync_device_info(ctypes.byref(n), ctypes.byref(k)), "depsync_device_info")
+    return n.value, k.value

@@ -1,0 +1,575 @@
+// C-ABI layer: policy objects, chain planning, workspace/epoch management and the two-stream
+// launch (Sections III-A and III-D of the paper; declarations in include/depsync.h).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/depsync.h"
+#include "chain_args.h"
+#include "host_model.h"
+#include "launch.h"
+
+using namespace depsync;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+// Workspace layout in 32-bit words.
+constexpr uint32_t WS_TICKET = 0;
+constexpr uint32_t WS_STATUS = 16;       // StatusBlock, 8 words
+constexpr uint32_t WS_ZERO_PAGE = 64;    // 64 words = 256 zero bytes (never written after init)
+constexpr uint32_t WS_SEMS = 128;
+constexpr uint32_t WS_MAX_SEMS = 1u << 16;
+constexpr uint32_t WS_WORDS = WS_SEMS + WS_MAX_SEMS;
+
+int hip_fail(hipError_t e) {
+    g_last_hip_error = (int)e;
+    return DEPSYNC_EHIP;
+}
+#define HIP_TRY(expr)                                  \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) return hip_fail(e__);   \
+    } while (0)
+
+}  // namespace
+
+struct sync_policy {
+    int kind;
+    depsync_policy_params params;
+    int device;
+    uint32_t* ws;
+    hipStream_t own_stream;
+    hipEvent_t ev_fork, ev_join;
+    // epoch state: semaphores and the dispatch counter only ever grow between resets
+    uint64_t geom_sig;
+    uint32_t epoch;
+    uint32_t launches;
+    bool need_reset;
+};
+
+namespace {
+
+struct Plan {
+    int tile[3];
+    int n_stages;
+    uint32_t grid_x[3], grid_y[3], n_tiles[3];
+    uint32_t dep_kind[3];      // dependency of stage s on stage s-1
+    uint32_t sem_off[3];       // offset of that dependency's semaphores inside the sem area
+    uint32_t sem_count[3];
+    uint32_t sem_value[3];
+    uint32_t stride[3];
+    uint32_t n_sems;
+    int slots;
+    double flops, bytes;
+    uint32_t amode;
+    int dtype;
+};
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+uint32_t cdiv(uint32_t a, uint32_t b) { return (a + b - 1) / b; }
+
+int device_cus(int n_cu) {
+    if (n_cu > 0) return n_cu;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return -1;
+    return cus;
+}
+
+// Relative cost per flop of the macro-tile shapes (larger tiles reuse operands more).
+double tile_cost_factor(int tile) {
+    switch (tile) {
+        case DEPSYNC_TILE_256x256: return 1.00;
+        case DEPSYNC_TILE_256x128: return 1.10;
+        case DEPSYNC_TILE_128x256: return 1.10;
+        case DEPSYNC_TILE_128x128: return 1.35;
+        case DEPSYNC_TILE_64x128: return 1.9;
+        default: return 2.8;
+    }
+}
+
+// Pick one macro-tile for both stages by simulating the fine-grained schedule of the chain
+// on `slots` workgroup slots for every candidate shape (host_model.h).
+int choose_tile(uint32_t M, uint32_t n_out1, uint32_t K1, uint32_t N2, uint32_t K2, bool gate_up,
+                int n_cu, int rows_halo_tiles) {
+    int best = 0;
+    double best_t = 0;
+    for (int t = 1; t < DEPSYNC_TILE__COUNT; ++t) {
+        const TileShape* ts = tile_shape(t);
+        if (gate_up && ts->wave_cols < 64) continue;
+        const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
+        const uint32_t gy = cdiv(M, ts->rows);
+        const uint32_t gx1 = cdiv(n_out1, tn1), gx2 = cdiv(N2, ts->cols);
+        const double f = tile_cost_factor(t);
+        // `occupancy` workgroups share a CU's matrix units, so each runs at 1/occupancy of its rate
+        const double d1 = f * (double)ts->rows * ts->cols * K1 * ts->occupancy;
+        const double d2 = f * (double)ts->rows * ts->cols * K2 * ts->occupancy;
+        const double tm = simulate_chain(n_cu * ts->occupancy, gx1, gy, d1, gx2, gy, d2, rows_halo_tiles,
+                                         /*stream_sync=*/false);
+        if (best == 0 || tm < best_t) { best = t; best_t = tm; }
+    }
+    return best;
+}
+
+int policy_dep_kind_gemm(int kind) {
+    switch (kind) {
+        case DEPSYNC_ROWSYNC: return DEP_ROW;
+        case DEPSYNC_TILESYNC: return DEP_TILE;
+        default: return DEP_STRIDED;
+    }
+}
+int policy_dep_kind_conv(int kind) {
+    switch (kind) {
+        case DEPSYNC_ROWSYNC: return DEP_CONV_ROW;
+        case DEPSYNC_TILESYNC: return DEP_CONV_TILE;
+        default: return DEP_CONV_TAPROW;
+    }
+}
+
+int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu, Plan& p) {
+    if (!d) return DEPSYNC_EINVAL;
+    if (d->M <= 0 || d->K1 <= 0 || d->N1 <= 0 || d->N2 <= 0) return DEPSYNC_EINVAL;
+    if (d->dtype != DEPSYNC_BF16 && d->dtype != DEPSYNC_FP16) return DEPSYNC_EINVAL;
+    if (d->mid < DEPSYNC_MID_NONE || d->mid > DEPSYNC_MID_CAUSAL_ATTN) return DEPSYNC_EINVAL;
+    if (d->mid == DEPSYNC_MID_CAUSAL_ATTN) return DEPSYNC_ENOTIMPL;
+    if (!d->X || !d->W1t || !d->H || !d->W2t || !d->Y) return DEPSYNC_EINVAL;
+    if (!aligned16(d->X) || !aligned16(d->W1t) || !aligned16(d->H) || !aligned16(d->W2t) || !aligned16(d->Y))
+        return DEPSYNC_EINVAL;
+    const bool gate_up = d->mid == DEPSYNC_MID_SWIGLU;
+    const uint32_t K2 = (uint32_t)d->N1;
+    if (d->K1 % 64 || K2 % 64) return DEPSYNC_EINVAL;
+    if (d->ldx < d->K1 || d->ldw1 < d->K1 || d->ldh < d->N1 || d->ldw2 < (int64_t)K2 || d->ldy < d->N2)
+        return DEPSYNC_EINVAL;
+    if (d->ldx % 8 || d->ldw1 % 8 || d->ldh % 8 || d->ldw2 % 8 || d->ldy % 8) return DEPSYNC_EINVAL;
+    const uint64_t lim = 1ull << 32;
+    const uint64_t w1_rows = gate_up ? 2ull * d->N1 : (uint64_t)d->N1;
+    if ((uint64_t)d->M * d->ldx * 2 >= lim || w1_rows * d->ldw1 * 2 >= lim || (uint64_t)d->M * d->ldh * 2 >= lim ||
+        (uint64_t)d->N2 * d->ldw2 * 2 >= lim || (uint64_t)d->M * d->ldy * 2 >= lim)
+        return DEPSYNC_EINVAL;
+    if (d->tile_prod < 0 || d->tile_prod >= DEPSYNC_TILE__COUNT || d->tile_cons < 0 ||
+        d->tile_cons >= DEPSYNC_TILE__COUNT)
+        return DEPSYNC_EINVAL;
+    if (d->tile_prod && d->tile_cons && d->tile_prod != d->tile_cons) return DEPSYNC_ENOTIMPL;
+
+    const int cus = device_cus(n_cu);
+    if (cus <= 0) return DEPSYNC_EHIP;
+    int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
+    if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
+    const TileShape* ts = tile_shape(tile);
+    if (!ts) return DEPSYNC_EINVAL;
+    if (gate_up && ts->wave_cols < 64) return DEPSYNC_EINVAL;
+
+    std::memset(&p, 0, sizeof(p));
+    p.n_stages = 2;
+    p.amode = A_DENSE;
+    p.dtype = d->dtype;
+    p.tile[0] = p.tile[1] = tile;
+    const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
+    p.grid_y[0] = p.grid_y[1] = cdiv(d->M, ts->rows);
+    p.grid_x[0] = cdiv(d->N1, tn1);
+    p.grid_x[1] = cdiv(d->N2, ts->cols);
+    for (int s = 0; s < 2; ++s) p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
+
+    const int kind = pol ? pol->kind : DEPSYNC_ROWSYNC;
+    p.dep_kind[1] = policy_dep_kind_gemm(kind);
+    p.sem_off[1] = 0;
+    if (p.dep_kind[1] == DEP_ROW) {
+        p.sem_count[1] = p.grid_y[0];
+        p.sem_value[1] = p.grid_x[0];
+    } else if (p.dep_kind[1] == DEP_TILE) {
+        p.sem_count[1] = p.n_tiles[0];
+        p.sem_value[1] = 1;
+    } else {
+        uint32_t stride = pol ? pol->params.stride : 0;
+        if (stride == 0) {
+            const uint32_t count = (pol && pol->params.count) ? pol->params.count : 3;
+            if (p.grid_x[0] % count) return DEPSYNC_EINVAL;
+            stride = p.grid_x[0] / count;
+        }
+        if (stride == 0 || p.grid_x[0] % stride) return DEPSYNC_EINVAL;
+        p.stride[1] = stride;
+        p.sem_count[1] = p.grid_y[0] * stride;
+        p.sem_value[1] = p.grid_x[0] / stride;
+    }
+    p.n_sems = p.sem_count[1];
+    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
+    p.slots = cus * ts->occupancy;
+    const double M = d->M, w1c = gate_up ? 2.0 * d->N1 : d->N1;
+    p.flops = 2.0 * M * w1c * d->K1 + 2.0 * M * d->N2 * K2;
+    p.bytes = 2.0 * (M * d->K1 + w1c * d->K1 + 2.0 * M * d->N1 + (double)d->N2 * K2 + M * d->N2);
+    return DEPSYNC_OK;
+}
+
+int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu, Plan& p) {
+    if (!d) return DEPSYNC_EINVAL;
+    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K1 <= 0 || d->K2 <= 0) return DEPSYNC_EINVAL;
+    if (d->dtype != DEPSYNC_BF16 && d->dtype != DEPSYNC_FP16) return DEPSYNC_EINVAL;
+    if (!d->in || !d->w1 || !d->mid || !d->w2 || !d->out) return DEPSYNC_EINVAL;
+    if (!aligned16(d->in) || !aligned16(d->w1) || !aligned16(d->mid) || !aligned16(d->w2) || !aligned16(d->out))
+        return DEPSYNC_EINVAL;
+    if (d->C % 64 || d->K1 % 64 || d->K2 % 8) return DEPSYNC_EINVAL;
+    if (d->H >= 32768 || d->W >= 32768) return DEPSYNC_EINVAL;
+    const uint64_t Mpix = (uint64_t)d->B * d->H * d->W;
+    const uint64_t lim = 1ull << 32;
+    const uint64_t cmax = (uint64_t)std::max(std::max(d->C, d->K1), d->K2);
+    if (Mpix * cmax * 2 >= lim || 9ull * d->C * d->K1 * 2 >= lim || 9ull * d->K1 * d->K2 * 2 >= lim)
+        return DEPSYNC_EINVAL;
+    if (d->tile_prod < 0 || d->tile_prod >= DEPSYNC_TILE__COUNT || d->tile_cons < 0 ||
+        d->tile_cons >= DEPSYNC_TILE__COUNT)
+        return DEPSYNC_EINVAL;
+    if (d->tile_prod && d->tile_cons && d->tile_prod != d->tile_cons) return DEPSYNC_ENOTIMPL;
+    const int cus = device_cus(n_cu);
+    if (cus <= 0) return DEPSYNC_EHIP;
+    const uint32_t M = (uint32_t)Mpix;
+    int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
+    if (!tile) {
+        // halo: a consumer row tile reads W+1 rows beyond each end
+        tile = choose_tile(M, d->K1, 9 * d->C, d->K2, 9 * d->K1, false, cus, 1);
+    }
+    const TileShape* ts = tile_shape(tile);
+    if (!ts) return DEPSYNC_EINVAL;
+
+    std::memset(&p, 0, sizeof(p));
+    p.n_stages = 2;
+    p.amode = A_CONV3X3;
+    p.dtype = d->dtype;
+    p.tile[0] = p.tile[1] = tile;
+    p.grid_y[0] = p.grid_y[1] = cdiv(M, ts->rows);
+    p.grid_x[0] = cdiv(d->K1, ts->cols);
+    p.grid_x[1] = cdiv(d->K2, ts->cols);
+    for (int s = 0; s < 2; ++s) p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
+    const int kind = pol ? pol->kind : DEPSYNC_STRIDEDSYNC;
+    p.dep_kind[1] = policy_dep_kind_conv(kind);
+    if (p.dep_kind[1] == DEP_CONV_TILE) {
+        if (ts->cols % 64) return DEPSYNC_EINVAL;
+        p.sem_count[1] = p.n_tiles[0];
+        p.sem_value[1] = 1;
+    } else {
+        p.sem_count[1] = p.grid_y[0];
+        p.sem_value[1] = p.grid_x[0];
+    }
+    p.n_sems = p.sem_count[1];
+    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
+    p.slots = cus * ts->occupancy;
+    const double Md = (double)M;
+    p.flops = 2.0 * Md * d->K1 * 9.0 * d->C + 2.0 * Md * d->K2 * 9.0 * d->K1;
+    p.bytes = 2.0 * (Md * d->C + 9.0 * d->C * d->K1 + 2.0 * Md * d->K1 + 9.0 * d->K1 * d->K2 + Md * d->K2);
+    return DEPSYNC_OK;
+}
+
+void fill_plan_info(const Plan& p, depsync_plan_info* o) {
+    std::memset(o, 0, sizeof(*o));
+    o->tile_prod = p.tile[0];
+    o->tile_cons = p.tile[p.n_stages - 1];
+    o->tile_mid = p.n_stages == 3 ? p.tile[1] : 0;
+    o->prod_grid_x = p.grid_x[0]; o->prod_grid_y = p.grid_y[0];
+    o->cons_grid_x = p.grid_x[p.n_stages - 1]; o->cons_grid_y = p.grid_y[p.n_stages - 1];
+    o->n_prod = p.n_tiles[0];
+    o->n_cons = p.n_tiles[p.n_stages - 1];
+    if (p.n_stages == 3) { o->mid_grid_x = p.grid_x[1]; o->mid_grid_y = p.grid_y[1]; o->n_mid = p.n_tiles[1]; }
+    o->n_sems = p.n_sems;
+    o->slots = p.slots;
+    uint32_t total = 0;
+    int ws = 0;
+    for (int s = 0; s < p.n_stages; ++s) { ws += cdiv(p.n_tiles[s], p.slots); total += p.n_tiles[s]; }
+    o->waves_streamsync = ws;
+    o->waves_fine = cdiv(total, p.slots);
+    o->flops = p.flops;
+    o->bytes = p.bytes;
+}
+
+uint64_t geom_signature(const Plan& p) {
+    uint64_t h = 1469598103934665603ull;
+    auto mix = [&](uint64_t v) { h = (h ^ v) * 1099511628211ull; };
+    mix(p.n_stages);
+    for (int s = 0; s < p.n_stages; ++s) { mix(p.n_tiles[s]); mix(p.sem_count[s]); mix(p.sem_value[s]); mix(p.dep_kind[s]); }
+    return h;
+}
+
+// Make semaphores/counter consistent for a launch with geometry `p`; returns the epoch.
+int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t* epoch_out) {
+    uint32_t total = 0, vmax = 1;
+    for (int s = 0; s < p.n_stages; ++s) { total += p.n_tiles[s]; vmax = std::max(vmax, p.sem_value[s]); }
+    const uint64_t sig = geom_signature(p);
+    const uint64_t next = (uint64_t)(pol->epoch + 2) * std::max(total, vmax);
+    if (pol->need_reset || sig != pol->geom_sig || next >= (1ull << 31)) {
+        // zero the dispatch counter and every semaphore the previous geometry may have touched
+        hipError_t e = launch_fill_u32(pol->ws + WS_TICKET, 0u, 1, stream);
+        if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_SEMS, 0u, WS_MAX_SEMS, stream);
+        if (e != hipSuccess) return hip_fail(e);
+        pol->epoch = 0;
+        pol->geom_sig = sig;
+        pol->need_reset = false;
+    }
+    *epoch_out = pol->epoch;
+    return DEPSYNC_OK;
+}
+
+void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) {
+    a.n_stages = p.n_stages;
+    uint32_t t = 0;
+    for (int s = 0; s < 4; ++s) {
+        a.first_ticket[s] = t;
+        if (s < p.n_stages) t += p.n_tiles[s];
+    }
+    a.ticket = pol->ws + WS_TICKET;
+    a.ticket_base = epoch * t;
+    a.block_offset = 0;
+    a.flags = pol->params.flags;
+    a.spin_limit = pol->params.spin_limit;
+    a.delay_tile = pol->params.delay_tile;
+    a.delay_iters = pol->params.delay_iters;
+    a.status = reinterpret_cast<StatusBlock*>(pol->ws + WS_STATUS);
+    for (int s = 0; s < p.n_stages; ++s) {
+        StageDesc& st = a.st[s];
+        st.grid_x = p.grid_x[s];
+        st.grid_y = p.grid_y[s];
+        st.zero_page = pol->ws + WS_ZERO_PAGE;
+        st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
+        if (s > 0) {
+            const TileShape* pts = tile_shape(p.tile[s - 1]);
+            st.sems = pol->ws + WS_SEMS + p.sem_off[s];
+            st.sem_value = p.sem_value[s];
+            st.sem_target_base = epoch * p.sem_value[s];
+            st.prod_tm = pts->rows;
+            st.prod_tn = (a.st[s - 1].bmode == B_GATE_UP) ? pts->cols / 2 : pts->cols;
+            st.prod_grid_x = p.grid_x[s - 1];
+            st.prod_grid_y = p.grid_y[s - 1];
+            st.stride = p.stride[s];
+        }
+        if (s + 1 < p.n_stages) {
+            st.post_kind = p.dep_kind[s + 1];
+            st.post_sems = pol->ws + WS_SEMS + p.sem_off[s + 1];
+            st.post_stride = p.stride[s + 1];
+        } else {
+            st.post_kind = DEP_NONE;
+        }
+    }
+}
+
+int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mode, void* sp_, void* sc_) {
+    hipStream_t sp = static_cast<hipStream_t>(sp_);
+    hipStream_t sc = sc_ ? static_cast<hipStream_t>(sc_) : pol->own_stream;
+    const bool sync = mode != DEPSYNC_MODE_PLAIN;
+    uint32_t total = 0;
+    for (int s = 0; s < p.n_stages; ++s) total += p.n_tiles[s];
+    if (sync && (a.flags & DEPSYNC_FLAG_HW_ORDER) && mode == DEPSYNC_MODE_FINE && total > (uint32_t)p.slots)
+        return DEPSYNC_EINVAL;
+
+    if (mode == DEPSYNC_MODE_FINE) {
+        HIP_TRY(hipEventRecord(pol->ev_fork, sp));
+        HIP_TRY(hipStreamWaitEvent(sc, pol->ev_fork, 0));
+    }
+    uint32_t off = 0;
+    for (int s = 0; s < p.n_stages; ++s) {
+        // producer on the caller's stream; later stages on the second stream in FINE mode
+        hipStream_t st = (mode == DEPSYNC_MODE_FINE && s > 0) ? sc : sp;
+        a.block_offset = off;
+        HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, p.n_tiles[s], st, a));
+        off += p.n_tiles[s];
+    }
+    if (mode == DEPSYNC_MODE_FINE) {
+        HIP_TRY(hipEventRecord(pol->ev_join, sc));
+        HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join, 0));
+    }
+    if (sync) {
+        pol->epoch += 1;
+    }
+    pol->launches += 1;
+    return DEPSYNC_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* params, sync_policy_t** out) {
+    if (!out) return DEPSYNC_EINVAL;
+    *out = nullptr;
+    if (kind != DEPSYNC_ROWSYNC && kind != DEPSYNC_TILESYNC && kind != DEPSYNC_STRIDEDSYNC) return DEPSYNC_EINVAL;
+    sync_policy* p = new (std::nothrow) sync_policy();
+    if (!p) return DEPSYNC_ENOMEM;
+    p->kind = kind;
+    if (params) p->params = *params; else std::memset(&p->params, 0, sizeof(p->params));
+    hipError_t e = hipGetDevice(&p->device);
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->ws), WS_WORDS * sizeof(uint32_t));
+    if (e != hipSuccess) { delete p; return e == hipErrorOutOfMemory ? DEPSYNC_ENOMEM : hip_fail(e); }
+    e = hipMemset(p->ws, 0, WS_WORDS * sizeof(uint32_t));
+    if (e == hipSuccess) {
+        StatusBlock sb{};
+        sb.first_timeout = -1;
+        e = hipMemcpy(p->ws + WS_STATUS, &sb, sizeof(sb), hipMemcpyHostToDevice);
+    }
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->own_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming);
+    if (e != hipSuccess) { (void)hipFree(p->ws); delete p; return hip_fail(e); }
+    p->epoch = 0;
+    p->geom_sig = 0;
+    p->launches = 0;
+    p->need_reset = false;
+    *out = p;
+    return DEPSYNC_OK;
+}
+
+int sync_policy_destroy(sync_policy_t* pol) {
+    if (!pol) return DEPSYNC_EINVAL;
+    (void)hipDeviceSynchronize();
+    (void)hipEventDestroy(pol->ev_fork);
+    (void)hipEventDestroy(pol->ev_join);
+    (void)hipStreamDestroy(pol->own_stream);
+    (void)hipFree(pol->ws);
+    delete pol;
+    return DEPSYNC_OK;
+}
+
+int dep_chain_reset(sync_policy_t* pol, void* stream) {
+    if (!pol) return DEPSYNC_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, 1, st));
+    HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, st));
+    HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS + 1, 0xffffffffu, 1, st));   // first_timeout = -1
+    HIP_TRY(launch_fill_u32(pol->ws + WS_SEMS, 0u, WS_MAX_SEMS, st));
+    pol->epoch = 0;
+    pol->launches = 0;
+    pol->need_reset = false;
+    return DEPSYNC_OK;
+}
+
+int depsync_last_status(sync_policy_t* pol, depsync_status* out) {
+    if (!pol || !out) return DEPSYNC_EINVAL;
+    HIP_TRY(hipDeviceSynchronize());
+    StatusBlock sb;
+    HIP_TRY(hipMemcpy(&sb, pol->ws + WS_STATUS, sizeof(sb), hipMemcpyDeviceToHost));
+    out->timed_out = sb.timed_out;
+    out->first_timeout = sb.first_timeout;
+    out->posts = sb.posts;
+    out->waits = sb.waits;
+    out->polling_waits = sb.polling_waits;
+    out->launches = pol->launches;
+    if (sb.timed_out > 0) { pol->need_reset = true; return DEPSYNC_ETIMEOUT; }
+    return DEPSYNC_OK;
+}
+
+int depsync_gemm_chain_plan(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int n_cu,
+                            depsync_plan_info* out) {
+    if (!out) return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_gemm(d, pol, n_cu, p);
+    if (rc != DEPSYNC_OK) return rc;
+    fill_plan_info(p, out);
+    return DEPSYNC_OK;
+}
+
+int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int n_cu,
+                            depsync_plan_info* out) {
+    if (!out) return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_conv(d, pol, n_cu, p);
+    if (rc != DEPSYNC_OK) return rc;
+    fill_plan_info(p, out);
+    return DEPSYNC_OK;
+}
+
+int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
+                   void* stream_consumer) {
+    if (!pol) return DEPSYNC_EINVAL;
+    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN)
+        return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_gemm(d, pol, 0, p);
+    if (rc != DEPSYNC_OK) return rc;
+    uint32_t epoch = 0;
+    if (mode != DEPSYNC_MODE_PLAIN) {
+        rc = prepare_epoch(pol, p, static_cast<hipStream_t>(stream_producer), &epoch);
+        if (rc != DEPSYNC_OK) return rc;
+    }
+    ChainArgs a;
+    std::memset(&a, 0, sizeof(a));
+    const bool gate_up = d->mid == DEPSYNC_MID_SWIGLU;
+    StageDesc& s0 = a.st[0];
+    s0.A = d->X; s0.B = d->W1t; s0.C = d->H;
+    s0.M = d->M; s0.N = d->N1; s0.K = d->K1;
+    s0.lda = (uint32_t)d->ldx; s0.ldb = (uint32_t)d->ldw1; s0.ldc = (uint32_t)d->ldh;
+    s0.op = OP_GEMM; s0.amode = A_DENSE; s0.bmode = gate_up ? B_GATE_UP : B_DENSE;
+    s0.act = d->mid == DEPSYNC_MID_GELU ? ACT_GELU : d->mid == DEPSYNC_MID_RELU ? ACT_RELU
+             : gate_up ? ACT_SWIGLU : ACT_NONE;
+    StageDesc& s1 = a.st[1];
+    s1.A = d->H; s1.B = d->W2t; s1.C = d->Y;
+    s1.M = d->M; s1.N = d->N2; s1.K = d->N1;
+    s1.lda = (uint32_t)d->ldh; s1.ldb = (uint32_t)d->ldw2; s1.ldc = (uint32_t)d->ldy;
+    s1.op = OP_GEMM; s1.amode = A_DENSE; s1.bmode = B_DENSE; s1.act = ACT_NONE;
+    fill_common(a, pol, p, epoch);
+    return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
+}
+
+int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
+                   void* stream_consumer) {
+    if (!pol) return DEPSYNC_EINVAL;
+    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN)
+        return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_conv(d, pol, 0, p);
+    if (rc != DEPSYNC_OK) return rc;
+    uint32_t epoch = 0;
+    if (mode != DEPSYNC_MODE_PLAIN) {
+        rc = prepare_epoch(pol, p, static_cast<hipStream_t>(stream_producer), &epoch);
+        if (rc != DEPSYNC_OK) return rc;
+    }
+    ChainArgs a;
+    std::memset(&a, 0, sizeof(a));
+    const uint32_t M = (uint32_t)d->B * d->H * d->W;
+    StageDesc& s0 = a.st[0];
+    s0.A = d->in; s0.B = d->w1; s0.C = d->mid;
+    s0.M = M; s0.N = d->K1; s0.K = 9u * d->C;
+    s0.lda = d->C; s0.ldb = 9u * d->C; s0.ldc = d->K1;
+    s0.op = OP_GEMM; s0.amode = A_CONV3X3; s0.bmode = B_DENSE; s0.act = ACT_RELU;
+    s0.H = d->H; s0.W = d->W; s0.Cin = d->C;
+    StageDesc& s1 = a.st[1];
+    s1.A = d->mid; s1.B = d->w2; s1.C = d->out;
+    s1.M = M; s1.N = d->K2; s1.K = 9u * d->K1;
+    s1.lda = d->K1; s1.ldb = 9u * d->K1; s1.ldc = d->K2;
+    s1.op = OP_GEMM; s1.amode = A_CONV3X3; s1.bmode = B_DENSE; s1.act = ACT_NONE;
+    s1.H = d->H; s1.W = d->W; s1.Cin = d->K1;
+    fill_common(a, pol, p, epoch);
+    return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
+}
+
+const char* depsync_strerror(int status) {
+    switch (status) {
+        case DEPSYNC_OK: return "ok";
+        case DEPSYNC_EINVAL: return "invalid argument (null pointer, shape, alignment or enum)";
+        case DEPSYNC_ENOMEM: return "out of memory or too many semaphores";
+        case DEPSYNC_EHIP: return "a HIP call failed (see depsync_last_hip_error)";
+        case DEPSYNC_ETIMEOUT: return "a bounded semaphore wait expired";
+        case DEPSYNC_ENOTIMPL: return "not implemented in this build";
+        default: return "unknown status";
+    }
+}
+
+int depsync_last_hip_error(void) { return g_last_hip_error; }
+
+int depsync_tile_shape(int tile, int* rows, int* cols) {
+    const TileShape* ts = tile_shape(tile);
+    if (!ts || !rows || !cols) return DEPSYNC_EINVAL;
+    *rows = ts->rows;
+    *cols = ts->cols;
+    return DEPSYNC_OK;
+}
+
+int depsync_device_info(int* n_cu, int* clock_khz) {
+    if (!n_cu || !clock_khz) return DEPSYNC_EINVAL;
+    int dev = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(n_cu, hipDeviceAttributeMultiprocessorCount, dev));
+    HIP_TRY(hipDeviceGetAttribute(clock_khz, hipDeviceAttributeClockRate, dev));
+    return DEPSYNC_OK;
+}
+
+}  // extern "C"

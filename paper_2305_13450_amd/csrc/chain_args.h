@@ -1,0 +1,81 @@
+// Plain-data kernel arguments shared by the host launcher and the device code of the chain
+// kernels.  A chain has up to three stages (producer, optional middle stage, consumer); each
+// stage after the first has one dependency on the stage before it (Section III-A).
+#pragma once
+#include <stdint.h>
+
+namespace depsync {
+
+// How a stage addresses its A operand (rows of the implicit GeMM).
+enum AMode : uint32_t { A_DENSE = 0, A_CONV3X3 = 1 };
+// How a stage maps rows of its B-operand tile to rows of the weight array.
+enum BMode : uint32_t { B_DENSE = 0, B_GATE_UP = 1 };
+// Epilogue applied to the fp32 accumulators before rounding to 16 bits.
+enum Act : uint32_t { ACT_NONE = 0, ACT_GELU = 1, ACT_RELU = 2, ACT_SWIGLU = 3 };
+// What a stage computes.
+enum StageOp : uint32_t { OP_GEMM = 0, OP_ATTN = 1 };
+
+// Dependency of a stage on the previous stage's output (its A operand).
+enum DepKind : uint32_t {
+    DEP_NONE = 0,
+    DEP_ROW = 1,          // RowSync: wait once for every producer row tile this tile reads
+    DEP_TILE = 2,         // TileSync: wait per producer column tile as the K loop reaches it
+    DEP_STRIDED = 3,      // StridedSync on a GeMM: like TILE, semaphore shared at a stride
+    DEP_CONV_ROW = 4,     // conv, RowSync: all halo row tiles up front
+    DEP_CONV_TAPROW = 5,  // conv, StridedSync: per filter row r, the row tiles shifted by (r-1)*W
+    DEP_CONV_TILE = 6,    // conv, TileSync: per (filter row, producer channel tile)
+    DEP_ATTN_QKV = 7,     // attention stage on the QKV GeMM
+    DEP_ATTN_OUT = 8      // output GeMM on the attention stage
+};
+
+struct StageDesc {
+    const void* A;      // [M x K] rows of lda elements (conv: NHWC input)
+    const void* B;      // [N x K] rows of ldb elements (K contiguous)
+    void* C;            // [M x N] rows of ldc elements
+    uint32_t M, N, K;   // N = output columns (B_GATE_UP: B has 2N rows)
+    uint32_t lda, ldb, ldc;
+    uint32_t grid_x, grid_y;   // column tiles, row tiles
+    uint32_t op, amode, bmode, act;
+    // conv geometry (A_CONV3X3): image height, width, input channels
+    uint32_t H, W, Cin;
+    const void* zero_page;     // >= 256 zero bytes, source for padded taps
+    // attention (OP_ATTN): A = QKV, C = T
+    uint32_t batch, seq, heads, head_dim;
+    // dependency on the previous stage
+    uint32_t dep_kind;
+    uint32_t* sems;            // semaphores this stage WAITS on (posted by the previous stage)
+    uint32_t sem_target_base;  // semaphore value before this launch's posts
+    uint32_t sem_value;        // posts per semaphore per launch
+    uint32_t prod_tm;          // producer tile rows
+    uint32_t prod_tn;          // producer tile columns of ITS OUTPUT (= K range per tile here)
+    uint32_t prod_grid_x, prod_grid_y;
+    uint32_t stride;           // DEP_STRIDED: semaphores per producer row
+    // posting (this stage as a producer)
+    uint32_t post_kind;        // DEP_NONE if nobody waits on this stage, else the consumer's kind
+    uint32_t* post_sems;
+    uint32_t post_stride;
+};
+
+struct StatusBlock {
+    int32_t timed_out;
+    int32_t first_timeout;
+    uint32_t posts;
+    uint32_t waits;
+    uint32_t polling_waits;
+    uint32_t pad[3];
+};
+
+struct ChainArgs {
+    StageDesc st[3];
+    uint32_t n_stages;
+    uint32_t first_ticket[4];   // stage s owns tickets [first_ticket[s], first_ticket[s+1])
+    uint32_t* ticket;           // dispatch counter
+    uint32_t ticket_base;       // counter value before this chain's draws
+    uint32_t block_offset;      // HW order / PLAIN: ticket of this launch's block 0
+    uint32_t flags;             // DEPSYNC_FLAG_*
+    uint32_t spin_limit;
+    uint32_t delay_tile, delay_iters;
+    StatusBlock* status;
+};
+
+}  // namespace depsync

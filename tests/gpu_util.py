@@ -1,0 +1,54 @@
+"""Helpers shared by the GPU parity tests (the tests call the library through its C ABI via the
+thin binding; the oracle is only used to produce expected values)."""
+import numpy as np
+import torch
+
+import inputs
+import oracle
+import paper_2305_13450_amd as ds
+
+TOL_BF16 = 2e-2     # max-abs error normalised by the RMS of the oracle's output
+TOL_FP16 = 4e-3
+
+
+def rel_err(got: torch.Tensor, ref: np.ndarray) -> float:
+    g = got.detach().to("cpu").to(torch.float64).numpy()
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    return float(np.max(np.abs(g - ref))) / max(rms, 1e-30)
+
+
+def dev(t: torch.Tensor) -> torch.Tensor:
+    return t.to("cuda")
+
+
+def run_gemm_chain(X, W1, W2, policy, mode, mid=ds.MID_GELU, tile=ds.TILE_AUTO, poison=True, streams=None):
+    """X[M,K1], W1/W2 in mathematical [K,N] shape (host or device).  Returns (H, Y) device tensors."""
+    Xd = dev(X)
+    W1t = dev(W1).t().contiguous()
+    W2t = dev(W2).t().contiguous()
+    M = X.shape[0]
+    n1 = W1.shape[1] // 2 if mid == ds.MID_SWIGLU else W1.shape[1]
+    H = torch.empty((M, n1), dtype=X.dtype, device="cuda")
+    Y = torch.empty((M, W2.shape[1]), dtype=X.dtype, device="cuda")
+    if poison:
+        H.fill_(float("nan"))
+        Y.fill_(float("nan"))
+    sp, sc = streams if streams else (None, None)
+    torch.cuda.synchronize()
+    ds.dep_gemm_chain(Xd, W1t, H, W2t, Y, policy, mode=mode, mid=mid, tile=tile, stream_producer=sp, stream_consumer=sc)
+    torch.cuda.synchronize()
+    return H, Y
+
+
+def run_conv_chain(x, w1, w2, policy, mode, tile=ds.TILE_AUTO, poison=True):
+    xd, w1d, w2d = dev(x), dev(w1), dev(w2)
+    B, H, W, C = x.shape
+    mid = torch.empty((B, H, W, w1.shape[0]), dtype=x.dtype, device="cuda")
+    out = torch.empty((B, H, W, w2.shape[0]), dtype=x.dtype, device="cuda")
+    if poison:
+        mid.fill_(float("nan"))
+        out.fill_(float("nan"))
+    torch.cuda.synchronize()
+    ds.dep_conv_chain(xd, w1d, mid, w2d, out, policy, mode=mode, tile=tile)
+    torch.cuda.synchronize()
+    return mid, out

@@ -1,0 +1,196 @@
+"""GPU parity tests of dep_gemm_chain against the fp64 oracle, element by element, plus the
+bit-exactness of fine-grained synchronisation against the same kernels under stream sync."""
+import numpy as np
+import pytest
+import torch
+
+import inputs
+import oracle
+import paper_2305_13450_amd as ds
+from gpu_util import TOL_BF16, TOL_FP16, rel_err, run_gemm_chain
+
+pytestmark = pytest.mark.gpu
+
+ALL_TILES = [ds.TILE_256x256, ds.TILE_256x128, ds.TILE_128x256, ds.TILE_128x128, ds.TILE_64x128, ds.TILE_64x64]
+MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN]
+
+
+@pytest.fixture(scope="module")
+def cfg1():
+    t = inputs.mlp(**inputs.CFG1)
+    H, Y = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    return t, H, Y
+
+
+def test_cfg1_rowsync_matches_oracle_and_is_bit_exact(cfg1):
+    t, Href, Yref = cfg1
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    outs = {}
+    for mode in MODES:
+        print(f"cfg1 mode={mode}", flush=True)
+        H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode)
+        assert rel_err(H, Href) <= TOL_BF16
+        assert rel_err(Y, Yref) <= TOL_BF16
+        outs[mode] = (H, Y)
+    for mode in (ds.MODE_STREAMSYNC, ds.MODE_PLAIN):
+        assert torch.equal(outs[ds.MODE_FINE][0], outs[mode][0])
+        assert torch.equal(outs[ds.MODE_FINE][1], outs[mode][1])
+    pol.destroy()
+
+
+@pytest.mark.parametrize("tile", ALL_TILES)
+@pytest.mark.parametrize("kind", [ds.ROWSYNC, ds.TILESYNC])
+def test_every_tile_shape_ragged(tile, kind):
+    # several tiles in both directions and ragged tails in M and N for every macro-tile shape
+    M, K1, N1, N2 = 300, 192, 576, 328
+    print(f"ragged tile={tile} kind={kind}", flush=True)
+    t = inputs.mlp(M, K1, N1, N2, seed=3)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pol = ds.SyncPolicy(kind)
+    res = [run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode, tile=tile) for mode in MODES]
+    for H, Y in res:
+        assert rel_err(H, Href) <= TOL_BF16
+        assert rel_err(Y, Yref) <= TOL_BF16
+    for H, Y in res[1:]:
+        assert torch.equal(res[0][0], H) and torch.equal(res[0][1], Y)
+    pol.destroy()
+
+
+@pytest.mark.parametrize("mid,act", [(ds.MID_NONE, oracle.ACT_NONE), (ds.MID_RELU, oracle.ACT_RELU)])
+def test_other_pointwise_ops(mid, act):
+    t = inputs.mlp(130, 128, 256, 136, seed=5)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), act)
+    pol = ds.SyncPolicy(ds.TILESYNC)
+    H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, mid=mid, tile=ds.TILE_64x64)
+    assert rel_err(H, Href) <= TOL_BF16 and rel_err(Y, Yref) <= TOL_BF16
+    pol.destroy()
+
+
+def test_fp16_chain():
+    t = inputs.mlp(200, 256, 384, 264, seed=7, dtype=torch.float16)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    a = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_128x128)
+    b = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_STREAMSYNC, tile=ds.TILE_128x128)
+    assert rel_err(a[0], Href) <= TOL_FP16 and rel_err(a[1], Yref) <= TOL_FP16
+    assert torch.equal(a[1], b[1])
+    pol.destroy()
+
+
+@pytest.mark.parametrize("M", [1, 7, 64])
+def test_skinny_m(M):
+    t = inputs.mlp(M, 512, 1024, 512, seed=11)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pol = ds.SyncPolicy(ds.TILESYNC)
+    for mode in MODES:
+        H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode)
+        assert rel_err(H, Href) <= TOL_BF16 and rel_err(Y, Yref) <= TOL_BF16
+    pol.destroy()
+
+
+def test_swiglu_chain_matches_oracle():
+    # Nh = 192 is not a multiple of the 128 gate/up columns a 256-wide tile owns: ragged tail
+    M, K1, Nh, N2 = 150, 256, 192, 200
+    t = inputs.swiglu(M, K1, Nh, N2, seed=13)
+    Href, Yref = oracle.swiglu_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["Wgu"]), inputs.to_f64(t["W2"]))
+    for tile in (ds.TILE_256x256, ds.TILE_256x128, ds.TILE_128x256, ds.TILE_128x128, ds.TILE_64x128):
+        print(f"swiglu tile={tile}", flush=True)
+        pol = ds.SyncPolicy(ds.TILESYNC)
+        res = [run_gemm_chain(t["X"], t["Wgu"], t["W2"], pol, mode, mid=ds.MID_SWIGLU, tile=tile) for mode in MODES]
+        for H, Y in res:
+            assert rel_err(H, Href) <= TOL_BF16 and rel_err(Y, Yref) <= TOL_BF16
+        assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][1], res[2][1])
+        pol.destroy()
+
+
+def test_stridedsync_on_gemm_chain():
+    # 6 producer column tiles of 64; tiles x, x+2, x+4 share a semaphore (stride 2, count 3)
+    t = inputs.mlp(192, 128, 384, 128, seed=17)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC, count=3, flags=ds.FLAG_COUNT)
+    H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
+    assert rel_err(Y, Yref) <= TOL_BF16
+    st = pol.status()
+    assert st.posts == 6 * 3                   # every producer tile posts once
+    assert st.waits == (3 * 2) * 2             # 6 consumer tiles, 2 shared semaphores each
+    pol.destroy()
+
+
+def test_sync_counts_of_the_fig1_shaped_chain(golden):
+    # 3 row tiles x 2 column tiles per GeMM, as in Fig. 1: 12 waits under TileSync, 6 under RowSync
+    g = {k: int(v) for k, v in golden("fig1_example.txt")}
+    t = inputs.mlp(3 * 128, 128, 2 * 128, 2 * 128, seed=19)
+    _, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    for kind, key in ((ds.TILESYNC, "syncs_tilesync"), (ds.ROWSYNC, "syncs_rowsync")):
+        pol = ds.SyncPolicy(kind, flags=ds.FLAG_COUNT)
+        _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_128x128)
+        st = pol.status()
+        assert rel_err(Y, Yref) <= TOL_BF16
+        assert st.posts == 6 and st.waits == g[key]
+        pol.destroy()
+
+
+def test_repeated_launches_reuse_the_workspace_without_reset():
+    t = inputs.mlp(520, 256, 512, 384, seed=23)
+    _, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pol = ds.SyncPolicy(ds.TILESYNC)
+    first = None
+    for it in range(30):
+        _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_64x128)
+        if first is None:
+            first = Y.clone()
+            assert rel_err(Y, Yref) <= TOL_BF16
+        assert torch.equal(Y, first), it
+    # a different geometry on the same policy re-zeroes the workspace by itself
+    _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_128x128)
+    assert rel_err(Y, Yref) <= TOL_BF16
+    pol.destroy()
+
+
+def test_delayed_and_reversed_producers_do_not_change_the_result():
+    t = inputs.mlp(512, 256, 512, 256, seed=29)
+    _, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    base = ds.SyncPolicy(ds.TILESYNC)
+    _, Y0 = run_gemm_chain(t["X"], t["W1"], t["W2"], base, ds.MODE_STREAMSYNC, tile=ds.TILE_64x64)
+    assert rel_err(Y0, Yref) <= TOL_BF16
+    base.destroy()
+    for kind in (ds.TILESYNC, ds.ROWSYNC):
+        for kw in (dict(delay_tile=1, delay_iters=300), dict(delay_tile=37, delay_iters=300),
+                   dict(flags=ds.FLAG_REVERSE_ORDER), dict(flags=ds.FLAG_NO_REORDER)):
+            pol = ds.SyncPolicy(kind, **kw)
+            _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
+            assert torch.equal(Y, Y0), (kind, kw)
+            pol.destroy()
+
+
+def test_bounded_wait_reports_timeout_and_reset_recovers():
+    # The first producer tile's post is held back for a few milliseconds while consumers give up
+    # after 8 polls: every kernel still exits, and the status reports the expired wait.
+    t = inputs.mlp(128, 128, 128, 128, seed=31)
+    _, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pol = ds.SyncPolicy(ds.TILESYNC, spin_limit=8, delay_tile=1, delay_iters=2000)
+    run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
+    st = pol.status(raise_on_timeout=False)
+    assert st.timed_out > 0 and st.first_timeout >= 4        # tickets 0..3 are producer tiles
+    with pytest.raises(ds.DepsyncError):
+        pol.status()
+    pol.reset()
+    pol2 = ds.SyncPolicy(ds.TILESYNC)
+    _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol2, ds.MODE_FINE, tile=ds.TILE_64x64)
+    assert rel_err(Y, Yref) <= TOL_BF16
+    assert pol.status().timed_out == 0
+    pol.destroy(); pol2.destroy()
+
+
+def test_invalid_arguments_are_rejected_before_any_launch():
+    t = inputs.mlp(64, 128, 128, 128, seed=1)
+    X = t["X"].cuda(); W1t = t["W1"].t().contiguous().cuda(); W2t = t["W2"].t().contiguous().cuda()
+    H = torch.empty((64, 128), dtype=torch.bfloat16, device="cuda"); Y = torch.empty_like(H)
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    with pytest.raises(ds.DepsyncError) as e:
+        ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=7)
+    assert e.value.status == ds.EINVAL
+    with pytest.raises(ds.DepsyncError) as e:     # misaligned base pointer
+        ds.dep_gemm_chain(X.view(-1)[1:1 + 63 * 128].view(63, 128), W1t, H[:63], W2t, Y[:63], pol)
+    assert e.value.status == ds.EINVAL
+    pol.destroy()

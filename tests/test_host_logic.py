@@ -1,0 +1,135 @@
+"""CPU-only tests of the library's host logic: the shared object loads, exports what the header
+declares, and its host mirrors agree with the paper's formulas and the oracle's sync model."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2305_13450_amd as ds
+from oracle import sync_model as sm
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "depsync.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b([a-z_0-9]+)\s*\([^;{]*\)\s*;", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = ctypes.CDLL(ds.LIB_PATH)
+    names = _declared_functions()
+    assert {"sync_policy_create", "dep_gemm_chain", "dep_conv_chain", "dep_chain_reset"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert set(ds.EXPORTS) == set(names)
+
+
+def test_strerror_and_tile_shapes():
+    assert ds._lib().depsync_strerror(0) == b"ok"
+    assert b"invalid" in ds._lib().depsync_strerror(ds.EINVAL)
+    assert ds.tile_shape(ds.TILE_256x256) == (256, 256)
+    assert ds.tile_shape(ds.TILE_64x128) == (64, 128)
+    with pytest.raises(ds.DepsyncError):
+        ds.tile_shape(0)
+
+
+def test_policy_mirrors_match_oracle_model():
+    for grid in ((3, 2), (24, 8), (5, 7)):
+        for y in range(grid[1]):
+            for x in range(grid[0]):
+                assert ds.row_major(x, y, *grid) == sm.row_major((x, y), grid)
+                assert ds.policy_sem(ds.TILESYNC, x, y, *grid) == sm.tilesync_sem((x, y), grid)
+                assert ds.policy_sem(ds.ROWSYNC, x, y, *grid) == sm.rowsync_sem((x, y), grid)
+        assert ds.policy_value(ds.TILESYNC, *grid) == 1
+        assert ds.policy_value(ds.ROWSYNC, *grid) == grid[0]
+    grid, s = (12, 5), 4
+    for y in range(grid[1]):
+        for x in range(grid[0]):
+            assert ds.policy_sem(ds.STRIDEDSYNC, x, y, *grid, s) == sm.stridedsync_sem((x, y), grid, s)
+    assert ds.policy_value(ds.STRIDEDSYNC, *grid, s) == 3
+
+
+def test_wave_model_table1(golden):
+    for batch, gemm, gx, gy, gz, occ, n_sm, w, util in golden("table1_waves.txt"):
+        tbs = int(gx) * int(gy) * int(gz)
+        waves, u = ds.wave_model(tbs, int(occ), int(n_sm))
+        assert waves == -(-tbs // (int(occ) * int(n_sm)))
+        assert 100 * u == pytest.approx(float(util))
+
+
+def test_fig1_example_counts_and_schedule(golden):
+    g = {k: int(v) for k, v in golden("fig1_example.txt")}
+    grid = (g["col_tiles"], g["row_tiles"])
+    assert ds.sync_count(ds.TILESYNC, grid, grid) == g["syncs_tilesync"]
+    assert ds.sync_count(ds.ROWSYNC, grid, grid) == g["syncs_rowsync"]
+    assert ds.simulate_chain(g["n_sm"], grid, 1.0, grid, 1.0, stream_sync=True) == g["total_waves_stream_sync"]
+    assert ds.simulate_chain(g["n_sm"], grid, 1.0, grid, 1.0, stream_sync=False) == g["total_waves_fine_grained"]
+
+
+def test_schedule_model_matches_oracle_simulator():
+    for slots, pg, cg, d1, d2 in ((256, (24, 8), (48, 8), 2.0, 1.0), (7, (3, 5), (4, 5), 1.0, 1.5), (4, (2, 3), (2, 3), 1.0, 1.0)):
+        tiles = sm.gemm_chain_tiles(pg, cg, d1, d2)
+        for ss in (True, False):
+            assert ds.simulate_chain(slots, pg, d1, cg, d2, stream_sync=ss) == pytest.approx(sm.simulate(slots, tiles, ss))
+
+
+def _fake_gemm_desc(M, K1, N1, N2, mid=ds.MID_GELU, tile=0):
+    d = ds.GemmChainDesc()
+    d.M, d.K1, d.N1, d.N2, d.dtype, d.mid = M, K1, N1, N2, ds.BF16, mid
+    d.X = d.W1t = d.H = d.W2t = d.Y = 0x1000          # never dereferenced by the planner
+    d.ldx, d.ldw1, d.ldh, d.ldw2, d.ldy = K1, K1, N1, N1, N2
+    d.tile_prod = d.tile_cons = tile
+    return d
+
+
+def test_planner_grids_flops_and_validation():
+    d = _fake_gemm_desc(2048, 12288, 6144, 12288, tile=ds.TILE_256x256)
+    info = ds.PlanInfo()
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    assert (info.prod_grid_x, info.prod_grid_y, info.cons_grid_x, info.cons_grid_y) == (24, 8, 48, 8)
+    assert (info.n_prod, info.n_cons, info.slots) == (192, 384, 256)
+    assert (info.waves_streamsync, info.waves_fine) == (1 + 2, 3)
+    assert info.flops == pytest.approx(2 * 2048 * 12288 * 6144 * 2)
+    assert info.bytes == pytest.approx(2 * (2048 * 12288 + 2 * 12288 * 6144 + 2 * 2048 * 6144 + 2048 * 12288))
+    # gate/up fusion halves the producer's output tile width
+    d = _fake_gemm_desc(256, 8192, 2752, 8192, mid=ds.MID_SWIGLU, tile=ds.TILE_128x128)
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    assert (info.prod_grid_x, info.cons_grid_x) == (43, 64)
+    # rejections
+    bad = _fake_gemm_desc(256, 1000, 4096, 1024)
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(bad), None, 256, ctypes.byref(info)) == ds.EINVAL
+    bad = _fake_gemm_desc(256, 1024, 4096, 1024); bad.X = 0x1004
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(bad), None, 256, ctypes.byref(info)) == ds.EINVAL
+    bad = _fake_gemm_desc(256, 1024, 4096, 1024); bad.ldh = 4100
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(bad), None, 256, ctypes.byref(info)) == ds.EINVAL
+    bad = _fake_gemm_desc(0, 1024, 4096, 1024)
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(bad), None, 256, ctypes.byref(info)) == ds.EINVAL
+    assert ds._lib().depsync_gemm_chain_plan(None, None, 256, ctypes.byref(info)) == ds.EINVAL
+
+
+def test_planner_auto_tile_prefers_more_tiles_for_small_m():
+    info = ds.PlanInfo()
+    d = _fake_gemm_desc(2048, 12288, 6144, 12288)
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    big = info.tile_prod
+    d = _fake_gemm_desc(64, 12288, 6144, 12288)
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    r_big, c_big = ds.tile_shape(big)
+    r_small, c_small = ds.tile_shape(info.tile_prod)
+    assert r_small * c_small <= r_big * c_big and r_small <= 128
+
+
+def test_conv_planner():
+    d = ds.ConvChainDesc()
+    d.B, d.H, d.W, d.C, d.K1, d.K2, d.dtype = 4, 56, 56, 256, 256, 256, ds.BF16
+    d.inp = d.w1 = d.mid = d.w2 = d.out = 0x1000
+    d.tile_prod = d.tile_cons = ds.TILE_128x128
+    info = ds.PlanInfo()
+    assert ds._lib().depsync_conv_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    assert (info.prod_grid_x, info.prod_grid_y) == (2, 98)
+    assert info.flops == pytest.approx(2 * 2.0 * 4 * 56 * 56 * 256 * 9 * 256)
+    d.C = 96
+    assert ds._lib().depsync_conv_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.EINVAL
