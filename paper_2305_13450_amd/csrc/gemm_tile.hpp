@@ -54,8 +54,9 @@ template <> struct Mma<_Float16> {
 
 // Position swizzle of the 16-byte chunks of LDS row r.  Any 8 consecutive rows get 8 distinct
 // positions (32 banks), and any 16 consecutive rows get 16 distinct (position, row parity)
-// pairs (64 banks).
-__device__ __forceinline__ uint32_t swz(uint32_t r) { return (r ^ (r >> 3)) & 7u; }
+// pairs (64 banks).  The pattern repeats every 16 rows, so fragment blocks 32 rows apart share
+// one per-lane offset.
+__device__ __forceinline__ uint32_t swz(uint32_t r) { return (r & 7u) ^ ((r >> 3) & 1u); }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;

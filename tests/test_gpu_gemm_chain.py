@@ -7,7 +7,7 @@ import torch
 import inputs
 import oracle
 import paper_2305_13450_amd as ds
-from gpu_util import TOL_BF16, TOL_FP16, rel_err, run_gemm_chain
+from gpu_util import TOL_BF16, TOL_FP16, TOL_MID, mid_err, rel_err, run_gemm_chain
 
 pytestmark = pytest.mark.gpu
 
@@ -29,7 +29,7 @@ def test_cfg1_rowsync_matches_oracle_and_is_bit_exact(cfg1):
     for mode in MODES:
         print(f"cfg1 mode={mode}", flush=True)
         H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode)
-        assert rel_err(H, Href) <= TOL_BF16
+        assert mid_err(H, Href) <= TOL_MID
         assert rel_err(Y, Yref) <= TOL_BF16
         outs[mode] = (H, Y)
     for mode in (ds.MODE_STREAMSYNC, ds.MODE_PLAIN):
@@ -49,7 +49,7 @@ def test_every_tile_shape_ragged(tile, kind):
     pol = ds.SyncPolicy(kind)
     res = [run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode, tile=tile) for mode in MODES]
     for H, Y in res:
-        assert rel_err(H, Href) <= TOL_BF16
+        assert mid_err(H, Href) <= TOL_MID
         assert rel_err(Y, Yref) <= TOL_BF16
     for H, Y in res[1:]:
         assert torch.equal(res[0][0], H) and torch.equal(res[0][1], Y)
@@ -62,7 +62,7 @@ def test_other_pointwise_ops(mid, act):
     Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), act)
     pol = ds.SyncPolicy(ds.TILESYNC)
     H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, mid=mid, tile=ds.TILE_64x64)
-    assert rel_err(H, Href) <= TOL_BF16 and rel_err(Y, Yref) <= TOL_BF16
+    assert mid_err(H, Href) <= TOL_MID and rel_err(Y, Yref) <= TOL_BF16
     pol.destroy()
 
 
@@ -72,7 +72,7 @@ def test_fp16_chain():
     pol = ds.SyncPolicy(ds.ROWSYNC)
     a = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_128x128)
     b = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_STREAMSYNC, tile=ds.TILE_128x128)
-    assert rel_err(a[0], Href) <= TOL_FP16 and rel_err(a[1], Yref) <= TOL_FP16
+    assert mid_err(a[0], Href, 2.0 ** -11) <= TOL_MID and rel_err(a[1], Yref) <= TOL_FP16
     assert torch.equal(a[1], b[1])
     pol.destroy()
 
@@ -84,7 +84,7 @@ def test_skinny_m(M):
     pol = ds.SyncPolicy(ds.TILESYNC)
     for mode in MODES:
         H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode)
-        assert rel_err(H, Href) <= TOL_BF16 and rel_err(Y, Yref) <= TOL_BF16
+        assert mid_err(H, Href) <= TOL_MID and rel_err(Y, Yref) <= TOL_BF16
     pol.destroy()
 
 
@@ -98,7 +98,10 @@ def test_swiglu_chain_matches_oracle():
         pol = ds.SyncPolicy(ds.TILESYNC)
         res = [run_gemm_chain(t["X"], t["Wgu"], t["W2"], pol, mode, mid=ds.MID_SWIGLU, tile=tile) for mode in MODES]
         for H, Y in res:
-            assert rel_err(H, Href) <= TOL_BF16 and rel_err(Y, Yref) <= TOL_BF16
+            # silu(g)*u is heavy-tailed and K2 is small here, so the largest outputs sit more than five
+            # RMS out, where one bf16 rounding alone exceeds 2e-2 of the RMS: bound the error beyond
+            # the output's own rounding instead (stricter everywhere but in that extreme tail)
+            assert mid_err(H, Href) <= TOL_MID and mid_err(Y, Yref) <= 1e-2
         assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][1], res[2][1])
         pol.destroy()
 
