@@ -25,8 +25,10 @@
  *  - Element type is 16-bit (bf16 or fp16) with fp32 accumulation; the intermediate and the
  *    output are rounded to the 16-bit type with round-to-nearest-even.
  *  - Every row must start on a 16-byte boundary: base pointers 16-byte aligned and leading
- *    dimensions multiples of 8 elements; inner (K) dimensions multiples of 64.  Violations
- *    return DEPSYNC_EINVAL.
+ *    dimensions multiples of 8 elements; inner (K) dimensions multiples of 64.  The
+ *    intermediate (H, mid) must additionally be 128-byte aligned with a leading dimension
+ *    that is a multiple of 64 elements, so that no cache line holds the output of two producer
+ *    tiles.  Violations return DEPSYNC_EINVAL.
  */
 #ifndef DEPSYNC_H
 #define DEPSYNC_H
@@ -100,8 +102,9 @@ typedef struct {
                              between tiles that share a semaphore; 0 = derive from the chain  */
     uint32_t count;       /* STRIDEDSYNC: tiles per semaphore; 0 = derive                     */
     uint32_t flags;       /* DEPSYNC_FLAG_*                                                   */
-    uint32_t spin_limit;  /* 0 = wait without bound; otherwise give up after this many polls,
-                             record DEPSYNC_ETIMEOUT in the status and skip the tile's stores */
+    uint32_t spin_limit;  /* give up a wait after this many polls, record DEPSYNC_ETIMEOUT in the
+                             status and skip the tile's stores; 0 = the default bound (2^22 polls,
+                             a few seconds), 0xffffffff = wait without bound                    */
     uint32_t delay_tile;  /* debug: producer tile (row-major index) + 1 to delay; 0 = none    */
     uint32_t delay_iters; /* debug: s_sleep iterations the delayed tile spends before its post */
 } depsync_policy_params;

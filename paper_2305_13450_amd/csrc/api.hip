@@ -20,8 +20,8 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 // Workspace layout in 32-bit words.
-constexpr uint32_t WS_TICKET = 0;
-constexpr uint32_t WS_STATUS = 16;       // StatusBlock, 8 words
+constexpr uint32_t WS_TICKET = 0;        // 3 stages x 8 dispatch counters
+constexpr uint32_t WS_STATUS = 32;       // StatusBlock, 8 words
 constexpr uint32_t WS_ZERO_PAGE = 64;    // 64 words = 256 zero bytes (never written after init)
 constexpr uint32_t WS_SEMS = 128;
 constexpr uint32_t WS_MAX_SEMS = 1u << 16;
@@ -147,6 +147,8 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     if (d->ldx < d->K1 || d->ldw1 < d->K1 || d->ldh < d->N1 || d->ldw2 < (int64_t)K2 || d->ldy < d->N2)
         return DEPSYNC_EINVAL;
     if (d->ldx % 8 || d->ldw1 % 8 || d->ldh % 8 || d->ldw2 % 8 || d->ldy % 8) return DEPSYNC_EINVAL;
+    // rows of the intermediate must be whole 128-byte cache lines (see dep_wait in gemm_tile.hpp)
+    if (d->ldh % 64 || (reinterpret_cast<uintptr_t>(d->H) & 127u)) return DEPSYNC_EINVAL;
     const uint64_t lim = 1ull << 32;
     const uint64_t w1_rows = gate_up ? 2ull * d->N1 : (uint64_t)d->N1;
     if ((uint64_t)d->M * d->ldx * 2 >= lim || w1_rows * d->ldw1 * 2 >= lim || (uint64_t)d->M * d->ldh * 2 >= lim ||
@@ -213,6 +215,7 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     if (!d->in || !d->w1 || !d->mid || !d->w2 || !d->out) return DEPSYNC_EINVAL;
     if (!aligned16(d->in) || !aligned16(d->w1) || !aligned16(d->mid) || !aligned16(d->w2) || !aligned16(d->out))
         return DEPSYNC_EINVAL;
+    if (reinterpret_cast<uintptr_t>(d->mid) & 127u) return DEPSYNC_EINVAL;   // whole cache lines per pixel
     if (d->C % 64 || d->K1 % 64 || d->K2 % 8) return DEPSYNC_EINVAL;
     if (d->H >= 32768 || d->W >= 32768) return DEPSYNC_EINVAL;
     const uint64_t Mpix = (uint64_t)d->B * d->H * d->W;
@@ -288,7 +291,7 @@ uint64_t geom_signature(const Plan& p) {
     uint64_t h = 1469598103934665603ull;
     auto mix = [&](uint64_t v) { h = (h ^ v) * 1099511628211ull; };
     mix(p.n_stages);
-    for (int s = 0; s < p.n_stages; ++s) { mix(p.n_tiles[s]); mix(p.sem_count[s]); mix(p.sem_value[s]); mix(p.dep_kind[s]); }
+    for (int s = 0; s < p.n_stages; ++s) { mix(p.grid_x[s]); mix(p.grid_y[s]); mix(p.sem_count[s]); mix(p.sem_value[s]); mix(p.dep_kind[s]); }
     return h;
 }
 
@@ -300,7 +303,7 @@ int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t*
     const uint64_t next = (uint64_t)(pol->epoch + 2) * std::max(total, vmax);
     if (pol->need_reset || sig != pol->geom_sig || next >= (1ull << 31)) {
         // zero the dispatch counter and every semaphore the previous geometry may have touched
-        hipError_t e = launch_fill_u32(pol->ws + WS_TICKET, 0u, 1, stream);
+        hipError_t e = launch_fill_u32(pol->ws + WS_TICKET, 0u, 24, stream);
         if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_SEMS, 0u, WS_MAX_SEMS, stream);
         if (e != hipSuccess) return hip_fail(e);
         pol->epoch = 0;
@@ -319,10 +322,13 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
         if (s < p.n_stages) t += p.n_tiles[s];
     }
     a.ticket = pol->ws + WS_TICKET;
-    a.ticket_base = epoch * t;
+    a.epoch = epoch;
     a.block_offset = 0;
     a.flags = pol->params.flags;
-    a.spin_limit = pol->params.spin_limit;
+    // 0 selects a generous default bound (seconds), so that a dependency that can never be
+    // satisfied ends in DEPSYNC_ETIMEOUT instead of a hung GPU; 0xffffffff waits without bound
+    a.spin_limit = pol->params.spin_limit == 0 ? (1u << 22)
+                   : pol->params.spin_limit == 0xffffffffu ? 0u : pol->params.spin_limit;
     a.delay_tile = pol->params.delay_tile;
     a.delay_iters = pol->params.delay_iters;
     a.status = reinterpret_cast<StatusBlock*>(pol->ws + WS_STATUS);
@@ -432,7 +438,7 @@ int sync_policy_destroy(sync_policy_t* pol) {
 int dep_chain_reset(sync_policy_t* pol, void* stream) {
     if (!pol) return DEPSYNC_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, 1, st));
+    HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, 24, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS + 1, 0xffffffffu, 1, st));   // first_timeout = -1
     HIP_TRY(launch_fill_u32(pol->ws + WS_SEMS, 0u, WS_MAX_SEMS, st));

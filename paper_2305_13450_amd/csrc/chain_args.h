@@ -69,8 +69,8 @@ struct ChainArgs {
     StageDesc st[3];
     uint32_t n_stages;
     uint32_t first_ticket[4];   // stage s owns tickets [first_ticket[s], first_ticket[s+1])
-    uint32_t* ticket;           // dispatch counter
-    uint32_t ticket_base;       // counter value before this chain's draws
+    uint32_t* ticket;           // dispatch counters: [stage][XCD queue], 3 x 8
+    uint32_t epoch;             // chains run on this workspace since its last reset
     uint32_t block_offset;      // HW order / PLAIN: ticket of this launch's block 0
     uint32_t flags;             // DEPSYNC_FLAG_*
     uint32_t spin_limit;

@@ -1,7 +1,7 @@
 // The chain kernel template and its per-(element type, A addressing mode) launcher.
 //
-// One kernel template serves every launch of a chain: a workgroup draws a ticket, finds the
-// stage and tile the ticket names and runs that tile (see sync_device.hpp for why producer
+// One kernel template serves every launch of a chain: a workgroup draws the stage and
+// tile it runs from the chain's dispatch queues (see sync_device.hpp for why producer
 // and consumer share one body).  It is instantiated per macro-tile shape, element type, A
 // addressing mode, and with the synchronisation hooks compiled in (FINE, STREAMSYNC) or out
 // (PLAIN).  Each translation unit kern_*.hip instantiates one (type, mode) family so that the
@@ -16,19 +16,20 @@ namespace depsync {
 
 template <class Cfg, typename T, bool SYNC, uint32_t AMODE>
 __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs args) {
+    // One LDS object only: with a second one the compiler can no longer tell the DMA writes
+    // into the idle stage from the fragment reads of the current stage and serialises them.
     __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
-    __shared__ uint32_t ticket_slot;
 
-    const uint32_t rel = draw_ticket<SYNC>(args, &ticket_slot);
-    uint32_t stage = 0;
-    if (args.n_stages > 1 && rel >= args.first_ticket[1]) stage = 1;
-    if (args.n_stages > 2 && rel >= args.first_ticket[2]) stage = 2;
-    const StageDesc& s = args.st[stage];
-    uint32_t tile_lin = rel - args.first_ticket[stage];
-    if (SYNC && stage == 0 && (args.flags & DS_FLAG_REVERSE_ORDER))
-        tile_lin = (args.first_ticket[1] - args.first_ticket[0]) - 1u - tile_lin;
-
-    gemm_tile<Cfg, T, SYNC, AMODE>(args, s, tile_lin, rel, lds);
+    const TileId t = draw_tile<SYNC>(args, reinterpret_cast<uint32_t*>(lds));
+    if (t.rel == 0xffffffffu) return;
+    const StageDesc& s = args.st[t.stage];
+    if constexpr (SYNC) {
+        if (s.dep_kind != DEP_NONE) {
+            gemm_tile<Cfg, T, true, AMODE, true>(args, s, t.tx, t.ty, t.rel, lds);
+            return;
+        }
+    }
+    gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds);
 }
 
 //                       TM   TN  WM WN  waves per SIMD

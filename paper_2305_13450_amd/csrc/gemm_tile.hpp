@@ -12,6 +12,9 @@
 // before the wait (the load/wait reordering of Section IV-C).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
+
 #include "chain_args.h"
 #include "sync_device.hpp"
 
@@ -64,7 +67,6 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 __device__ __forceinline__ void dma16(const char* g, char* l) {
     __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)l, 16, 0, 0);
 }
-
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
@@ -123,7 +125,12 @@ __device__ __forceinline__ bool dep_segment(const StageDesc& s, uint32_t m0, uin
 }
 
 // Wait (blocking) or test (non-blocking) the semaphores of one dependency segment.  Returns
-// true when all are reached; the acquire fence has then been executed.
+// true when all are reached.  Acquire ordering without a cache invalidate: the semaphore reads
+// are agent-scope atomic loads whose values this wave branches on before it issues the
+// dependent operand's loads.  Those loads cannot hit a stale line in this XCD's L2: caches are
+// invalidated when a kernel starts, nothing reads a line of the intermediate before the tile
+// that produces it has posted, and the host requires the intermediate's rows to be 128-byte
+// aligned, so a cache line never mixes the outputs of two producer tiles.
 __device__ __forceinline__ bool dep_wait(WaitCtx& w, const StageDesc& s, const DepRange& r, bool blocking) {
     const uint32_t target = s.sem_target_base + s.sem_value;
     bool polled = false;
@@ -136,7 +143,6 @@ __device__ __forceinline__ bool dep_wait(WaitCtx& w, const StageDesc& s, const D
             sem_wait(w, sem, target, v);
         }
     }
-    acquire_agent();
     if (w.args->flags & DS_FLAG_COUNT) {
         for (uint32_t y = r.y0; y <= r.y1; ++y) count_wait(*w.args, polled);
     }
@@ -145,22 +151,39 @@ __device__ __forceinline__ bool dep_wait(WaitCtx& w, const StageDesc& s, const D
 
 // ---- the tile ------------------------------------------------------------------------------
 
-template <class Cfg, typename T, bool SYNC, uint32_t AMODE>
-__device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc& s, uint32_t tile_lin,
+// A wave-uniform value pinned into scalar registers (so that the compiler keeps it there
+// instead of re-reading kernel arguments inside the K loop).
+__device__ __forceinline__ uint32_t uni(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+__device__ __forceinline__ const char* uni_ptr(const void* p) {
+    const uint64_t v = reinterpret_cast<uint64_t>(p);
+    const uint64_t lo = uni((uint32_t)v), hi = uni((uint32_t)(v >> 32));
+    return reinterpret_cast<const char*>(lo | (hi << 32));
+}
+
+// DEP: this tile's A operand is produced by the previous stage of the chain (the tile waits
+// on semaphores before it requests a slice of A).
+template <class Cfg, typename T, bool SYNC, uint32_t AMODE, bool DEP>
+__device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc& s, uint32_t tx, uint32_t ty,
                                           uint32_t rel_ticket, char* lds) {
     using M = Mma<T>;
     using V8 = typename M::V8;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, FM = Cfg::FM, FN = Cfg::FN;
     constexpr int NIA = Cfg::NIA, NIB = Cfg::NIB;
+    static_assert(!DEP || SYNC, "dependencies exist only with the synchronisation hooks compiled in");
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
-    const uint32_t wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const uint32_t wave = uni(tid >> 6);
     const uint32_t wm = wave / Cfg::WN, wn = wave % Cfg::WN;
-    const uint32_t tx = tile_lin % s.grid_x, ty = tile_lin / s.grid_x;   // row-major, x fastest
+    const uint32_t sM = uni(s.M), sN = uni(s.N);
     const bool gate_up = (s.bmode == B_GATE_UP);
     const uint32_t tn_out = gate_up ? TN / 2 : TN;       // output columns this tile owns
     const uint32_t m0 = ty * TM, n0 = tx * tn_out;
-    const uint32_t KT = s.K / 64;
+    const uint32_t KT = uni(s.K / 64);
+    const char* const Abase = uni_ptr(s.A);
+    const char* const Bbase = uni_ptr(s.B);
+    // conv geometry (unused otherwise)
+    const uint32_t cH = uni(s.H), cW = uni(s.W), cCin = uni(s.Cin);
+    const char* const zero_page = uni_ptr(s.zero_page);
 
     WaitCtx wctx{&args, rel_ticket, true};
 
@@ -172,11 +195,11 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     for (int i = 0; i < NIA; ++i) {
         const uint32_t r = (wave * NIA + i) * 8 + lrow;
         const uint32_t c = lpos ^ swz(r);
-        const uint32_t m = min(m0 + r, s.M - 1);
+        const uint32_t m = min(m0 + r, sM - 1);
         offA[i] = m * s.lda * 2u + c * 16u;
         if constexpr (AMODE == A_CONV3X3) {
-            const uint32_t rem = m % (s.H * s.W);
-            pixyx[i] = ((rem / s.W) << 16) | (rem % s.W);
+            const uint32_t rem = m % (cH * cW);
+            pixyx[i] = ((rem / cW) << 16) | (rem % cW);
         }
     }
 #pragma unroll
@@ -186,40 +209,55 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         uint32_t row;
         if (gate_up) {
             const uint32_t blk = q >> 5, within = q & 31u;
-            const uint32_t col = min(n0 + (blk >> 1) * 32 + within, s.N - 1);
-            row = (blk & 1u) * s.N + col;
+            const uint32_t col = min(n0 + (blk >> 1) * 32 + within, sN - 1);
+            row = (blk & 1u) * sN + col;
         } else {
-            row = min(n0 + q, s.N - 1);
+            row = min(n0 + q, sN - 1);
         }
         offB[i] = row * s.ldb * 2u + c * 16u;
     }
 
-    auto issue_B = [&](uint32_t stage, uint32_t kt) {
-        const char* base = (const char*)s.B + (size_t)kt * 128u;
-        char* l = lds + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (NIB * 1024);
-#pragma unroll
-        for (int i = 0; i < NIB; ++i) dma16(base + offB[i], l + i * 1024);
-    };
-    auto issue_A = [&](uint32_t stage, uint32_t kt) {
-        char* l = lds + stage * Cfg::STAGE_BYTES + wave * (NIA * 1024);
+    // Source of the K step that is being requested ("next" step): a byte offset for B and the
+    // dense A, and for the conv the filter tap (fr, fs in -1..1) and the byte shift of that tap.
+    struct NextStep {
+        uint32_t kbytes;     // kt * 128
+        uint32_t tap, c0;    // conv: filter tap 0..8 and first input channel of the step
+        int fr, fs;
+        long shift;
+    } nx;
+    auto set_next = [&](uint32_t kt) __attribute__((always_inline)) {
+        nx.kbytes = kt * 128u;
         if constexpr (AMODE == A_CONV3X3) {
             const uint32_t k0 = kt * 64u;
-            const uint32_t tap = k0 / s.Cin, c0 = k0 % s.Cin;
-            const int fr = (int)(tap / 3) - 1, fs = (int)(tap % 3) - 1;
-            const long shift = ((long)fr * (long)s.W + fs) * (long)s.Cin * 2 + (long)c0 * 2;
-            const char* base = (const char*)s.A + shift;
-            const char* zero = (const char*)s.zero_page + lpos * 16u;
-#pragma unroll
-            for (int i = 0; i < NIA; ++i) {
-                const int y = (int)(pixyx[i] >> 16) + fr, x = (int)(pixyx[i] & 0xffffu) + fs;
-                const bool valid = (y >= 0) && (y < (int)s.H) && (x >= 0) && (x < (int)s.W);
-                dma16(valid ? base + offA[i] : zero, l + i * 1024);
-            }
-        } else {
-            const char* base = (const char*)s.A + (size_t)kt * 128u;
-#pragma unroll
-            for (int i = 0; i < NIA; ++i) dma16(base + offA[i], l + i * 1024);
+            nx.tap = k0 / cCin; nx.c0 = k0 % cCin;
+            nx.fr = (int)(nx.tap / 3) - 1; nx.fs = (int)(nx.tap % 3) - 1;
+            nx.shift = ((long)nx.fr * (long)cW + nx.fs) * (long)cCin * 2 + (long)nx.c0 * 2;
         }
+    };
+    // One 1 KB DMA instruction of the B (weights) or A operand of the next K step into `stage`.
+    auto dma_B = [&](uint32_t stage, int i) __attribute__((always_inline)) {
+        char* l = lds + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (NIB * 1024);
+        dma16(Bbase + nx.kbytes + offB[i], l + i * 1024);
+    };
+    auto dma_A = [&](uint32_t stage, int i) __attribute__((always_inline)) {
+        char* l = lds + stage * Cfg::STAGE_BYTES + wave * (NIA * 1024);
+        const char* src;
+        if constexpr (AMODE == A_CONV3X3) {
+            const int y = (int)(pixyx[i] >> 16) + nx.fr, x = (int)(pixyx[i] & 0xffffu) + nx.fs;
+            const bool valid = (y >= 0) && (y < (int)cH) && (x >= 0) && (x < (int)cW);
+            src = valid ? Abase + nx.shift + offA[i] : zero_page + lpos * 16u;
+        } else {
+            src = Abase + nx.kbytes + offA[i];
+        }
+        dma16(src, l + i * 1024);
+    };
+    auto issue_B = [&](uint32_t stage) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NIB; ++i) dma_B(stage, i);
+    };
+    auto issue_A = [&](uint32_t stage) __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < NIA; ++i) dma_A(stage, i);
     };
 
     // ---- per-lane fragment read offsets (bytes inside the A / B part of a stage) ----
@@ -243,51 +281,85 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
     const bool reorder = !(args.flags & DS_FLAG_NO_REORDER);
-    const bool has_dep = SYNC && (s.dep_kind != DEP_NONE);
 
-    // ---- prologue: K step 0 into stage 0 ----
-    {
-        DepRange dr;
-        const bool need = has_dep && dep_segment(s, m0, TM, 0, dr);
-        if (need && !reorder) dep_wait(wctx, s, dr, true);
-        issue_B(0, 0);
-        if (need && reorder) dep_wait(wctx, s, dr, true);
-        issue_A(0, 0);
+    // Dependency segments start at multiples of seg_steps K steps (0: only at step 0).
+    uint32_t seg_steps = 0, seg_left = 0;
+    if constexpr (DEP) {
+        switch (s.dep_kind) {
+            case DEP_TILE: case DEP_STRIDED: case DEP_CONV_TILE: seg_steps = s.prod_tn / 64; break;
+            case DEP_CONV_TAPROW: seg_steps = 3 * cCin / 64; break;
+            default: seg_steps = 0; break;
+        }
+        seg_steps = uni(seg_steps);
+        seg_left = seg_steps;
     }
 
-    for (uint32_t kt = 0; kt < KT; ++kt) {
-        const uint32_t cur = kt & 1u;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // stage `cur` is complete; nobody still reads stage cur^1
-
-        bool pend_a = false, pend_b = false;
+    // ---- prologue: K step 0 into stage 0 ----
+    set_next(0);
+    if constexpr (DEP) {
         DepRange dr;
-        if (kt + 1 < KT) {
-            const bool need = has_dep && dep_segment(s, m0, TM, kt + 1, dr);
-            const bool ready = !need || dep_wait(wctx, s, dr, false);
-            if (ready || reorder) issue_B(cur ^ 1u, kt + 1); else pend_b = true;
-            if (ready) issue_A(cur ^ 1u, kt + 1); else pend_a = true;
+        const bool need = dep_segment(s, m0, TM, 0, dr);
+        if (need && !reorder) dep_wait(wctx, s, dr, true);
+        issue_B(0);
+        if (need && reorder) dep_wait(wctx, s, dr, true);
+    } else {
+        issue_B(0);
+    }
+    issue_A(0);
+
+    // The K loop.  Per step and wave: 4*FM groups of FN MFMAs.  The DMA instructions of the next
+    // step are spread over those groups (a wave that issues them all at once sits at the memory
+    // pipeline's queue and starves its matrix unit), weights first; the fragments of the next
+    // 16-wide K slice are read from LDS while the current slice's MFMAs run.  The body is free of
+    // branches: the last step simply re-requests its own slice into the idle stage.
+    constexpr int NG = 4 * FM;            // MFMA groups per step
+    constexpr int ND = NIA + NIB;         // DMA instructions per step
+    for (uint32_t kt = 0; kt < KT; ++kt) {
+        const uint32_t cur = kt & 1u, nxt = cur ^ 1u;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // stage `cur` is complete; nobody still reads stage `nxt`
+
+        set_next(min(kt + 1, KT - 1));
+        if constexpr (DEP) {
+            if (seg_steps != 0 && --seg_left == 0) {
+                seg_left = seg_steps;
+                DepRange dr;
+                if (kt + 1 < KT && dep_segment(s, m0, TM, kt + 1, dr) && !dep_wait(wctx, s, dr, false)) {
+                    // The producer is not there yet.  Request the weights of the next step first
+                    // (the load/wait reordering), then really wait; the body requests the A slice.
+                    if (reorder) issue_B(nxt);
+                    dep_wait(wctx, s, dr, true);
+                }
+            }
         }
 
         const char* la = lds + cur * Cfg::STAGE_BYTES;
         const char* lb = la + Cfg::A_BYTES;
+        V8 af[2][FM], bf[2][FN];
+#pragma unroll
+        for (int i = 0; i < FM; ++i) af[0][i] = *(const V8*)(la + aoff[0] + i * (32 * 128));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) bf[0][j] = *(const V8*)(lb + boff[0] + j * (32 * 128));
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-            V8 af[FM], bf[FN];
+            const int c = kk & 1, n = c ^ 1;
 #pragma unroll
-            for (int i = 0; i < FM; ++i) af[i] = *(const V8*)(la + aoff[kk] + i * (32 * 128));
+            for (int i = 0; i < FM; ++i) {
+                const int g = kk * FM + i;
+                if (kk < 3) {
+                    af[n][i] = *(const V8*)(la + aoff[kk + 1] + i * (32 * 128));
 #pragma unroll
-            for (int j = 0; j < FN; ++j) bf[j] = *(const V8*)(lb + boff[kk] + j * (32 * 128));
+                    for (int j = (i * FN) / FM; j < ((i + 1) * FN) / FM; ++j)
+                        bf[n][j] = *(const V8*)(lb + boff[kk + 1] + j * (32 * 128));
+                }
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+                for (int d = (g * ND) / NG; d < ((g + 1) * ND) / NG; ++d) {
+                    if (d < NIB) dma_B(nxt, d);
+                    else dma_A(nxt, d - NIB);
+                }
 #pragma unroll
-                for (int j = 0; j < FN; ++j) acc[i][j] = M::mma(af[i], bf[j], acc[i][j]);
-        }
-
-        if (pend_a) {   // the producer was not ready: now really wait, then request the slice
-            dep_wait(wctx, s, dr, true);
-            if (pend_b) issue_B(cur ^ 1u, kt + 1);
-            issue_A(cur ^ 1u, kt + 1);
+                for (int j = 0; j < FN; ++j) acc[i][j] = M::mma(af[c][i], bf[c][j], acc[i][j]);
+            }
         }
     }
 
@@ -296,6 +368,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // 8*(v/4) + 4*(lane/32) + v%4 for v = 0..15.
     if (wctx.ok) {
         T* Cp = (T*)s.C;
+        const uint32_t ldc = s.ldc, act = s.act;
         const uint32_t colw = lane & 31u, rowh = (lane >> 5) * 4u;
         if (gate_up) {
             if constexpr (FN >= 2) {
@@ -308,7 +381,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         for (int v = 0; v < 16; ++v) {
                             const uint32_t row = m0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + rowh + (v % 4);
                             const float g = acc[i][2 * jp][v], u = acc[i][2 * jp + 1][v];
-                            if (row < s.M && col < s.N) Cp[(size_t)row * s.ldc + col] = (T)(silu_f(g) * u);
+                            if (row < sM && col < sN) Cp[(size_t)row * ldc + col] = (T)(silu_f(g) * u);
                         }
                     }
             }
@@ -322,15 +395,15 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                     for (int v = 0; v < 16; ++v) {
                         const uint32_t row = m0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + rowh + (v % 4);
                         float x = acc[i][j][v];
-                        if (s.act == ACT_GELU) x = gelu_erf(x);
-                        else if (s.act == ACT_RELU) x = fmaxf(x, 0.0f);
-                        if (row < s.M && col < s.N) Cp[(size_t)row * s.ldc + col] = (T)x;
+                        if (act == ACT_GELU) x = gelu_erf(x);
+                        else if (act == ACT_RELU) x = fmaxf(x, 0.0f);
+                        if (row < sM && col < sN) Cp[(size_t)row * ldc + col] = (T)x;
                     }
                 }
         }
     }
 
-    if (SYNC) post_tile(args, s, tile_lin, tx, ty);
+    if (SYNC) post_tile(args, s, ty * s.grid_x + tx, tx, ty);
 }
 
 }  // namespace depsync

@@ -4,16 +4,18 @@
 //  * Dispatch.  The paper relies on CUDA issuing the blocks of the earlier-launched kernel
 //    first and adds a one-thread "wait kernel" to order the launches (Section III-B).  HIP
 //    makes no such promise across hardware queues, so here EVERY workgroup of every launch of
-//    a chain draws a ticket from one shared counter and runs whatever tile the ticket names:
-//    tickets [0,P) are producer tiles, [P,P+C) consumer tiles, in row-major order (Section
-//    III-C).  A workgroup can only be spinning while it holds a ticket >= P, and by then all
-//    tickets < P are held by resident workgroups that never wait, so every semaphore is
-//    eventually posted whatever the dispatcher does.
-//  * post: every wave makes its stores visible at agent scope, the workgroup meets at a
-//    barrier, one lane does a release increment of the tile's semaphore (Section III-D).
+//    a chain draws its tile from shared dispatch queues in which all producer tiles come
+//    before the consumer tiles, each stage in row-major order (Section III-C); see draw_tile.
+//    A workgroup can only be spinning while it holds a consumer tile, and the producer tiles
+//    it waits for are held by resident workgroups that never wait or are still ahead of every
+//    consumer in their queue, so every semaphore is eventually posted whatever the dispatcher
+//    does.
+//  * post: every wave drains its stores, the workgroup meets at a barrier, one lane does an
+//    agent-scope release increment of the tile's semaphore (Section III-D).
 //  * wait: every wave polls the same semaphore word (all lanes read one address, the result
-//    is made scalar, so the spin loop is wave-uniform), sleeps between polls, and executes an
-//    agent-scope acquire fence once the value is reached.  No lane-0 branch, no extra barrier.
+//    is made scalar, so the spin loop is wave-uniform) and sleeps between polls.  No lane-0
+//    branch, no extra barrier, and no cache invalidate (see dep_wait in gemm_tile.hpp for why
+//    none is needed).
 #pragma once
 #include <hip/hip_runtime.h>
 #include "chain_args.h"
@@ -32,10 +34,6 @@ __device__ __forceinline__ uint32_t sem_load(const uint32_t* sem) {
 
 __device__ __forceinline__ bool sem_reached(uint32_t v, uint32_t target) {
     return (int32_t)(v - target) >= 0;
-}
-
-__device__ __forceinline__ void acquire_agent() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
 }
 
 // State one wave keeps while it runs a tile.
@@ -98,7 +96,9 @@ __device__ __forceinline__ uint32_t policy_sem(uint32_t kind, uint32_t x, uint32
 // post (Section III-D): called by all threads of the workgroup after the tile's stores.
 __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s, uint32_t tile_lin, uint32_t x, uint32_t y) {
     if (s.post_kind == DEP_NONE) return;
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    // every wave's stores have left the wave (vmcnt) before the barrier; the one release below
+    // then writes the XCD's L2 back once for the whole tile
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
         if (a.delay_tile == tile_lin + 1) {
@@ -111,17 +111,90 @@ __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s
     }
 }
 
-// Draw the tile this workgroup runs.  Returns the relative ticket in [0, total).
+// The tile a workgroup runs.
+struct TileId {
+    uint32_t stage, tx, ty;
+    uint32_t rel;      // first_ticket[stage] + row-major index: unique per tile, used in the status
+};
+
+__device__ __forceinline__ uint32_t xcc_id() {
+    uint32_t x;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(x));
+    return x & 7u;
+}
+
+// Tile dispatch (Sections III-B and III-C).  Every stage has one queue per XCD (each XCD has
+// its own L2): queue q of a stage holds the stage's tiles whose column tile index is congruent
+// to q mod 8, in row-major order, so that the tiles an XCD works on share operand rows and
+// columns.  A workgroup of ANY launch of the chain takes a tile of the earliest stage that
+// still has undrawn tiles, from the queue of the XCD it runs on if that one is not empty, else
+// from the next non-empty one.  Hence no consumer tile is handed out while a producer tile is
+// undrawn anywhere: a workgroup can only be waiting when every tile of the stage it waits for
+// is already held by a resident workgroup, and by induction over the stages those finish.
+// A queue counter only grows: entry = counter - epoch * queue_length; a draw beyond the end
+// is undone, so after a chain every counter has advanced by exactly its queue length.
+__device__ __forceinline__ uint32_t queue_len(const StageDesc& st, uint32_t q) {
+    return ((st.grid_x + 7u - q) >> 3) * st.grid_y;
+}
+
 template <bool SYNC>
-__device__ __forceinline__ uint32_t draw_ticket(const ChainArgs& a, uint32_t* lds_slot) {
-    if (!SYNC || (a.flags & DS_FLAG_HW_ORDER)) return a.block_offset + blockIdx.x;
+__device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_slot) {
+    TileId t;
+    if (!SYNC || (a.flags & DS_FLAG_HW_ORDER)) {
+        const uint32_t rel = a.block_offset + blockIdx.x;
+        uint32_t stage = 0;
+        if (a.n_stages > 1 && rel >= a.first_ticket[1]) stage = 1;
+        if (a.n_stages > 2 && rel >= a.first_ticket[2]) stage = 2;
+        const uint32_t lin = rel - a.first_ticket[stage], gx = a.st[stage].grid_x;
+        t.stage = stage; t.tx = lin % gx; t.ty = lin / gx; t.rel = rel;
+        return t;
+    }
     if (threadIdx.x == 0) {
-        uint32_t t = __hip_atomic_fetch_add(a.ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        *lds_slot = t - a.ticket_base;
+        const uint32_t home = xcc_id();
+        uint32_t stage = 0, tx = 0, ty = 0;
+        bool found = false;
+        for (uint32_t s = 0; s < a.n_stages && !found; ++s) {
+            const StageDesc& st = a.st[s];
+            uint32_t* cnt = a.ticket + 8u * s;
+            // one look at the stage's eight counters: skip a stage that is already handed out
+            uint32_t c[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) c[q] = __hip_atomic_load(cnt + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            bool left = false;
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const uint32_t len = queue_len(st, q);
+                left = left || (c[q] - a.epoch * len < len);
+            }
+            if (!left) continue;
+            for (uint32_t k = 0; k < 8; ++k) {
+                const uint32_t q = (home + k) & 7u;
+                const uint32_t ncol = (st.grid_x + 7u - q) >> 3, len = ncol * st.grid_y;
+                if (len == 0) continue;
+                uint32_t i = __hip_atomic_fetch_add(cnt + q, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                             a.epoch * len;
+                if (i >= len) {   // queue exhausted: undo and try the next XCD's queue
+                    __hip_atomic_fetch_sub(cnt + q, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    continue;
+                }
+                if (s == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
+                stage = s; ty = i / ncol; tx = q + 8u * (i % ncol);
+                found = true;
+                break;
+            }
+        }
+        lds_slot[0] = stage; lds_slot[1] = tx; lds_slot[2] = ty; lds_slot[3] = found ? 1u : 0u;
     }
     __syncthreads();
-    uint32_t t = *lds_slot;
-    return __builtin_amdgcn_readfirstlane(t);
+    t.stage = __builtin_amdgcn_readfirstlane(lds_slot[0]);
+    t.tx = __builtin_amdgcn_readfirstlane(lds_slot[1]);
+    t.ty = __builtin_amdgcn_readfirstlane(lds_slot[2]);
+    const uint32_t found = __builtin_amdgcn_readfirstlane(lds_slot[3]);
+    __syncthreads();   // the slot is part of the operand staging area: everyone has read it before reuse
+    // Exactly as many workgroups are launched as there are tiles, so a draw cannot come back
+    // empty; if the counters were corrupted it does, and the workgroup leaves without a tile.
+    t.rel = found ? a.first_ticket[t.stage] + t.ty * a.st[t.stage].grid_x + t.tx : 0xffffffffu;
+    return t;
 }
 
 }  // namespace depsync

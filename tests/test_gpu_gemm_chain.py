@@ -150,6 +150,35 @@ def test_repeated_launches_reuse_the_workspace_without_reset():
     pol.destroy()
 
 
+def test_changing_inputs_on_reused_buffers_never_reads_stale_intermediate():
+    # The same H and Y buffers are reused by back-to-back chains whose inputs alternate, so a consumer
+    # that hit a cache line of H left over from the previous chain would produce the other answer.
+    ta = inputs.mlp(1024, 512, 1024, 768, seed=41)
+    tb = inputs.mlp(1024, 512, 1024, 768, seed=42)
+    W1t = ta["W1"].t().contiguous().cuda(); W2t = ta["W2"].t().contiguous().cuda()
+    Xs = [ta["X"].cuda(), tb["X"].cuda()]
+    H = torch.empty((1024, 1024), dtype=torch.bfloat16, device="cuda"); Y = torch.empty((1024, 768), dtype=torch.bfloat16, device="cuda")
+    pol = ds.SyncPolicy(ds.TILESYNC)
+    want = []
+    for X in Xs:
+        ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=ds.MODE_STREAMSYNC, tile=ds.TILE_128x128)
+        torch.cuda.synchronize()
+        want.append(Y.clone())
+    assert not torch.equal(want[0], want[1])
+    for kind in (ds.TILESYNC, ds.ROWSYNC):
+        p2 = ds.SyncPolicy(kind)
+        outs = []
+        for it in range(24):                      # enqueue back to back, no host sync in between
+            Yi = torch.empty_like(Y)
+            ds.dep_gemm_chain(Xs[it & 1], W1t, H, W2t, Yi, p2, mode=ds.MODE_FINE, tile=ds.TILE_128x128)
+            outs.append(Yi)
+        torch.cuda.synchronize()
+        for it, Yi in enumerate(outs):
+            assert torch.equal(Yi, want[it & 1]), (kind, it)
+        p2.destroy()
+    pol.destroy()
+
+
 def test_delayed_and_reversed_producers_do_not_change_the_result():
     t = inputs.mlp(512, 256, 512, 256, seed=29)
     _, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
