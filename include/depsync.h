@@ -109,7 +109,22 @@ typedef struct {
     uint32_t delay_iters; /* debug: s_sleep iterations the delayed tile spends before its post */
 } depsync_policy_params;
 
+#define DEPSYNC_FLAG_TRACE 16u        /* record per-tile start / ready / end times (FINE and
+                                         STREAMSYNC); read them with depsync_read_trace        */
+
 typedef struct sync_policy sync_policy_t;
+
+/* Per-tile timing record; times are ticks of the GPU's constant 100 MHz counter. */
+typedef struct {
+    uint32_t rel;       /* producer tiles: row-major index; later stages: offset by the tiles
+                           of the stages before                                               */
+    uint32_t where;     /* bits 0-7: 1 if the tile had a dependency, else 0; 8-15: XCD;
+                           16-23: CU within its shader array; 24-31: shader engine            */
+    uint32_t tx, ty;    /* column tile, row tile                                              */
+    uint64_t t_start;   /* tile handed out                                                    */
+    uint64_t t_ready;   /* first dependency satisfied (t_start's neighbour if none)           */
+    uint64_t t_end;     /* stores and post done                                               */
+} depsync_trace_rec;
 
 typedef struct {
     int32_t timed_out;       /* number of tiles whose bounded wait expired                    */
@@ -193,6 +208,11 @@ int dep_chain_reset(sync_policy_t* pol, void* stream);
 /* Synchronises the policy's streams, then copies the status block to the host.  Returns
  * DEPSYNC_ETIMEOUT if a bounded wait expired since the last reset.                        */
 int depsync_last_status(sync_policy_t* pol, depsync_status* out);
+
+/* Synchronises the device and copies up to max_records trace records (index = rel) of the
+ * last chain run with DEPSYNC_FLAG_TRACE; returns the number copied or a negative status.
+ * At most 8192 tiles are traced.                                                          */
+int depsync_read_trace(sync_policy_t* pol, depsync_trace_rec* out, int max_records);
 
 /* ---- chains -------------------------------------------------------------------------- */
 

@@ -20,11 +20,11 @@ MODE_FINE, MODE_STREAMSYNC, MODE_PLAIN = 0, 1, 2
 MID_NONE, MID_GELU, MID_RELU, MID_SWIGLU, MID_CAUSAL_ATTN = 0, 1, 2, 3, 4
 BF16, FP16 = 0, 1
 TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128, TILE_64x128, TILE_64x64 = range(7)
-FLAG_NO_REORDER, FLAG_COUNT, FLAG_REVERSE_ORDER, FLAG_HW_ORDER = 1, 2, 4, 8
+FLAG_NO_REORDER, FLAG_COUNT, FLAG_REVERSE_ORDER, FLAG_HW_ORDER, FLAG_TRACE = 1, 2, 4, 8, 16
 OK, EINVAL, ENOMEM, EHIP, ETIMEOUT, ENOTIMPL = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [
-    "sync_policy_create", "sync_policy_destroy", "dep_chain_reset", "depsync_last_status",
+    "sync_policy_create", "sync_policy_destroy", "dep_chain_reset", "depsync_last_status", "depsync_read_trace",
     "dep_gemm_chain", "dep_conv_chain", "depsync_gemm_chain_plan", "depsync_conv_chain_plan",
     "depsync_row_major", "depsync_policy_sem", "depsync_policy_value", "depsync_wave_model",
     "depsync_sync_count", "depsync_simulate_chain", "depsync_strerror", "depsync_last_hip_error",
@@ -51,6 +51,11 @@ class Status(ctypes.Structure):
     _fields_ = [("timed_out", ctypes.c_int32), ("first_timeout", ctypes.c_int32),
                 ("posts", ctypes.c_uint32), ("waits", ctypes.c_uint32),
                 ("polling_waits", ctypes.c_uint32), ("launches", ctypes.c_uint32)]
+
+
+class TraceRec(ctypes.Structure):
+    _fields_ = [("rel", ctypes.c_uint32), ("where", ctypes.c_uint32), ("tx", ctypes.c_uint32), ("ty", ctypes.c_uint32),
+                ("t_start", ctypes.c_uint64), ("t_ready", ctypes.c_uint64), ("t_end", ctypes.c_uint64)]
 
 
 class PlanInfo(ctypes.Structure):
@@ -105,6 +110,7 @@ def _lib() -> ctypes.CDLL:
         L.sync_policy_destroy.argtypes = [vp]
         L.dep_chain_reset.argtypes = [vp, vp]
         L.depsync_last_status.argtypes = [vp, ctypes.POINTER(Status)]
+        L.depsync_read_trace.argtypes = [vp, ctypes.POINTER(TraceRec), i32]
         L.dep_gemm_chain.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, vp, vp]
         L.dep_conv_chain.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, vp, vp]
         L.depsync_gemm_chain_plan.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
@@ -186,6 +192,14 @@ class SyncPolicy:
 
     def reset(self, stream=None):
         _check(_lib().dep_chain_reset(self.handle, _stream_handle(stream)), "dep_chain_reset")
+
+    def read_trace(self, n_tiles: int):
+        """Per-tile timing records of the last chain run with FLAG_TRACE (list of TraceRec)."""
+        buf = (TraceRec * n_tiles)()
+        n = _lib().depsync_read_trace(self.handle, buf, n_tiles)
+        if n < 0:
+            raise DepsyncError(n, "depsync_read_trace")
+        return list(buf[:n])
 
     def status(self, raise_on_timeout: bool = True) -> Status:
         st = Status()

@@ -25,7 +25,9 @@ constexpr uint32_t WS_STATUS = 32;       // StatusBlock, 8 words
 constexpr uint32_t WS_ZERO_PAGE = 64;    // 64 words = 256 zero bytes (never written after init)
 constexpr uint32_t WS_SEMS = 128;
 constexpr uint32_t WS_MAX_SEMS = 1u << 16;
-constexpr uint32_t WS_WORDS = WS_SEMS + WS_MAX_SEMS;
+constexpr uint32_t WS_TRACE = WS_SEMS + WS_MAX_SEMS;      // TraceRec[WS_TRACE_CAP], 10 words each
+constexpr uint32_t WS_TRACE_CAP = 8192;
+constexpr uint32_t WS_WORDS = WS_TRACE + WS_TRACE_CAP * (sizeof(TraceRec) / 4);
 
 int hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -332,6 +334,8 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
     a.delay_tile = pol->params.delay_tile;
     a.delay_iters = pol->params.delay_iters;
     a.status = reinterpret_cast<StatusBlock*>(pol->ws + WS_STATUS);
+    a.trace = reinterpret_cast<TraceRec*>(pol->ws + WS_TRACE);
+    a.trace_cap = WS_TRACE_CAP;
     for (int s = 0; s < p.n_stages; ++s) {
         StageDesc& st = a.st[s];
         st.grid_x = p.grid_x[s];
@@ -461,6 +465,15 @@ int depsync_last_status(sync_policy_t* pol, depsync_status* out) {
     out->launches = pol->launches;
     if (sb.timed_out > 0) { pol->need_reset = true; return DEPSYNC_ETIMEOUT; }
     return DEPSYNC_OK;
+}
+
+int depsync_read_trace(sync_policy_t* pol, depsync_trace_rec* out, int max_records) {
+    if (!pol || !out || max_records < 0) return DEPSYNC_EINVAL;
+    static_assert(sizeof(depsync_trace_rec) == sizeof(TraceRec), "trace record layout");
+    HIP_TRY(hipDeviceSynchronize());
+    const size_t n = std::min<size_t>((size_t)max_records, WS_TRACE_CAP);
+    HIP_TRY(hipMemcpy(out, pol->ws + WS_TRACE, n * sizeof(TraceRec), hipMemcpyDeviceToHost));
+    return (int)n;
 }
 
 int depsync_gemm_chain_plan(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int n_cu,

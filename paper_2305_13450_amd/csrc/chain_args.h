@@ -65,6 +65,17 @@ struct StatusBlock {
     uint32_t pad[3];
 };
 
+// One record per tile, written when DEPSYNC_FLAG_TRACE is set (times in 10 ns ticks of the
+// constant 100 MHz counter).
+struct TraceRec {
+    uint32_t rel;        // first_ticket[stage] + row-major tile index
+    uint32_t where;      // stage | xcc << 8 | cu << 16 | se << 24
+    uint32_t tx, ty;
+    uint64_t t_start;    // tile drawn
+    uint64_t t_ready;    // first dependency satisfied (== t_start for tiles without one)
+    uint64_t t_end;      // stores and post done
+};
+
 struct ChainArgs {
     StageDesc st[3];
     uint32_t n_stages;
@@ -76,6 +87,8 @@ struct ChainArgs {
     uint32_t spin_limit;
     uint32_t delay_tile, delay_iters;
     StatusBlock* status;
+    TraceRec* trace;            // trace_cap records, or nullptr
+    uint32_t trace_cap;
 };
 
 }  // namespace depsync

@@ -186,6 +186,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const char* const zero_page = uni_ptr(s.zero_page);
 
     WaitCtx wctx{&args, rel_ticket, true};
+    const bool tracing = SYNC && (args.flags & DS_FLAG_TRACE) && args.trace != nullptr && rel_ticket < args.trace_cap;
+    uint64_t t_start = 0, t_ready = 0;
+    if (tracing) t_start = now_ticks();
 
     // ---- per-lane DMA source offsets (bytes from the operand base, K step 0) ----
     const uint32_t lrow = lane >> 3, lpos = lane & 7u;
@@ -305,6 +308,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     } else {
         issue_B(0);
     }
+    if (tracing) t_ready = now_ticks();
     issue_A(0);
 
     // The K loop.  Per step and wave: 4*FM groups of FN MFMAs.  The DMA instructions of the next
@@ -404,6 +408,12 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     }
 
     if (SYNC) post_tile(args, s, ty * s.grid_x + tx, tx, ty);
+    if (tracing && tid == 0) {
+        TraceRec r;
+        r.rel = rel_ticket; r.where = hw_where(DEP ? 1u : 0u); r.tx = tx; r.ty = ty;
+        r.t_start = t_start; r.t_ready = t_ready; r.t_end = now_ticks();
+        args.trace[rel_ticket] = r;
+    }
 }
 
 }  // namespace depsync

@@ -26,6 +26,7 @@ namespace depsync {
 #define DS_FLAG_COUNT 2u
 #define DS_FLAG_REVERSE_ORDER 4u
 #define DS_FLAG_HW_ORDER 8u
+#define DS_FLAG_TRACE 16u
 
 __device__ __forceinline__ uint32_t sem_load(const uint32_t* sem) {
     uint32_t v = __hip_atomic_load(sem, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -42,6 +43,16 @@ struct WaitCtx {
     uint32_t ticket;     // relative ticket of the tile (for the status block)
     bool ok;             // false once a bounded wait expired: the tile's stores are skipped
 };
+
+__device__ __forceinline__ uint64_t now_ticks() { return __builtin_amdgcn_s_memrealtime(); }
+
+__device__ __forceinline__ uint32_t hw_where(uint32_t stage) {
+    uint32_t xcc, hw;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID, 0, 32)" : "=s"(hw));
+    const uint32_t cu = (hw >> 8) & 15u, se = (hw >> 13) & 7u;
+    return stage | ((xcc & 15u) << 8) | (cu << 16) | (se << 24);
+}
 
 __device__ __forceinline__ void note_timeout(WaitCtx& w) {
     w.ok = false;
