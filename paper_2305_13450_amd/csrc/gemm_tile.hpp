@@ -289,8 +289,14 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     uint32_t seg_steps = 0, seg_left = 0;
     if constexpr (DEP) {
         switch (s.dep_kind) {
-            case DEP_TILE: case DEP_STRIDED: case DEP_CONV_TILE: seg_steps = s.prod_tn / 64; break;
+            case DEP_TILE: case DEP_STRIDED: seg_steps = s.prod_tn / 64; break;
             case DEP_CONV_TAPROW: seg_steps = 3 * cCin / 64; break;
+            case DEP_CONV_TILE: {   // starts of filter rows and of producer channel tiles inside them
+                uint32_t a = 3 * cCin / 64, b = s.prod_tn / 64;
+                while (b != 0) { const uint32_t r = a % b; a = b; b = r; }
+                seg_steps = a;
+                break;
+            }
             default: seg_steps = 0; break;
         }
         seg_steps = uni(seg_steps);

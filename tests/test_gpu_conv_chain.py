@@ -1,0 +1,99 @@
+"""GPU parity tests of dep_conv_chain (implicit-GeMM 3x3 convolutions) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+import inputs
+import oracle
+import paper_2305_13450_amd as ds
+from gpu_util import TOL_BF16, TOL_MID, mid_err, rel_err, run_conv_chain
+
+pytestmark = pytest.mark.gpu
+
+MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN]
+KINDS = [ds.STRIDEDSYNC, ds.ROWSYNC, ds.TILESYNC]
+
+
+def _oracle(t):
+    return oracle.conv_chain(inputs.to_f64(t["x"]), inputs.to_f64(t["w1"]), inputs.to_f64(t["w2"]))
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("tile", [ds.TILE_256x256, ds.TILE_128x128, ds.TILE_64x64])
+def test_conv_chain_small_images_all_policies(kind, tile):
+    # 3 images of 13x11 pixels (429 rows of the implicit GeMM: several row tiles, ragged tail, images
+    # that straddle tile boundaries), 64 -> 128 -> 64 channels
+    print(f"conv kind={kind} tile={tile}", flush=True)
+    t = inputs.conv(3, 13, 11, 64, 128, 64, seed=2)
+    mid_ref, out_ref = _oracle(t)
+    pol = ds.SyncPolicy(kind)
+    res = [run_conv_chain(t["x"], t["w1"], t["w2"], pol, mode, tile=tile) for mode in MODES]
+    for mid, out in res:
+        assert mid_err(mid, mid_ref) <= TOL_MID
+        assert rel_err(out, out_ref) <= TOL_BF16
+    for mid, out in res[1:]:
+        assert torch.equal(res[0][0], mid) and torch.equal(res[0][1], out)
+    pol.destroy()
+
+
+def test_conv_chain_one_pixel_wide_and_tiny_images():
+    for (B, H, W) in ((2, 1, 9), (2, 7, 1), (5, 2, 2), (1, 1, 1)):
+        t = inputs.conv(B, H, W, 64, 64, 64, seed=4)
+        mid_ref, out_ref = _oracle(t)
+        pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+        mid, out = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
+        assert mid_err(mid, mid_ref) <= TOL_MID and rel_err(out, out_ref) <= TOL_BF16, (B, H, W)
+        pol.destroy()
+
+
+def test_conv_chain_delayed_halo_row_is_waited_for():
+    # 28x28x128 image: a row tile of 64 pixels spans 2.3 image rows, so a consumer tile reads three or
+    # four producer row tiles (its own and the halo above and below).  Delaying a halo producer must
+    # not change the result under any policy.
+    t = inputs.conv(1, 28, 28, 128, 128, 128, seed=6)
+    mid_ref, out_ref = _oracle(t)
+    base = ds.SyncPolicy(ds.ROWSYNC)
+    _, out0 = run_conv_chain(t["x"], t["w1"], t["w2"], base, ds.MODE_STREAMSYNC, tile=ds.TILE_64x64)
+    assert rel_err(out0, out_ref) <= TOL_BF16
+    base.destroy()
+    for kind in KINDS:
+        for delay_tile in (1, 6, 13, 26):      # producer tiles (2 channel tiles per row tile)
+            pol = ds.SyncPolicy(kind, delay_tile=delay_tile, delay_iters=200)
+            _, out = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
+            assert torch.equal(out, out0), (kind, delay_tile)
+            pol.destroy()
+        pol = ds.SyncPolicy(kind, flags=ds.FLAG_REVERSE_ORDER)
+        _, out = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
+        assert torch.equal(out, out0), (kind, "reversed")
+        pol.destroy()
+
+
+def test_conv_chain_vgg_stage_sampled_pixels():
+    # VGG-19 stage (56x56, 256 -> 256), batch 4: output checked at sampled pixels the oracle evaluates
+    # one by one (corners, edges, image boundaries inside the batch, interior)
+    B, H, W, C = 4, 56, 56, 256
+    t = inputs.conv(B, H, W, C, C, C, seed=0)
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    outs = [run_conv_chain(t["x"], t["w1"], t["w2"], pol, mode)[1] for mode in (ds.MODE_FINE, ds.MODE_STREAMSYNC)]
+    assert torch.equal(outs[0], outs[1])
+    rng = np.random.default_rng(0)
+    pix = [(0, 0, 0), (0, 0, W - 1), (0, H - 1, 0), (B - 1, H - 1, W - 1), (1, 0, 0), (0, H - 1, W - 1), (2, 17, 0), (3, 0, 31)]
+    pix += [(int(rng.integers(B)), int(rng.integers(H)), int(rng.integers(W))) for _ in range(40)]
+    ref = oracle.conv_chain_pixels(inputs.to_f64(t["x"]), inputs.to_f64(t["w1"]), inputs.to_f64(t["w2"]), pix)
+    got = torch.stack([outs[0][b, y, x] for (b, y, x) in pix]).cpu().double().numpy()
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    assert float(np.max(np.abs(got - ref))) / rms <= TOL_BF16
+    pol.destroy()
+
+
+def test_conv_chain_rejects_bad_channels():
+    x = torch.zeros((1, 4, 4, 32), dtype=torch.bfloat16, device="cuda")
+    w1 = torch.zeros((64, 3, 3, 32), dtype=torch.bfloat16, device="cuda")
+    mid = torch.zeros((1, 4, 4, 64), dtype=torch.bfloat16, device="cuda")
+    w2 = torch.zeros((64, 3, 3, 64), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros((1, 4, 4, 64), dtype=torch.bfloat16, device="cuda")
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    with pytest.raises(ds.DepsyncError) as e:
+        ds.dep_conv_chain(x, w1, mid, w2, out, pol)
+    assert e.value.status == ds.EINVAL
+    pol.destroy()
