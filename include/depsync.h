@@ -59,8 +59,13 @@ typedef enum {
 typedef enum {
     DEPSYNC_MODE_FINE = 0,       /* two streams, per-tile semaphores (the paper's method)  */
     DEPSYNC_MODE_STREAMSYNC = 1, /* the same kernels on one stream (the paper's baseline)  */
-    DEPSYNC_MODE_PLAIN = 2       /* the same tile code with the sync hooks compiled out,
+    DEPSYNC_MODE_PLAIN = 2,      /* the same tile code with the sync hooks compiled out,
                                     one stream, hardware block order                        */
+    DEPSYNC_MODE_FUSED = 3       /* per-tile semaphores as in FINE, but ONE dispatch holding the
+                                    workgroups of all stages on stream_producer: no second
+                                    stream, no event fork/join (a few microseconds each on
+                                    this GPU).  Possible because every workgroup draws its
+                                    tile from the shared queues whichever launch it is from  */
 } depsync_mode;
 
 /* What sits between the two GeMMs. */
@@ -93,9 +98,11 @@ typedef enum {
 #define DEPSYNC_FLAG_REVERSE_ORDER 4u /* debug: hand producer tiles out in reverse order     */
 #define DEPSYNC_FLAG_HW_ORDER 8u      /* FINE/STREAMSYNC: take the tile from the hardware
                                          block index, no dispatch counter ("avoid custom tile
-                                         order", Section IV-C).  Only legal when producer and
-                                         consumer tiles all fit on the GPU at once; otherwise
-                                         DEPSYNC_EINVAL.                                      */
+                                         order", Section IV-C).  In FINE mode only legal when the
+                                         tiles of all stages fit on the GPU at once (otherwise
+                                         DEPSYNC_EINVAL); in FUSED mode always legal, because
+                                         each XCD starts the workgroups of one dispatch in index
+                                         order, producers first.                              */
 
 typedef struct {
     uint32_t stride;      /* STRIDEDSYNC on a GeMM chain: distance, in producer column tiles,

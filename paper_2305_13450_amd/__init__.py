@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(HERE, "libdepsync.so")
 
 # enums of include/depsync.h
 ROWSYNC, TILESYNC, STRIDEDSYNC = 0, 1, 2
-MODE_FINE, MODE_STREAMSYNC, MODE_PLAIN = 0, 1, 2
+MODE_FINE, MODE_STREAMSYNC, MODE_PLAIN, MODE_FUSED = 0, 1, 2, 3
 MID_NONE, MID_GELU, MID_RELU, MID_SWIGLU, MID_CAUSAL_ATTN = 0, 1, 2, 3, 4
 BF16, FP16 = 0, 1
 TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128, TILE_64x128, TILE_64x64 = range(7)

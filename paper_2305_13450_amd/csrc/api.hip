@@ -373,21 +373,29 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     if (sync && (a.flags & DEPSYNC_FLAG_HW_ORDER) && mode == DEPSYNC_MODE_FINE && total > (uint32_t)p.slots)
         return DEPSYNC_EINVAL;
 
-    if (mode == DEPSYNC_MODE_FINE) {
-        HIP_TRY(hipEventRecord(pol->ev_fork, sp));
-        HIP_TRY(hipStreamWaitEvent(sc, pol->ev_fork, 0));
-    }
-    uint32_t off = 0;
-    for (int s = 0; s < p.n_stages; ++s) {
-        // producer on the caller's stream; later stages on the second stream in FINE mode
-        hipStream_t st = (mode == DEPSYNC_MODE_FINE && s > 0) ? sc : sp;
-        a.block_offset = off;
-        HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, p.n_tiles[s], st, a));
-        off += p.n_tiles[s];
-    }
-    if (mode == DEPSYNC_MODE_FINE) {
-        HIP_TRY(hipEventRecord(pol->ev_join, sc));
-        HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join, 0));
+    if (mode == DEPSYNC_MODE_FUSED) {
+        // all stages in one dispatch; needs one macro-tile shape for the whole chain
+        for (int s = 1; s < p.n_stages; ++s)
+            if (p.tile[s] != p.tile[0]) return DEPSYNC_ENOTIMPL;
+        a.block_offset = 0;
+        HIP_TRY(launch_chain_kernel(p.tile[0], p.dtype, p.amode, true, total, sp, a));
+    } else {
+        if (mode == DEPSYNC_MODE_FINE) {
+            HIP_TRY(hipEventRecord(pol->ev_fork, sp));
+            HIP_TRY(hipStreamWaitEvent(sc, pol->ev_fork, 0));
+        }
+        uint32_t off = 0;
+        for (int s = 0; s < p.n_stages; ++s) {
+            // producer on the caller's stream; later stages on the second stream in FINE mode
+            hipStream_t st = (mode == DEPSYNC_MODE_FINE && s > 0) ? sc : sp;
+            a.block_offset = off;
+            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, p.n_tiles[s], st, a));
+            off += p.n_tiles[s];
+        }
+        if (mode == DEPSYNC_MODE_FINE) {
+            HIP_TRY(hipEventRecord(pol->ev_join, sc));
+            HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join, 0));
+        }
     }
     if (sync) {
         pol->epoch += 1;
@@ -500,7 +508,8 @@ int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_
 int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
                    void* stream_consumer) {
     if (!pol) return DEPSYNC_EINVAL;
-    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN)
+    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN &&
+        mode != DEPSYNC_MODE_FUSED)
         return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_gemm(d, pol, 0, p);
@@ -532,7 +541,8 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
 int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
                    void* stream_consumer) {
     if (!pol) return DEPSYNC_EINVAL;
-    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN)
+    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN &&
+        mode != DEPSYNC_MODE_FUSED)
         return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_conv(d, pol, 0, p);

@@ -32,13 +32,13 @@ __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs a
     gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds);
 }
 
-//                       TM   TN  WM WN  waves per SIMD
-using Cfg256x256 = TileCfg<256, 256, 2, 2, 1>;
-using Cfg256x128 = TileCfg<256, 128, 2, 2, 1>;
-using Cfg128x256 = TileCfg<128, 256, 2, 2, 1>;
-using Cfg128x128 = TileCfg<128, 128, 2, 2, 2>;
-using Cfg64x128 = TileCfg<64, 128, 2, 2, 2>;
-using Cfg64x64 = TileCfg<64, 64, 2, 2, 2>;
+//                        TM   TN  WM WN  workgroups per CU, LDS stages
+using Cfg256x256 = TileCfg<256, 256, 2, 2, 1, 2>;   // 128 KB
+using Cfg256x128 = TileCfg<256, 128, 2, 2, 1, 3>;   // 144 KB
+using Cfg128x256 = TileCfg<128, 256, 2, 2, 1, 3>;   // 144 KB
+using Cfg128x128 = TileCfg<128, 128, 2, 2, 2, 2>;   // 2 x 64 KB
+using Cfg64x128 = TileCfg<64, 128, 2, 2, 2, 3>;     // 2 x 72 KB
+using Cfg64x64 = TileCfg<64, 64, 2, 2, 2, 4>;       // 2 x 64 KB
 
 template <class Cfg, typename T, uint32_t AMODE>
 static hipError_t launch_cfg(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {

@@ -24,12 +24,12 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int TM_, int TN_, int WM_, int WN_, int MINB_>
+template <int TM_, int TN_, int WM_, int WN_, int MINB_, int NSTAGE_>
 struct TileCfg {
     static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_, MINB = MINB_;
     static constexpr int BK = 64;                     // K elements per pipeline step
     static constexpr int ROWB = BK * 2;               // bytes per LDS row
-    static constexpr int NSTAGE = 2;
+    static constexpr int NSTAGE = NSTAGE_;               // LDS stages: NSTAGE-1 K steps in flight
     static constexpr int WTM = TM / WM, WTN = TN / WN;  // wave sub-tile
     static constexpr int FM = WTM / 32, FN = WTN / 32;  // 32x32 blocks per wave
     static constexpr int NIA = TM / 32, NIB = TN / 32;  // 1 KB DMA instructions per wave per step
@@ -37,6 +37,7 @@ struct TileCfg {
     static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
     static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
     static_assert(WM * WN == 4, "four waves per workgroup");
+    static_assert(NSTAGE >= 2 && MINB * LDS_BYTES <= 160 * 1024, "stages must fit the 160 KB LDS");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
     static_assert(TM % 32 == 0 && TN % 32 == 0, "each wave issues whole 8-row DMA groups");
 };
@@ -286,7 +287,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const bool reorder = !(args.flags & DS_FLAG_NO_REORDER);
 
     // Dependency segments start at multiples of seg_steps K steps (0: only at step 0).
-    uint32_t seg_steps = 0, seg_left = 0;
+    uint32_t seg_steps = 0, seg_next = 0;
     if constexpr (DEP) {
         switch (s.dep_kind) {
             case DEP_TILE: case DEP_STRIDED: seg_steps = s.prod_tn / 64; break;
@@ -300,48 +301,53 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
             default: seg_steps = 0; break;
         }
         seg_steps = uni(seg_steps);
-        seg_left = seg_steps;
     }
-
-    // ---- prologue: K step 0 into stage 0 ----
-    set_next(0);
-    if constexpr (DEP) {
-        DepRange dr;
-        const bool need = dep_segment(s, m0, TM, 0, dr);
-        if (need && !reorder) dep_wait(wctx, s, dr, true);
-        issue_B(0);
-        if (need && reorder) dep_wait(wctx, s, dr, true);
-    } else {
-        issue_B(0);
-    }
-    if (tracing) t_ready = now_ticks();
-    issue_A(0);
-
-    // The K loop.  Per step and wave: 4*FM groups of FN MFMAs.  The DMA instructions of the next
-    // step are spread over those groups (a wave that issues them all at once sits at the memory
-    // pipeline's queue and starves its matrix unit), weights first; the fragments of the next
-    // 16-wide K slice are read from LDS while the current slice's MFMAs run.  The body is free of
-    // branches: the last step simply re-requests its own slice into the idle stage.
-    constexpr int NG = 4 * FM;            // MFMA groups per step
-    constexpr int ND = NIA + NIB;         // DMA instructions per step
-    for (uint32_t kt = 0; kt < KT; ++kt) {
-        const uint32_t cur = kt & 1u, nxt = cur ^ 1u;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();   // stage `cur` is complete; nobody still reads stage `nxt`
-
-        set_next(min(kt + 1, KT - 1));
+    // Called before the A slice of K step k (< KT) is requested into `stage`: if a dependency
+    // segment starts there, make sure its producer tiles have posted.  When they have not, the
+    // weights of the step are requested first (the load/wait reordering) and then the wave
+    // really waits; the caller requests the slice (and, harmlessly, the weights again) afterwards.
+    auto dep_before_request = [&](uint32_t k, uint32_t stage) __attribute__((always_inline)) {
         if constexpr (DEP) {
-            if (seg_steps != 0 && --seg_left == 0) {
-                seg_left = seg_steps;
+            if (k == seg_next) {
+                seg_next = seg_steps ? seg_next + seg_steps : 0xffffffffu;
                 DepRange dr;
-                if (kt + 1 < KT && dep_segment(s, m0, TM, kt + 1, dr) && !dep_wait(wctx, s, dr, false)) {
-                    // The producer is not there yet.  Request the weights of the next step first
-                    // (the load/wait reordering), then really wait; the body requests the A slice.
-                    if (reorder) issue_B(nxt);
+                if (dep_segment(s, m0, TM, k, dr) && !dep_wait(wctx, s, dr, false)) {
+                    if (reorder) issue_B(stage);
                     dep_wait(wctx, s, dr, true);
                 }
             }
         }
+    };
+
+    // ---- prologue: K steps 0 .. NST-2 into stages 0 .. NST-2 ----
+    constexpr int NST = Cfg::NSTAGE;
+    constexpr int NG = 4 * FM;            // MFMA groups per step
+    constexpr int ND = NIA + NIB;         // DMA instructions per step
+    static_assert((NST - 2) * ND <= 48, "outstanding DMA instructions must fit the vmcnt counter");
+#pragma unroll
+    for (int p = 0; p < NST - 1; ++p) {
+        set_next(min((uint32_t)p, KT - 1));
+        if ((uint32_t)p < KT) dep_before_request(p, p);
+        if (p == 0 && tracing) t_ready = now_ticks();
+        issue_B(p);
+        issue_A(p);
+    }
+
+    // The K loop.  Per step and wave: 4*FM groups of FN MFMAs.  The DMA instructions of the step
+    // NST-1 ahead are spread over those groups (a wave that issues them all at once sits at the
+    // memory pipeline's queue and starves its matrix unit), weights first; the fragments of the
+    // next 16-wide K slice are read from LDS while the current slice's MFMAs run.  The body is
+    // free of branches: past the end the last slice is simply requested again into an idle stage.
+    uint32_t cur = 0, req = NST - 1;      // stage being computed on / stage being filled
+    for (uint32_t kt = 0; kt < KT; ++kt) {
+        // step kt's DMA group is complete when at most the NST-2 younger groups are outstanding
+        // (a bare s_barrier: __syncthreads() would also wait for the younger groups)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NST - 2) * ND) : "memory");
+        // now stage `cur` is complete for all waves and nobody still reads stage `req`
+
+        const uint32_t kreq = kt + (NST - 1);
+        set_next(min(kreq, KT - 1));
+        if (kreq < KT) dep_before_request(kreq, req);
 
         const char* la = lds + cur * Cfg::STAGE_BYTES;
         const char* lb = la + Cfg::A_BYTES;
@@ -364,14 +370,18 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                 }
 #pragma unroll
                 for (int d = (g * ND) / NG; d < ((g + 1) * ND) / NG; ++d) {
-                    if (d < NIB) dma_B(nxt, d);
-                    else dma_A(nxt, d - NIB);
+                    if (d < NIB) dma_B(req, d);
+                    else dma_A(req, d - NIB);
                 }
 #pragma unroll
                 for (int j = 0; j < FN; ++j) acc[i][j] = M::mma(af[c][i], bf[c][j], acc[i][j]);
             }
         }
+        cur = (cur + 1 == NST) ? 0 : cur + 1;
+        req = (req + 1 == NST) ? 0 : req + 1;
     }
+    // every DMA into LDS has landed before the staging area is given up
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
     // ---- epilogue: activation, round to 16 bits, store ----
     // Accumulator layout of the 32x32 block: lane holds column (lane % 32) and rows

@@ -69,8 +69,16 @@ __device__ __forceinline__ void sem_wait(WaitCtx& w, const uint32_t* sem, uint32
     uint32_t v = first;
     const uint32_t limit = w.args->spin_limit;
     uint32_t spins = 0;
+    uint32_t nap = 0;
     while (!sem_reached(v, target)) {
-        __builtin_amdgcn_s_sleep(4);
+        // back off: 8, 16, 32, 64, then 127 units of 64 clocks (about 3 us) between polls, so that
+        // hundreds of waiting waves do not queue up on the semaphore's memory channel
+        if (nap == 0) __builtin_amdgcn_s_sleep(8);
+        else if (nap == 1) __builtin_amdgcn_s_sleep(16);
+        else if (nap == 2) __builtin_amdgcn_s_sleep(32);
+        else if (nap == 3) __builtin_amdgcn_s_sleep(64);
+        else __builtin_amdgcn_s_sleep(127);
+        ++nap;
         v = sem_load(sem);
         if (limit != 0 && ++spins >= limit) {
             if (!sem_reached(v, target)) note_timeout(w);
@@ -164,34 +172,43 @@ __device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_sl
         const uint32_t home = xcc_id();
         uint32_t stage = 0, tx = 0, ty = 0;
         bool found = false;
+        // Workgroups that were launched for the first stage go straight for their XCD's queue of
+        // that stage (one atomic in the common case).  Otherwise a workgroup looks at a stage's
+        // eight counters and only then increments one that still has entries: a failed
+        // increment (undone at once) can happen at most once per queue, so a crowd of
+        // workgroups arriving together cannot turn into a storm of atomics on empty queues.
+        bool direct = a.block_offset + blockIdx.x < a.first_ticket[1];
         for (uint32_t s = 0; s < a.n_stages && !found; ++s) {
             const StageDesc& st = a.st[s];
             uint32_t* cnt = a.ticket + 8u * s;
-            // one look at the stage's eight counters: skip a stage that is already handed out
-            uint32_t c[8];
+            for (uint32_t attempt = 0; attempt < 10 && !found; ++attempt) {
+                uint32_t q = home;
+                if (!(direct && s == 0 && attempt == 0)) {
+                    uint32_t c[8];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) c[q] = __hip_atomic_load(cnt + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            bool left = false;
+                    for (int j = 0; j < 8; ++j)
+                        c[j] = __hip_atomic_load(cnt + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    uint32_t avail = 0;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) {
-                const uint32_t len = queue_len(st, q);
-                left = left || (c[q] - a.epoch * len < len);
-            }
-            if (!left) continue;
-            for (uint32_t k = 0; k < 8; ++k) {
-                const uint32_t q = (home + k) & 7u;
+                    for (int j = 0; j < 8; ++j) {
+                        const uint32_t len = queue_len(st, j);
+                        if (c[j] - a.epoch * len < len) avail |= 1u << j;
+                    }
+                    if (avail == 0) break;                       // stage handed out: next stage
+                    const uint32_t rot = (avail >> home) | (avail << (8u - home));
+                    q = (home + (uint32_t)__builtin_ctz(rot & 0xffu)) & 7u;   // first non-empty from home
+                }
                 const uint32_t ncol = (st.grid_x + 7u - q) >> 3, len = ncol * st.grid_y;
                 if (len == 0) continue;
                 uint32_t i = __hip_atomic_fetch_add(cnt + q, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
                              a.epoch * len;
-                if (i >= len) {   // queue exhausted: undo and try the next XCD's queue
+                if (i >= len) {   // emptied in the meantime: undo and look again
                     __hip_atomic_fetch_sub(cnt + q, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     continue;
                 }
                 if (s == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
                 stage = s; ty = i / ncol; tx = q + 8u * (i % ncol);
                 found = true;
-                break;
             }
         }
         lds_slot[0] = stage; lds_slot[1] = tx; lds_slot[2] = ty; lds_slot[3] = found ? 1u : 0u;

@@ -10,7 +10,7 @@ from gpu_util import TOL_BF16, TOL_MID, mid_err, rel_err, run_conv_chain
 
 pytestmark = pytest.mark.gpu
 
-MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN]
+MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN, ds.MODE_FUSED]
 KINDS = [ds.STRIDEDSYNC, ds.ROWSYNC, ds.TILESYNC]
 
 

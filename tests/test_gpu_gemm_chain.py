@@ -12,7 +12,7 @@ from gpu_util import TOL_BF16, TOL_FP16, TOL_MID, mid_err, rel_err, run_gemm_cha
 pytestmark = pytest.mark.gpu
 
 ALL_TILES = [ds.TILE_256x256, ds.TILE_256x128, ds.TILE_128x256, ds.TILE_128x128, ds.TILE_64x128, ds.TILE_64x64]
-MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN]
+MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN, ds.MODE_FUSED]
 
 
 @pytest.fixture(scope="module")
@@ -32,7 +32,7 @@ def test_cfg1_rowsync_matches_oracle_and_is_bit_exact(cfg1):
         assert mid_err(H, Href) <= TOL_MID
         assert rel_err(Y, Yref) <= TOL_BF16
         outs[mode] = (H, Y)
-    for mode in (ds.MODE_STREAMSYNC, ds.MODE_PLAIN):
+    for mode in (ds.MODE_STREAMSYNC, ds.MODE_PLAIN, ds.MODE_FUSED):
         assert torch.equal(outs[ds.MODE_FINE][0], outs[mode][0])
         assert torch.equal(outs[ds.MODE_FINE][1], outs[mode][1])
     pol.destroy()
@@ -102,7 +102,7 @@ def test_swiglu_chain_matches_oracle():
             # RMS out, where one bf16 rounding alone exceeds 2e-2 of the RMS: bound the error beyond
             # the output's own rounding instead (stricter everywhere but in that extreme tail)
             assert mid_err(H, Href) <= TOL_MID and mid_err(Y, Yref) <= 1e-2
-        assert torch.equal(res[0][1], res[1][1]) and torch.equal(res[0][1], res[2][1])
+        assert all(torch.equal(res[0][1], r[1]) for r in res[1:])
         pol.destroy()
 
 
@@ -170,7 +170,8 @@ def test_changing_inputs_on_reused_buffers_never_reads_stale_intermediate():
         outs = []
         for it in range(24):                      # enqueue back to back, no host sync in between
             Yi = torch.empty_like(Y)
-            ds.dep_gemm_chain(Xs[it & 1], W1t, H, W2t, Yi, p2, mode=ds.MODE_FINE, tile=ds.TILE_128x128)
+            ds.dep_gemm_chain(Xs[it & 1], W1t, H, W2t, Yi, p2, mode=ds.MODE_FUSED if it % 3 == 2 else ds.MODE_FINE,
+                              tile=ds.TILE_128x128)
             outs.append(Yi)
         torch.cuda.synchronize()
         for it, Yi in enumerate(outs):
@@ -189,10 +190,15 @@ def test_delayed_and_reversed_producers_do_not_change_the_result():
     for kind in (ds.TILESYNC, ds.ROWSYNC):
         for kw in (dict(delay_tile=1, delay_iters=300), dict(delay_tile=37, delay_iters=300),
                    dict(flags=ds.FLAG_REVERSE_ORDER), dict(flags=ds.FLAG_NO_REORDER)):
-            pol = ds.SyncPolicy(kind, **kw)
-            _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
-            assert torch.equal(Y, Y0), (kind, kw)
-            pol.destroy()
+            for mode in (ds.MODE_FINE, ds.MODE_FUSED):
+                pol = ds.SyncPolicy(kind, **kw)
+                _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode, tile=ds.TILE_64x64)
+                assert torch.equal(Y, Y0), (kind, kw, mode)
+                pol.destroy()
+        pol = ds.SyncPolicy(kind, flags=ds.FLAG_HW_ORDER, delay_tile=5, delay_iters=300)
+        _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FUSED, tile=ds.TILE_64x64)
+        assert torch.equal(Y, Y0), (kind, "fused, hardware order")
+        pol.destroy()
 
 
 def test_bounded_wait_reports_timeout_and_reset_recovers():
