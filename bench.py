@@ -25,8 +25,8 @@ def parse():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--m", type=int, default=2048, help="tokens (rows of X)")
-    ap.add_argument("--workload", default="gpt3_mlp", choices=["gpt3_mlp", "llama_mlp", "cfg1"])
-    ap.add_argument("--policy", default="auto", choices=["auto", "row", "tile"])
+    ap.add_argument("--workload", default="gpt3_mlp", choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "cfg1"])
+    ap.add_argument("--policy", default="auto", choices=["auto", "row", "tile", "strided"])
     ap.add_argument("--tile", type=int, default=0, help="depsync_tile id, 0 = library's choice")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=384, help="rows of X the CPU oracle is timed on")
@@ -67,6 +67,7 @@ def main():
     n_cu, clock_khz = ds.device_info()
 
     M = args.m
+    attn = None
     if args.workload == "gpt3_mlp":
         shape = dict(M=M, K1=12288, N1=6144, N2=12288); mid = ds.MID_GELU
         t = inputs.mlp(**shape)
@@ -77,6 +78,13 @@ def main():
         t = inputs.swiglu(**shape)
         W1 = t["Wgu"]
         name = f"LLaMA-65B MLP shard X[{M}x8192] [Wg|Wu][8192x5504] SwiGLU W2[2752x8192] bf16"
+    elif args.workload == "gpt3_attn":
+        c = inputs.CFG4; mid = ds.MID_CAUSAL_ATTN
+        t = inputs.attention(M, c["K1"], c["heads"], c["d"], c["N2"])
+        W1 = t["Wqkv"]; t["W2"] = t["Wo"]
+        attn = dict(batch=1, seq=M, heads=c["heads"], head_dim=c["d"])
+        name = (f"GPT-3 attention shard X[{M}x12288] Wqkv[12288x4608] causal attention 12 heads x 128 "
+                f"(batch 1, seq {M}) Wo[1536x12288] bf16")
     else:
         shape = dict(inputs.CFG1); M = shape["M"]; mid = ds.MID_GELU
         t = inputs.mlp(**shape)
@@ -88,10 +96,13 @@ def main():
     n1 = W1t.shape[0] // 2 if mid == ds.MID_SWIGLU else W1t.shape[0]
     H = torch.empty((M, n1), dtype=X.dtype, device="cuda")
     Y = torch.empty((M, W2t.shape[0]), dtype=X.dtype, device="cuda")
+    extra = {}
+    if attn:
+        extra = dict(attn, T=torch.empty((M, attn["heads"] * attn["head_dim"]), dtype=X.dtype, device="cuda"))
 
     sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
-    kinds = {"row": ds.ROWSYNC, "tile": ds.TILESYNC}
-    pol_names = ["row", "tile"] if args.policy == "auto" else [args.policy]
+    kinds = {"row": ds.ROWSYNC, "tile": ds.TILESYNC, "strided": ds.STRIDEDSYNC}
+    pol_names = (["row", "tile", "strided"] if attn else ["row", "tile"]) if args.policy == "auto" else [args.policy]
     modes = {"fine": ds.MODE_FINE, "fused": ds.MODE_FUSED, "streamsync": ds.MODE_STREAMSYNC, "plain": ds.MODE_PLAIN}
     want = [m for m in args.modes.split(",") if m]
 
@@ -99,13 +110,13 @@ def main():
     plan = None
     for pn in pol_names:
         pol = ds.SyncPolicy(kinds[pn])
-        plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol, mid=mid, tile=args.tile)
+        plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol, mid=mid, tile=args.tile, **extra)
         for mn in want:
             if mn not in ("fine", "fused") and pn != pol_names[0]:
                 continue   # stream-sync and plain do not depend on the policy's granularity much
             def call(mode=modes[mn]):
                 ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=mode, mid=mid, tile=args.tile,
-                                  stream_producer=sp, stream_consumer=sc)
+                                  stream_producer=sp, stream_consumer=sc, **extra)
             us, wall_us = time_chain(ds, torch, call, sp, args.steps, args.warmup)
             results[(pn, mn)] = (us, wall_us)
         pol.status()
@@ -131,7 +142,7 @@ def main():
     roof["per_launch"] = {"flops": flops, "bytes": nbytes, "duration_us": lat}
 
     out = {
-        "metric": "dependent-chain latency, fine-grained sync, best of {two-stream, one-dispatch} x {RowSync, TileSync} (mean of steps)",
+        "metric": "dependent-chain latency, fine-grained sync, best of {two-stream, one-dispatch} x sync policies (mean of steps)",
         "value": lat, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": lat / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
@@ -152,14 +163,18 @@ def main():
         Xs = inputs.to_f64(t["X"][:rows])
         W1f, W2f = inputs.to_f64(W1), inputs.to_f64(t["W2"])
         t0 = time.perf_counter()
-        if mid == ds.MID_SWIGLU:
+        if attn:
+            # causal: the first `rows` tokens of the sequence need nothing from later tokens
+            oracle.attn_chain(Xs, W1f, W2f, 1, rows, attn["heads"], attn["head_dim"])
+        elif mid == ds.MID_SWIGLU:
             oracle.swiglu_chain(Xs, W1f, W2f)
         else:
             oracle.gemm_chain(Xs, W1f, W2f, oracle.ACT_GELU)
         dt = time.perf_counter() - t0
         out["cpu_baseline"] = {
             "value": dt * 1e6 * (M / rows), "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"fp64 oracle timed on the first {rows} of {M} rows of X (rows are independent); "
+            "sample": f"fp64 oracle timed on the first {rows} of {M} rows of X (rows are independent"
+                      f"{', the attention of a prefix being a prefix of the attention' if attn else ''}); "
                       f"{dt:.2f} s measured, scaled by {M}/{rows} to the full chain",
             "measured_s": dt, "gflops": flops * (rows / M) / dt / 1e9,
         }

@@ -66,6 +66,7 @@ struct Plan {
     uint32_t sem_count[3];
     uint32_t sem_value[3];
     uint32_t stride[3];
+    uint32_t out_tm[3], out_tn[3];   // rows / columns of its own output one tile of stage s covers
     uint32_t n_sems;
     int slots;
     double flops, bytes;
@@ -140,12 +141,20 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     if (d->M <= 0 || d->K1 <= 0 || d->N1 <= 0 || d->N2 <= 0) return DEPSYNC_EINVAL;
     if (d->dtype != DEPSYNC_BF16 && d->dtype != DEPSYNC_FP16) return DEPSYNC_EINVAL;
     if (d->mid < DEPSYNC_MID_NONE || d->mid > DEPSYNC_MID_CAUSAL_ATTN) return DEPSYNC_EINVAL;
-    if (d->mid == DEPSYNC_MID_CAUSAL_ATTN) return DEPSYNC_ENOTIMPL;
     if (!d->X || !d->W1t || !d->H || !d->W2t || !d->Y) return DEPSYNC_EINVAL;
     if (!aligned16(d->X) || !aligned16(d->W1t) || !aligned16(d->H) || !aligned16(d->W2t) || !aligned16(d->Y))
         return DEPSYNC_EINVAL;
     const bool gate_up = d->mid == DEPSYNC_MID_SWIGLU;
-    const uint32_t K2 = (uint32_t)d->N1;
+    const bool attn = d->mid == DEPSYNC_MID_CAUSAL_ATTN;
+    const uint32_t E = attn ? (uint32_t)d->heads * 128u : 0u;
+    if (attn) {
+        if (d->head_dim != 128) return d->head_dim > 0 ? DEPSYNC_ENOTIMPL : DEPSYNC_EINVAL;
+        if (d->batch <= 0 || d->seq <= 0 || d->heads <= 0) return DEPSYNC_EINVAL;
+        if ((int64_t)d->batch * d->seq != d->M || (int64_t)d->N1 != 3ll * E) return DEPSYNC_EINVAL;
+        if (!d->T || (reinterpret_cast<uintptr_t>(d->T) & 127u) || d->ldt < (int64_t)E || d->ldt % 64) return DEPSYNC_EINVAL;
+        if (d->batch > 1 && d->seq % 128) return DEPSYNC_ENOTIMPL;   // query blocks must not straddle sequences
+    }
+    const uint32_t K2 = attn ? E : (uint32_t)d->N1;
     if (d->K1 % 64 || K2 % 64) return DEPSYNC_EINVAL;
     if (d->ldx < d->K1 || d->ldw1 < d->K1 || d->ldh < d->N1 || d->ldw2 < (int64_t)K2 || d->ldy < d->N2)
         return DEPSYNC_EINVAL;
@@ -171,43 +180,68 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     if (gate_up && ts->wave_cols < 64) return DEPSYNC_EINVAL;
 
     std::memset(&p, 0, sizeof(p));
-    p.n_stages = 2;
+    const int last = attn ? 2 : 1;
+    p.n_stages = last + 1;
     p.amode = A_DENSE;
     p.dtype = d->dtype;
-    p.tile[0] = p.tile[1] = tile;
+    for (int s = 0; s < p.n_stages; ++s) p.tile[s] = tile;
     const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
-    p.grid_y[0] = p.grid_y[1] = cdiv(d->M, ts->rows);
+    p.grid_y[0] = p.grid_y[last] = cdiv(d->M, ts->rows);
     p.grid_x[0] = cdiv(d->N1, tn1);
-    p.grid_x[1] = cdiv(d->N2, ts->cols);
-    for (int s = 0; s < 2; ++s) p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
-
-    const int kind = pol ? pol->kind : DEPSYNC_ROWSYNC;
-    p.dep_kind[1] = policy_dep_kind_gemm(kind);
-    p.sem_off[1] = 0;
-    if (p.dep_kind[1] == DEP_ROW) {
-        p.sem_count[1] = p.grid_y[0];
-        p.sem_value[1] = p.grid_x[0];
-    } else if (p.dep_kind[1] == DEP_TILE) {
-        p.sem_count[1] = p.n_tiles[0];
-        p.sem_value[1] = 1;
-    } else {
-        uint32_t stride = pol ? pol->params.stride : 0;
-        if (stride == 0) {
-            const uint32_t count = (pol && pol->params.count) ? pol->params.count : 3;
-            if (p.grid_x[0] % count) return DEPSYNC_EINVAL;
-            stride = p.grid_x[0] / count;
-        }
-        if (stride == 0 || p.grid_x[0] % stride) return DEPSYNC_EINVAL;
-        p.stride[1] = stride;
-        p.sem_count[1] = p.grid_y[0] * stride;
-        p.sem_value[1] = p.grid_x[0] / stride;
+    p.grid_x[last] = cdiv(d->N2, ts->cols);
+    p.out_tm[0] = ts->rows; p.out_tn[0] = tn1;
+    if (attn) {   // middle stage: one tile per (head, block of 128 query rows)
+        p.grid_x[1] = d->heads;
+        p.grid_y[1] = (uint32_t)d->batch * cdiv(d->seq, 128);
+        p.out_tm[1] = 128; p.out_tn[1] = 128;
     }
-    p.n_sems = p.sem_count[1];
+    for (int s = 0; s < p.n_stages; ++s) p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
+
+    // dependency of stage s on stage s-1, per policy
+    const int kind = pol ? pol->kind : DEPSYNC_ROWSYNC;
+    uint32_t off = 0;
+    for (int s = 1; s < p.n_stages; ++s) {
+        uint32_t dk = policy_dep_kind_gemm(kind);
+        const uint32_t pgx = p.grid_x[s - 1], pgy = p.grid_y[s - 1];
+        if (attn && s == 2 && dk == DEP_STRIDED) dk = DEP_TILE;   // "Strided + TileSync" (Section V-C)
+        if (attn && s == 1 && dk == DEP_STRIDED && E % p.out_tn[0]) dk = DEP_TILE;
+        p.dep_kind[s] = dk;
+        p.sem_off[s] = off;
+        if (dk == DEP_ROW) {
+            p.sem_count[s] = pgy;
+            p.sem_value[s] = pgx;
+        } else if (dk == DEP_TILE) {
+            p.sem_count[s] = pgx * pgy;
+            p.sem_value[s] = 1;
+        } else {
+            uint32_t stride;
+            if (attn) {
+                stride = E / p.out_tn[0];               // Q, K and V column tiles of a head share a semaphore
+            } else {
+                stride = pol ? pol->params.stride : 0;
+                if (stride == 0) {
+                    const uint32_t count = (pol && pol->params.count) ? pol->params.count : 3;
+                    if (pgx % count) return DEPSYNC_EINVAL;
+                    stride = pgx / count;
+                }
+            }
+            if (stride == 0 || pgx % stride) return DEPSYNC_EINVAL;
+            p.stride[s] = stride;
+            p.sem_count[s] = pgy * stride;
+            p.sem_value[s] = pgx / stride;
+        }
+        off += p.sem_count[s];
+    }
+    p.n_sems = off;
     if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
     const double M = d->M, w1c = gate_up ? 2.0 * d->N1 : d->N1;
     p.flops = 2.0 * M * w1c * d->K1 + 2.0 * M * d->N2 * K2;
     p.bytes = 2.0 * (M * d->K1 + w1c * d->K1 + 2.0 * M * d->N1 + (double)d->N2 * K2 + M * d->N2);
+    if (attn) {   // causal: each of Q K^T and P V does seq*(seq+1)/2 * d multiply-adds per head and sequence
+        p.flops += 2.0 * 2.0 * d->batch * d->heads * 128.0 * 0.5 * (double)d->seq * ((double)d->seq + 1.0);
+        p.bytes += 2.0 * 2.0 * M * E;   // T written and read once
+    }
     return DEPSYNC_OK;
 }
 
@@ -249,6 +283,7 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     p.grid_y[0] = p.grid_y[1] = cdiv(M, ts->rows);
     p.grid_x[0] = cdiv(d->K1, ts->cols);
     p.grid_x[1] = cdiv(d->K2, ts->cols);
+    p.out_tm[0] = ts->rows; p.out_tn[0] = ts->cols;
     for (int s = 0; s < 2; ++s) p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
     const int kind = pol ? pol->kind : DEPSYNC_STRIDEDSYNC;
     p.dep_kind[1] = policy_dep_kind_conv(kind);
@@ -344,12 +379,11 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
         st.zero_page = pol->ws + WS_ZERO_PAGE;
         st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
         if (s > 0) {
-            const TileShape* pts = tile_shape(p.tile[s - 1]);
             st.sems = pol->ws + WS_SEMS + p.sem_off[s];
             st.sem_value = p.sem_value[s];
             st.sem_target_base = epoch * p.sem_value[s];
-            st.prod_tm = pts->rows;
-            st.prod_tn = (a.st[s - 1].bmode == B_GATE_UP) ? pts->cols / 2 : pts->cols;
+            st.prod_tm = p.out_tm[s - 1];
+            st.prod_tn = p.out_tn[s - 1];
             st.prod_grid_x = p.grid_x[s - 1];
             st.prod_grid_y = p.grid_y[s - 1];
             st.stride = p.stride[s];
@@ -529,10 +563,19 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
     s0.op = OP_GEMM; s0.amode = A_DENSE; s0.bmode = gate_up ? B_GATE_UP : B_DENSE;
     s0.act = d->mid == DEPSYNC_MID_GELU ? ACT_GELU : d->mid == DEPSYNC_MID_RELU ? ACT_RELU
              : gate_up ? ACT_SWIGLU : ACT_NONE;
-    StageDesc& s1 = a.st[1];
-    s1.A = d->H; s1.B = d->W2t; s1.C = d->Y;
-    s1.M = d->M; s1.N = d->N2; s1.K = d->N1;
-    s1.lda = (uint32_t)d->ldh; s1.ldb = (uint32_t)d->ldw2; s1.ldc = (uint32_t)d->ldy;
+    const bool attn = d->mid == DEPSYNC_MID_CAUSAL_ATTN;
+    if (attn) {
+        StageDesc& sa = a.st[1];
+        sa.A = d->H; sa.C = d->T;
+        sa.M = d->M; sa.N = d->heads * 128; sa.K = 128;
+        sa.lda = (uint32_t)d->ldh; sa.ldc = (uint32_t)d->ldt;
+        sa.op = OP_ATTN; sa.amode = A_DENSE; sa.bmode = B_DENSE; sa.act = ACT_NONE;
+        sa.batch = d->batch; sa.seq = d->seq; sa.heads = d->heads; sa.head_dim = 128;
+    }
+    StageDesc& s1 = a.st[attn ? 2 : 1];
+    s1.A = attn ? d->T : d->H; s1.B = d->W2t; s1.C = d->Y;
+    s1.M = d->M; s1.N = d->N2; s1.K = attn ? d->heads * 128 : d->N1;
+    s1.lda = (uint32_t)(attn ? d->ldt : d->ldh); s1.ldb = (uint32_t)d->ldw2; s1.ldc = (uint32_t)d->ldy;
     s1.op = OP_GEMM; s1.amode = A_DENSE; s1.bmode = B_DENSE; s1.act = ACT_NONE;
     fill_common(a, pol, p, epoch);
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);

@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "chain_args.h"
+#include "attn_tile.hpp"
 #include "gemm_tile.hpp"
 #include "sync_device.hpp"
 
@@ -18,11 +19,18 @@ template <class Cfg, typename T, bool SYNC, uint32_t AMODE>
 __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs args) {
     // One LDS object only: with a second one the compiler can no longer tell the DMA writes
     // into the idle stage from the fragment reads of the current stage and serialises them.
+    static_assert(Cfg::LDS_BYTES >= ATT_LDS_BYTES, "the attention tile stages its K and V blocks in the same LDS");
     __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
 
     const TileId t = draw_tile<SYNC>(args, reinterpret_cast<uint32_t*>(lds));
     if (t.rel == 0xffffffffu) return;
     const StageDesc& s = args.st[t.stage];
+    if constexpr (AMODE == A_DENSE) {
+        if (s.op == OP_ATTN) {   // middle stage of the attention chain
+            attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds);
+            return;
+        }
+    }
     if constexpr (SYNC) {
         if (s.dep_kind != DEP_NONE) {
             gemm_tile<Cfg, T, true, AMODE, true>(args, s, t.tx, t.ty, t.rel, lds);

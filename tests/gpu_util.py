@@ -30,6 +30,16 @@ def mid_err(got: torch.Tensor, ref: np.ndarray, ulp: float = 2.0 ** -8) -> float
 TOL_MID = 2e-3
 
 
+def row_err(got: torch.Tensor, ref: np.ndarray) -> float:
+    """Largest error of any row, normalised by the RMS of THAT row of the oracle's output.  For the
+    attention block the rows (tokens) differ in scale by the square root of their position (the
+    first token's output is one row of V, a late token's an average of many), so one 16-bit
+    rounding of a large early row already exceeds 2e-2 of the RMS of the whole tensor."""
+    g = got.detach().to("cpu").to(torch.float64).numpy()
+    rms = np.sqrt(np.mean(ref * ref, axis=1))
+    return float(np.max(np.max(np.abs(g - ref), axis=1) / np.maximum(rms, 1e-30)))
+
+
 def dev(t: torch.Tensor) -> torch.Tensor:
     return t.to("cuda")
 
@@ -65,3 +75,23 @@ def run_conv_chain(x, w1, w2, policy, mode, tile=ds.TILE_AUTO, poison=True):
     ds.dep_conv_chain(xd, w1d, mid, w2d, out, policy, mode=mode, tile=tile)
     torch.cuda.synchronize()
     return mid, out
+
+
+def run_attn_chain(X, Wqkv, Wo, batch, seq, heads, policy, mode, tile=ds.TILE_AUTO, poison=True, streams=None):
+    """Attention block: X[M,K1], Wqkv[K1,3E], Wo[E,N2] with E = 128 * heads.  Returns (QKV, T, Y)."""
+    Xd = dev(X)
+    Wqkv_t = dev(Wqkv).t().contiguous()
+    Wo_t = dev(Wo).t().contiguous()
+    M, E = X.shape[0], heads * 128
+    QKV = torch.empty((M, 3 * E), dtype=X.dtype, device="cuda")
+    T = torch.empty((M, E), dtype=X.dtype, device="cuda")
+    Y = torch.empty((M, Wo.shape[1]), dtype=X.dtype, device="cuda")
+    if poison:
+        for t in (QKV, T, Y):
+            t.fill_(float("nan"))
+    sp, sc = streams if streams else (None, None)
+    torch.cuda.synchronize()
+    ds.dep_gemm_chain(Xd, Wqkv_t, QKV, Wo_t, Y, policy, mode=mode, mid=ds.MID_CAUSAL_ATTN, tile=tile,
+                      stream_producer=sp, stream_consumer=sc, T=T, batch=batch, seq=seq, heads=heads, head_dim=128)
+    torch.cuda.synchronize()
+    return QKV, T, Y

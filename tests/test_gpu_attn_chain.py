@@ -1,0 +1,172 @@
+"""GPU parity tests of the three-stage attention chain (QKV GeMM -> causal attention -> output
+GeMM, Fig. 2b) against the fp64 oracle, and bit-exactness across the launch modes."""
+import numpy as np
+import pytest
+import torch
+
+import inputs
+import oracle
+import paper_2305_13450_amd as ds
+from gpu_util import TOL_BF16, TOL_MID, mid_err, rel_err, row_err, run_attn_chain
+
+pytestmark = pytest.mark.gpu
+
+ALL_TILES = [ds.TILE_256x256, ds.TILE_256x128, ds.TILE_128x256, ds.TILE_128x128, ds.TILE_64x128, ds.TILE_64x64]
+MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN, ds.MODE_FUSED]
+KINDS = [ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC]
+
+
+# End to end over three stages with two bf16 intermediates, per row: the rounding of QKV (2^-9
+# relative per element) reaches T through the scores and through V, and T is rounded again, which
+# leaves an error of standard deviation of about 0.8 % of a row's RMS; the maximum over the 3e6
+# elements of T at full size sits 5 standard deviations out, i.e. at 4 %.
+TOL_BF16_CHAIN3 = 6e-2
+
+
+def _case(batch, seq, heads, K1, N2, seed, dtype=torch.bfloat16):
+    t = inputs.attention(batch * seq, K1, heads, 128, N2, seed=seed, dtype=dtype)
+    ref = oracle.attn_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["Wqkv"]), inputs.to_f64(t["Wo"]), batch, seq, heads, 128)
+    t["dims"] = (batch, seq, heads)
+    return t, ref
+
+
+def _f64(x):
+    return x.detach().to("cpu").to(torch.float64).numpy()
+
+
+def _check(got, ref, t):
+    """bf16: every stage against the oracle applied to the input that stage really read (2e-2 per
+    row), and the whole chain against the oracle end to end (6e-2 per row: the rounding of QKV
+    and T to bf16 is carried through the softmax and the last GeMM)."""
+    QKV, T, Y = got
+    QKVr, Tr, Yr = ref
+    batch, seq, heads = t["dims"]
+    assert mid_err(QKV, QKVr) <= TOL_MID
+    assert row_err(T, oracle.causal_attention(_f64(QKV), batch, seq, heads, 128)) <= TOL_BF16
+    assert row_err(Y, oracle.gemm(_f64(T), inputs.to_f64(t["Wo"]))) <= TOL_BF16
+    assert row_err(T, Tr) <= TOL_BF16_CHAIN3
+    assert row_err(Y, Yr) <= TOL_BF16_CHAIN3
+
+
+@pytest.fixture(scope="module")
+def two_sequences():
+    return _case(batch=2, seq=256, heads=2, K1=256, N2=320, seed=11)
+
+
+@pytest.fixture(scope="module")
+def ragged_sequence():
+    # one sequence whose length is a multiple of neither the query block (128) nor the key block (64)
+    return _case(batch=1, seq=333, heads=3, K1=192, N2=200, seed=12)
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("tile", ALL_TILES)
+def test_two_sequences_every_tile_and_policy(two_sequences, tile, kind):
+    t, ref = two_sequences
+    print(f"attn batch=2 seq=256 heads=2 tile={tile} kind={kind}", flush=True)
+    pol = ds.SyncPolicy(kind)
+    res = [run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 2, 256, 2, pol, mode, tile=tile) for mode in MODES]
+    for got in res:
+        _check(got, ref, t)
+    for got in res[1:]:
+        for a, b in zip(res[0], got):
+            assert torch.equal(a, b)
+    pol.status()
+    pol.destroy()
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("tile", [ds.TILE_AUTO, ds.TILE_64x64, ds.TILE_256x128])
+def test_ragged_sequence(ragged_sequence, tile, kind):
+    t, ref = ragged_sequence
+    print(f"attn batch=1 seq=333 heads=3 tile={tile} kind={kind}", flush=True)
+    pol = ds.SyncPolicy(kind)
+    res = [run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 1, 333, 3, pol, mode, tile=tile) for mode in MODES]
+    for got in res:
+        _check(got, ref, t)
+    for got in res[1:]:
+        for a, b in zip(res[0], got):
+            assert torch.equal(a, b)
+    pol.destroy()
+
+
+def test_fp16_chain_meets_the_whole_tensor_tolerance():
+    # in the paper's precision (fp16) the chain meets max-abs / RMS <= 2e-2 over the whole tensors
+    t, (QKVr, Tr, Yr) = _case(batch=2, seq=256, heads=2, K1=256, N2=320, seed=11, dtype=torch.float16)
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    res = [run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 2, 256, 2, pol, mode) for mode in MODES]
+    for QKV, T, Y in res:
+        assert mid_err(QKV, QKVr, ulp=2.0 ** -11) <= TOL_MID
+        assert rel_err(T, Tr) <= TOL_BF16
+        assert rel_err(Y, Yr) <= TOL_BF16
+    for got in res[1:]:
+        for a, b in zip(res[0], got):
+            assert torch.equal(a, b)
+    pol.destroy()
+
+
+@pytest.mark.parametrize("M", inputs.CFG4["Ms"])
+def test_gpt3_attention_shard_full_size(M):
+    # config 4 at full size (12 of GPT-3's 96 heads, batch 1, seq = M) in the launch configuration
+    # the benchmark times: library-chosen tile, Strided (QKV -> attention) + Tile (attention -> Wo)
+    c = inputs.CFG4
+    print(f"attn cfg4 M={M}", flush=True)
+    t, ref = _case(batch=1, seq=M, heads=c["heads"], K1=c["K1"], N2=c["N2"], seed=0)
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    fine = run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 1, M, c["heads"], pol, ds.MODE_FINE)
+    ss = run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 1, M, c["heads"], pol, ds.MODE_STREAMSYNC)
+    _check(fine, ref, t)
+    for a, b in zip(fine, ss):
+        assert torch.equal(a, b)
+    st = pol.status()
+    assert st.timed_out == 0
+    pol.destroy()
+
+
+def test_causality_on_the_device(two_sequences):
+    # changing the LAST token of each sequence must leave every earlier row of T and Y unchanged
+    t, _ = two_sequences
+    pol = ds.SyncPolicy(ds.TILESYNC)
+    base = run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 2, 256, 2, pol, ds.MODE_FINE)
+    X2 = t["X"].clone()
+    X2[255] += 1.0
+    X2[511] -= 1.0
+    pert = run_attn_chain(X2, t["Wqkv"], t["Wo"], 2, 256, 2, pol, ds.MODE_FINE)
+    keep = torch.ones(512, dtype=torch.bool)
+    keep[255] = keep[511] = False
+    for a, b in zip(base, pert):
+        assert torch.equal(a[keep.cuda()], b[keep.cuda()])
+        assert not torch.equal(a[~keep.cuda()], b[~keep.cuda()])
+    pol.destroy()
+
+
+def test_repeated_launches_and_delayed_producer(two_sequences):
+    t, ref = two_sequences
+    pol = ds.SyncPolicy(ds.TILESYNC, delay_tile=3, delay_iters=200000)
+    first = run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 2, 256, 2, pol, ds.MODE_STREAMSYNC)
+    for i in range(4):
+        got = run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 2, 256, 2, pol, ds.MODE_FINE if i % 2 == 0 else ds.MODE_FUSED)
+        for a, b in zip(first, got):
+            assert torch.equal(a, b)
+    _check(first, ref, t)
+    pol.destroy()
+
+
+def test_invalid_attention_arguments(two_sequences):
+    t, _ = two_sequences
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    X = t["X"].cuda()
+    Wq = t["Wqkv"].t().contiguous().cuda()
+    Wo = t["Wo"].t().contiguous().cuda()
+    QKV = torch.empty((512, 768), dtype=X.dtype, device="cuda")
+    T = torch.empty((512, 256), dtype=X.dtype, device="cuda")
+    Y = torch.empty((512, 320), dtype=X.dtype, device="cuda")
+    kw = dict(mode=ds.MODE_FINE, mid=ds.MID_CAUSAL_ATTN)
+    with pytest.raises(ds.DepsyncError):      # batch * seq != M
+        ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, T=T, batch=2, seq=200, heads=2, head_dim=128, **kw)
+    with pytest.raises(ds.DepsyncError):      # only head dimension 128 is built
+        ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, T=T, batch=2, seq=256, heads=4, head_dim=64, **kw)
+    with pytest.raises(ds.DepsyncError):      # T missing
+        ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, batch=2, seq=256, heads=2, head_dim=128, **kw)
+    torch.cuda.synchronize()
+    pol.destroy()
