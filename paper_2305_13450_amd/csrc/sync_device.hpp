@@ -124,7 +124,13 @@ __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s
             for (uint32_t i = 0; i < a.delay_iters; ++i) __builtin_amdgcn_s_sleep(127);
         }
         uint32_t idx = policy_sem(s.post_kind, x, y, s.grid_y, s.post_stride);
-        __hip_atomic_fetch_add(&s.post_sems[idx], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        // Release, spelled out: write this XCD's L2 back and WAIT for the write-back before the
+        // semaphore moves.  A release-ordered atomic is not used because the compiler drops the
+        // wait between its write-back and its atomic when it sees no other vector memory
+        // operation pending (as here, right after the vmcnt(0) above), and then a consumer on
+        // another XCD can see the semaphore before the tile's data has reached memory.
+        asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
+        __hip_atomic_fetch_add(&s.post_sems[idx], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a.flags & DS_FLAG_COUNT)
             __hip_atomic_fetch_add(&a.status->posts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }

@@ -95,3 +95,19 @@ def run_attn_chain(X, Wqkv, Wo, batch, seq, heads, policy, mode, tile=ds.TILE_AU
                       stream_producer=sp, stream_consumer=sc, T=T, batch=batch, seq=seq, heads=heads, head_dim=128)
     torch.cuda.synchronize()
     return QKV, T, Y
+
+
+def same(a: torch.Tensor, b: torch.Tensor, what: str = "") -> bool:
+    """torch.equal that says where two results differ (row / column ranges, NaN count, largest
+    difference) before a bit-exactness assertion fails."""
+    if torch.equal(a, b):
+        return True
+    bad = (a != b) | torch.isnan(a) | torch.isnan(b)
+    flat = bad.reshape(-1, bad.shape[-1])
+    rows = flat.any(dim=1).nonzero().flatten().tolist()
+    cols = flat.any(dim=0).nonzero().flatten().tolist()
+    d = (a.float() - b.float())[bad]
+    print(f"MISMATCH {what}: {int(bad.sum())} elements, rows {rows[0]}..{rows[-1]} ({len(rows)}), "
+          f"cols {cols[0]}..{cols[-1]} ({len(cols)}), NaN a/b {int(torch.isnan(a).sum())}/{int(torch.isnan(b).sum())}, "
+          f"max |a-b| {float(d.abs().nan_to_num(0).max())}, first rows {rows[:8]}, first cols {cols[:8]}", flush=True)
+    return False

@@ -97,3 +97,25 @@ def test_conv_chain_rejects_bad_channels():
         ds.dep_conv_chain(x, w1, mid, w2, out, pol)
     assert e.value.status == ds.EINVAL
     pol.destroy()
+
+
+def test_posted_tiles_are_visible_on_every_xcd_repeated():
+    # Regression: the post must wait for the L2 write-back of the tile before the semaphore moves,
+    # or a consumer on another XCD occasionally reads the (NaN-poisoned) intermediate from memory
+    # before the tile's data has arrived there.  Many short chains with fresh poisoned buffers.
+    t = inputs.conv(1, 112, 112, 128, 128, 128, seed=0)
+    x, w1, w2 = t["x"].cuda(), t["w1"].cuda(), t["w2"].cuda()
+    for kind in (ds.TILESYNC, ds.STRIDEDSYNC):
+        pol = ds.SyncPolicy(kind)
+        ref_mid, ref_out = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_STREAMSYNC)
+        for mode in (ds.MODE_FINE, ds.MODE_FUSED):
+            differ = 0
+            for _ in range(250):
+                mid = torch.full_like(ref_mid, float("nan"))
+                out = torch.full_like(ref_out, float("nan"))
+                torch.cuda.synchronize()
+                ds.dep_conv_chain(x, w1, mid, w2, out, pol, mode=mode)
+                torch.cuda.synchronize()
+                differ += int(not (torch.equal(out, ref_out) and torch.equal(mid, ref_mid)))
+            assert differ == 0, (kind, mode, differ)
+        pol.destroy()
