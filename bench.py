@@ -24,6 +24,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--rounds", type=int, default=3, help="interleaved timing blocks per variant (comparison table)")
     ap.add_argument("--m", type=int, default=2048, help="tokens (rows of X)")
     ap.add_argument("--workload", default="gpt3_mlp", choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "cfg1"])
     ap.add_argument("--policy", default="auto", choices=["auto", "row", "tile", "strided"])
@@ -34,21 +35,18 @@ def parse():
     return ap.parse_args()
 
 
-def time_chain(ds, torch, call, sp, steps, warmup):
-    """Mean latency (us) of `call` over `steps` back-to-back launches, by HIP events on stream sp."""
-    for _ in range(warmup):
-        call()
+def time_block(torch, call, sp, steps):
+    """Mean latency (us) of `call` over `steps` back-to-back launches, by HIP events on stream sp
+    (every launch mode returns to sp, so the events bracket whole chains)."""
     torch.cuda.synchronize()
     e0 = torch.cuda.Event(enable_timing=True)
     e1 = torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
     e0.record(sp)
     for _ in range(steps):
         call()
     e1.record(sp)
     torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    return e0.elapsed_time(e1) * 1e3 / steps, wall * 1e6 / steps
+    return e0.elapsed_time(e1) * 1e3 / steps
 
 
 def main():
@@ -106,29 +104,43 @@ def main():
     modes = {"fine": ds.MODE_FINE, "fused": ds.MODE_FUSED, "streamsync": ds.MODE_STREAMSYNC, "plain": ds.MODE_PLAIN}
     want = [m for m in args.modes.split(",") if m]
 
-    results = {}
-    plan = None
-    for pn in pol_names:
-        pol = ds.SyncPolicy(kinds[pn])
-        plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol, mid=mid, tile=args.tile, **extra)
-        for mn in want:
-            if mn not in ("fine", "fused") and pn != pol_names[0]:
-                continue   # stream-sync and plain do not depend on the policy's granularity much
-            def call(mode=modes[mn]):
-                ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=mode, mid=mid, tile=args.tile,
-                                  stream_producer=sp, stream_consumer=sc, **extra)
-            us, wall_us = time_chain(ds, torch, call, sp, args.steps, args.warmup)
-            results[(pn, mn)] = (us, wall_us)
-        pol.status()
-        pol.destroy()
+    # Every (policy, launch mode) variant is warmed up, then timed in `rounds` interleaved blocks of
+    # `steps` launches (the chip's clock follows its power and temperature history, so variants
+    # timed one after the other are not comparable); a variant's latency is the median of its blocks.
+    pols = {pn: ds.SyncPolicy(kinds[pn]) for pn in pol_names}
+    plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pols[pol_names[0]], mid=mid, tile=args.tile, **extra)
+    variants = [(pn, mn) for pn in pol_names for mn in want
+                if mn in ("fine", "fused") or pn == pol_names[0]]   # stream-sync / plain: first policy only
+
+    def caller(pn, mn):
+        pol, mode = pols[pn], modes[mn]
+        def call():
+            ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=mode, mid=mid, tile=args.tile,
+                              stream_producer=sp, stream_consumer=sc, **extra)
+        return call
+    calls = {v: caller(*v) for v in variants}
+    for v in variants:
+        for _ in range(args.warmup):
+            calls[v]()
+    blocks = {v: [] for v in variants}
+    for _ in range(args.rounds):
+        for v in variants:
+            blocks[v].append(time_block(torch, calls[v], sp, args.steps))
+    results = {v: sorted(b)[len(b) // 2] for v, b in blocks.items()}
 
     # the fine-grained variants: two streams (FINE) or one dispatch (FUSED), per policy
-    fine = {(pn, mn): results[(pn, mn)][0] for pn in pol_names for mn in ("fine", "fused") if (pn, mn) in results}
-    best = min(fine, key=fine.get) if fine else (pol_names[0], want[0])
+    fine = {v: results[v] for v in variants if v[1] in ("fine", "fused")}
+    best = min(fine, key=fine.get) if fine else variants[0]
     best_pol, best_mode = best
-    lat = results[best][0]
-    ss = results.get((pol_names[0], "streamsync"), (None, None))[0]
-    plain = results.get((pol_names[0], "plain"), (None, None))[0]
+    # the headline: W warm-up launches, then exactly K timed launches of the best variant
+    for _ in range(args.warmup):
+        calls[best]()
+    lat = time_block(torch, calls[best], sp, args.steps)
+    ss = results.get((pol_names[0], "streamsync"))
+    plain = results.get((pol_names[0], "plain"))
+    for pol in pols.values():
+        pol.status()
+        pol.destroy()
     flops, nbytes = plan.flops, plan.bytes
     tflops = flops / (lat * 1e-6) / 1e12
     hbm_bound = (nbytes / 8e12) > (flops / (PEAK_BF16_TFLOPS * 1e12))
@@ -149,7 +161,8 @@ def main():
         "config": {"workload": name, "M": M, "policy": best_pol, "launch": best_mode, "tile": ds.tile_shape(plan.tile_prod),
                    "tiles_producer": plan.n_prod, "tiles_consumer": plan.n_cons, "slots": plan.slots,
                    "waves_streamsync": plan.waves_streamsync, "waves_fine": plan.waves_fine},
-        "latency_us": {f"{pn}/{mn}": round(v[0], 2) for (pn, mn), v in results.items()},
+        "latency_us": {f"{pn}/{mn}": round(v, 2) for (pn, mn), v in results.items()},
+        "latency_blocks_us": {f"{pn}/{mn}": [round(x, 1) for x in b] for (pn, mn), b in blocks.items()},
         "speedup_vs_streamsync": (ss / lat) if ss else None,
         "speedup_vs_plain": (plain / lat) if plain else None,
         "tflops": tflops, "pct_bf16_mfma_peak": 100 * tflops / PEAK_BF16_TFLOPS,

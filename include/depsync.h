@@ -88,7 +88,9 @@ typedef enum {
     DEPSYNC_TILE_128x128 = 4,
     DEPSYNC_TILE_64x128 = 5,
     DEPSYNC_TILE_64x64 = 6,
-    DEPSYNC_TILE__COUNT = 7
+    DEPSYNC_TILE_256x192 = 7,  /* 192-wide tiles divide widths of the form 3 * 2^k evenly */
+    DEPSYNC_TILE_128x192 = 8,
+    DEPSYNC_TILE__COUNT = 9
 } depsync_tile;
 
 /* Policy flags. */
@@ -128,6 +130,7 @@ typedef struct {
     uint32_t where;     /* bits 0-7: 1 if the tile had a dependency, else 0; 8-15: XCD;
                            16-23: CU within its shader array; 24-31: shader engine            */
     uint32_t tx, ty;    /* column tile, row tile                                              */
+    uint64_t t_enter;   /* workgroup started (before it drew its tile)                        */
     uint64_t t_start;   /* tile handed out                                                    */
     uint64_t t_ready;   /* first dependency satisfied (t_start's neighbour if none)           */
     uint64_t t_end;     /* stores and post done                                               */

@@ -25,7 +25,7 @@ constexpr uint32_t WS_STATUS = 32;       // StatusBlock, 8 words
 constexpr uint32_t WS_ZERO_PAGE = 64;    // 64 words = 256 zero bytes (never written after init)
 constexpr uint32_t WS_SEMS = 128;
 constexpr uint32_t WS_MAX_SEMS = 1u << 16;
-constexpr uint32_t WS_TRACE = WS_SEMS + WS_MAX_SEMS;      // TraceRec[WS_TRACE_CAP], 10 words each
+constexpr uint32_t WS_TRACE = WS_SEMS + WS_MAX_SEMS;      // TraceRec[WS_TRACE_CAP], 12 words each
 constexpr uint32_t WS_TRACE_CAP = 8192;
 constexpr uint32_t WS_WORDS = WS_TRACE + WS_TRACE_CAP * (sizeof(TraceRec) / 4);
 
@@ -92,8 +92,10 @@ double tile_cost_factor(int tile) {
         case DEPSYNC_TILE_256x256: return 1.00;
         case DEPSYNC_TILE_256x128: return 1.35;
         case DEPSYNC_TILE_128x256: return 1.35;
-        case DEPSYNC_TILE_128x128: return 1.10;
+        case DEPSYNC_TILE_128x128: return 1.20;
         case DEPSYNC_TILE_64x128: return 1.6;
+        case DEPSYNC_TILE_256x192: return 1.13;
+        case DEPSYNC_TILE_128x192: return 1.00;
         default: return 2.4;
     }
 }
@@ -106,7 +108,7 @@ int choose_tile(uint32_t M, uint32_t n_out1, uint32_t K1, uint32_t N2, uint32_t 
     double best_t = 0;
     for (int t = 1; t < DEPSYNC_TILE__COUNT; ++t) {
         const TileShape* ts = tile_shape(t);
-        if (gate_up && ts->wave_cols < 64) continue;
+        if (gate_up && ts->wave_cols % 64) continue;
         const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
         const uint32_t gy = cdiv(M, ts->rows);
         const uint32_t gx1 = cdiv(n_out1, tn1), gx2 = cdiv(N2, ts->cols);
@@ -177,7 +179,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
     const TileShape* ts = tile_shape(tile);
     if (!ts) return DEPSYNC_EINVAL;
-    if (gate_up && ts->wave_cols < 64) return DEPSYNC_EINVAL;
+    if (gate_up && ts->wave_cols % 64) return DEPSYNC_EINVAL;   // a wave needs whole gate/up pairs of 32-column blocks
 
     std::memset(&p, 0, sizeof(p));
     const int last = attn ? 2 : 1;

@@ -64,7 +64,7 @@ __device__ __forceinline__ void attn_wait_qkv(WaitCtx& w, const StageDesc& s, ui
 
 template <typename T, bool SYNC>
 __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc& s, uint32_t head, uint32_t qblk,
-                                          uint32_t rel_ticket, char* lds) {
+                                          uint32_t rel_ticket, char* lds, uint64_t t_enter) {
     using M = Mma<T>;
     using V8 = typename M::V8;
     typedef T T4 __attribute__((ext_vector_type(4)));
@@ -229,7 +229,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     if (tracing && tid == 0) {
         TraceRec r;
         r.rel = rel_ticket; r.where = hw_where(2u); r.tx = head; r.ty = qblk;
-        r.t_start = t_start; r.t_ready = t_ready; r.t_end = now_ticks();
+        r.t_enter = t_enter; r.t_start = t_start; r.t_ready = t_ready; r.t_end = now_ticks();
         args.trace[rel_ticket] = r;
     }
 }

@@ -71,6 +71,7 @@ struct TraceRec {
     uint32_t rel;        // first_ticket[stage] + row-major tile index
     uint32_t where;      // stage | xcc << 8 | cu << 16 | se << 24
     uint32_t tx, ty;
+    uint64_t t_enter;    // workgroup started
     uint64_t t_start;    // tile drawn
     uint64_t t_ready;    // first dependency satisfied (== t_start for tiles without one)
     uint64_t t_end;      // stores and post done

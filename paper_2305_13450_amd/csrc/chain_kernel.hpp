@@ -22,22 +22,24 @@ __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs a
     static_assert(Cfg::LDS_BYTES >= ATT_LDS_BYTES, "the attention tile stages its K and V blocks in the same LDS");
     __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
 
+    uint64_t t_enter = 0;
+    if (SYNC && (args.flags & DS_FLAG_TRACE)) t_enter = now_ticks();
     const TileId t = draw_tile<SYNC>(args, reinterpret_cast<uint32_t*>(lds));
     if (t.rel == 0xffffffffu) return;
     const StageDesc& s = args.st[t.stage];
     if constexpr (AMODE == A_DENSE) {
         if (s.op == OP_ATTN) {   // middle stage of the attention chain
-            attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds);
+            attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter);
             return;
         }
     }
     if constexpr (SYNC) {
         if (s.dep_kind != DEP_NONE) {
-            gemm_tile<Cfg, T, true, AMODE, true>(args, s, t.tx, t.ty, t.rel, lds);
+            gemm_tile<Cfg, T, true, AMODE, true>(args, s, t.tx, t.ty, t.rel, lds, t_enter);
             return;
         }
     }
-    gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds);
+    gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds, t_enter);
 }
 
 //                        TM   TN  WM WN  workgroups per CU, LDS stages
@@ -47,6 +49,8 @@ using Cfg128x256 = TileCfg<128, 256, 2, 2, 1, 3>;   // 144 KB
 using Cfg128x128 = TileCfg<128, 128, 2, 2, 2, 2>;   // 2 x 64 KB
 using Cfg64x128 = TileCfg<64, 128, 2, 2, 2, 3>;     // 2 x 72 KB
 using Cfg64x64 = TileCfg<64, 64, 2, 2, 2, 4>;       // 2 x 64 KB
+using Cfg256x192 = TileCfg<256, 192, 2, 2, 1, 2>;   // 112 KB
+using Cfg128x192 = TileCfg<128, 192, 2, 2, 2, 2>;   // 2 x 80 KB
 
 template <class Cfg, typename T, uint32_t AMODE>
 static hipError_t launch_cfg(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
@@ -66,6 +70,8 @@ static hipError_t launch_family(int tile, bool sync, uint32_t n_blocks, hipStrea
         case 4: return launch_cfg<Cfg128x128, T, AMODE>(sync, n_blocks, stream, a);
         case 5: return launch_cfg<Cfg64x128, T, AMODE>(sync, n_blocks, stream, a);
         case 6: return launch_cfg<Cfg64x64, T, AMODE>(sync, n_blocks, stream, a);
+        case 7: return launch_cfg<Cfg256x192, T, AMODE>(sync, n_blocks, stream, a);
+        case 8: return launch_cfg<Cfg128x192, T, AMODE>(sync, n_blocks, stream, a);
         default: return hipErrorInvalidValue;
     }
 }

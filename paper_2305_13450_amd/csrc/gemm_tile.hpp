@@ -165,7 +165,7 @@ __device__ __forceinline__ const char* uni_ptr(const void* p) {
 // on semaphores before it requests a slice of A).
 template <class Cfg, typename T, bool SYNC, uint32_t AMODE, bool DEP>
 __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc& s, uint32_t tx, uint32_t ty,
-                                          uint32_t rel_ticket, char* lds) {
+                                          uint32_t rel_ticket, char* lds, uint64_t t_enter) {
     using M = Mma<T>;
     using V8 = typename M::V8;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, FM = Cfg::FM, FN = Cfg::FN;
@@ -427,7 +427,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     if (tracing && tid == 0) {
         TraceRec r;
         r.rel = rel_ticket; r.where = hw_where(DEP ? 1u : 0u); r.tx = tx; r.ty = ty;
-        r.t_start = t_start; r.t_ready = t_ready; r.t_end = now_ticks();
+        r.t_enter = t_enter; r.t_start = t_start; r.t_ready = t_ready; r.t_end = now_ticks();
         args.trace[rel_ticket] = r;
     }
 }

@@ -8,10 +8,10 @@ namespace depsync {
 struct TileShape {
     int rows, cols;       // macro-tile
     int occupancy;        // workgroups resident per CU
-    int wave_cols;        // columns of one wave's sub-tile (gate/up fusion needs >= 64)
+    int wave_cols;        // columns of one wave's sub-tile (gate/up fusion needs a multiple of 64)
 };
 
-// nullptr for ids outside [1, 6].
+// nullptr for ids outside [1, 8].
 const TileShape* tile_shape(int tile);
 
 // Launch n_blocks workgroups of the chain kernel for macro-tile `tile`, element type `dtype`

@@ -36,8 +36,10 @@ const TileShape* tile_shape(int tile) {
         {128, 128, 2, 64},
         {64, 128, 2, 64},
         {64, 64, 2, 32},
+        {256, 192, 1, 96},
+        {128, 192, 2, 96},
     };
-    if (tile < 1 || tile > 6) return nullptr;
+    if (tile < 1 || tile > 8) return nullptr;
     return &shapes[tile];
 }
 
