@@ -20,12 +20,14 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 // Workspace layout in 32-bit words.
-constexpr uint32_t WS_TICKET = 0;        // 3 stages x 8 dispatch counters
-constexpr uint32_t WS_STATUS = 32;       // StatusBlock, 8 words
-constexpr uint32_t WS_ZERO_PAGE = 64;    // 64 words = 256 zero bytes (never written after init)
-constexpr uint32_t WS_SEMS = 128;
+constexpr uint32_t WS_TICKET = 0;        // 3 stages x 8 dispatch counters, one per 128-byte line
+constexpr uint32_t WS_TICKET_WORDS = 24 * SYNC_WORD_STRIDE;
+constexpr uint32_t WS_STATUS = WS_TICKET_WORDS;          // StatusBlock, 8 words
+constexpr uint32_t WS_ZERO_PAGE = WS_STATUS + 64;        // 64 words = 256 zero bytes (never written after init)
+constexpr uint32_t WS_SEMS = 1024;                       // one semaphore per 128-byte line
 constexpr uint32_t WS_MAX_SEMS = 1u << 16;
-constexpr uint32_t WS_TRACE = WS_SEMS + WS_MAX_SEMS;      // TraceRec[WS_TRACE_CAP], 12 words each
+constexpr uint32_t WS_SEM_WORDS = WS_MAX_SEMS * SYNC_WORD_STRIDE;
+constexpr uint32_t WS_TRACE = WS_SEMS + WS_SEM_WORDS;     // TraceRec[WS_TRACE_CAP], 12 words each
 constexpr uint32_t WS_TRACE_CAP = 8192;
 constexpr uint32_t WS_WORDS = WS_TRACE + WS_TRACE_CAP * (sizeof(TraceRec) / 4);
 
@@ -52,6 +54,7 @@ struct sync_policy {
     uint64_t geom_sig;
     uint32_t epoch;
     uint32_t launches;
+    uint32_t sems_dirty;   // semaphores that may be non-zero (largest count used since they were last cleared)
     bool need_reset;
 };
 
@@ -343,13 +346,15 @@ int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t*
     const uint64_t next = (uint64_t)(pol->epoch + 2) * std::max(total, vmax);
     if (pol->need_reset || sig != pol->geom_sig || next >= (1ull << 31)) {
         // zero the dispatch counter and every semaphore the previous geometry may have touched
-        hipError_t e = launch_fill_u32(pol->ws + WS_TICKET, 0u, 24, stream);
-        if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_SEMS, 0u, WS_MAX_SEMS, stream);
+        hipError_t e = launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, stream);
+        if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, stream);
         if (e != hipSuccess) return hip_fail(e);
         pol->epoch = 0;
         pol->geom_sig = sig;
         pol->need_reset = false;
+        pol->sems_dirty = 0;
     }
+    pol->sems_dirty = std::max(pol->sems_dirty, p.n_sems);
     *epoch_out = pol->epoch;
     return DEPSYNC_OK;
 }
@@ -381,7 +386,7 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
         st.zero_page = pol->ws + WS_ZERO_PAGE;
         st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
         if (s > 0) {
-            st.sems = pol->ws + WS_SEMS + p.sem_off[s];
+            st.sems = pol->ws + WS_SEMS + p.sem_off[s] * SYNC_WORD_STRIDE;
             st.sem_value = p.sem_value[s];
             st.sem_target_base = epoch * p.sem_value[s];
             st.prod_tm = p.out_tm[s - 1];
@@ -392,7 +397,7 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
         }
         if (s + 1 < p.n_stages) {
             st.post_kind = p.dep_kind[s + 1];
-            st.post_sems = pol->ws + WS_SEMS + p.sem_off[s + 1];
+            st.post_sems = pol->ws + WS_SEMS + p.sem_off[s + 1] * SYNC_WORD_STRIDE;
             st.post_stride = p.stride[s + 1];
         } else {
             st.post_kind = DEP_NONE;
@@ -468,6 +473,7 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
     p->epoch = 0;
     p->geom_sig = 0;
     p->launches = 0;
+    p->sems_dirty = 0;
     p->need_reset = false;
     *out = p;
     return DEPSYNC_OK;
@@ -487,10 +493,11 @@ int sync_policy_destroy(sync_policy_t* pol) {
 int dep_chain_reset(sync_policy_t* pol, void* stream) {
     if (!pol) return DEPSYNC_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, 24, st));
+    HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS + 1, 0xffffffffu, 1, st));   // first_timeout = -1
-    HIP_TRY(launch_fill_u32(pol->ws + WS_SEMS, 0u, WS_MAX_SEMS, st));
+    HIP_TRY(launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, st));
+    pol->sems_dirty = 0;
     pol->epoch = 0;
     pol->launches = 0;
     pol->need_reset = false;

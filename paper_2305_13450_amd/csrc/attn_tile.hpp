@@ -41,7 +41,7 @@ __device__ __forceinline__ void attn_wait_qkv(WaitCtx& w, const StageDesc& s, ui
     const uint32_t target = s.sem_target_base + s.sem_value;
     for (uint32_t y = y0; y <= y1; ++y) {
         if (s.dep_kind == DEP_ROW) {
-            const uint32_t* sem = s.sems + y;
+            const uint32_t* sem = s.sems + y * SYNC_WORD_STRIDE;
             uint32_t v = sem_load(sem);
             const bool polled = !sem_reached(v, target);
             if (polled) sem_wait(w, sem, target, v);
@@ -52,7 +52,7 @@ __device__ __forceinline__ void attn_wait_qkv(WaitCtx& w, const StageDesc& s, ui
         for (uint32_t b = 0; b < nblk; ++b) {
             const uint32_t c0 = b * E + head * ATT_D;
             for (uint32_t x = c0 / s.prod_tn; x <= (c0 + ATT_D - 1) / s.prod_tn; ++x) {
-                const uint32_t* sem = s.sems + policy_sem(s.dep_kind, x, y, s.prod_grid_y, s.stride);
+                const uint32_t* sem = s.sems + policy_sem(s.dep_kind, x, y, s.prod_grid_y, s.stride) * SYNC_WORD_STRIDE;
                 uint32_t v = sem_load(sem);
                 const bool polled = !sem_reached(v, target);
                 if (polled) sem_wait(w, sem, target, v);

@@ -77,6 +77,11 @@ struct TraceRec {
     uint64_t t_end;      // stores and post done
 };
 
+// Every dispatch counter and every semaphore has a 128-byte line of the workspace to itself:
+// hundreds of waves poll semaphores while others draw tiles, and words that share a line (or
+// a memory channel) make those requests queue up behind each other.
+constexpr uint32_t SYNC_WORD_STRIDE = 32;   // in 32-bit words
+
 struct ChainArgs {
     StageDesc st[3];
     uint32_t n_stages;

@@ -136,7 +136,7 @@ __device__ __forceinline__ bool dep_wait(WaitCtx& w, const StageDesc& s, const D
     const uint32_t target = s.sem_target_base + s.sem_value;
     bool polled = false;
     for (uint32_t y = r.y0; y <= r.y1; ++y) {
-        const uint32_t* sem = s.sems + policy_sem(s.dep_kind, r.x, y, s.prod_grid_y, s.stride);
+        const uint32_t* sem = s.sems + policy_sem(s.dep_kind, r.x, y, s.prod_grid_y, s.stride) * SYNC_WORD_STRIDE;
         uint32_t v = sem_load(sem);
         if (!sem_reached(v, target)) {
             if (!blocking) return false;

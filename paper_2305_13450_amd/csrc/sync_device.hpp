@@ -130,7 +130,7 @@ __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s
         // operation pending (as here, right after the vmcnt(0) above), and then a consumer on
         // another XCD can see the semaphore before the tile's data has reached memory.
         asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
-        __hip_atomic_fetch_add(&s.post_sems[idx], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&s.post_sems[idx * SYNC_WORD_STRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a.flags & DS_FLAG_COUNT)
             __hip_atomic_fetch_add(&a.status->posts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
@@ -186,14 +186,14 @@ __device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_sl
         bool direct = a.block_offset + blockIdx.x < a.first_ticket[1];
         for (uint32_t s = 0; s < a.n_stages && !found; ++s) {
             const StageDesc& st = a.st[s];
-            uint32_t* cnt = a.ticket + 8u * s;
+            uint32_t* cnt = a.ticket + 8u * s * SYNC_WORD_STRIDE;
             for (uint32_t attempt = 0; attempt < 10 && !found; ++attempt) {
                 uint32_t q = home;
                 if (!(direct && s == 0 && attempt == 0)) {
                     uint32_t c[8];
 #pragma unroll
                     for (int j = 0; j < 8; ++j)
-                        c[j] = __hip_atomic_load(cnt + j, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        c[j] = __hip_atomic_load(cnt + j * SYNC_WORD_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     uint32_t avail = 0;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
@@ -206,10 +206,10 @@ __device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_sl
                 }
                 const uint32_t ncol = (st.grid_x + 7u - q) >> 3, len = ncol * st.grid_y;
                 if (len == 0) continue;
-                uint32_t i = __hip_atomic_fetch_add(cnt + q, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
+                uint32_t i = __hip_atomic_fetch_add(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
                              a.epoch * len;
                 if (i >= len) {   // emptied in the meantime: undo and look again
-                    __hip_atomic_fetch_sub(cnt + q, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_fetch_sub(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     continue;
                 }
                 if (s == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
