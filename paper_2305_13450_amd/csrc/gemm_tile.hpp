@@ -125,29 +125,20 @@ __device__ __forceinline__ bool dep_segment(const StageDesc& s, uint32_t m0, uin
     }
 }
 
-// Wait (blocking) or test (non-blocking) the semaphores of one dependency segment.  Returns
-// true when all are reached.  Acquire ordering without a cache invalidate: the semaphore reads
-// are agent-scope atomic loads whose values this wave branches on before it issues the
-// dependent operand's loads.  Those loads cannot hit a stale line in this XCD's L2: caches are
-// invalidated when a kernel starts, nothing reads a line of the intermediate before the tile
-// that produces it has posted, and the host requires the intermediate's rows to be 128-byte
-// aligned, so a cache line never mixes the outputs of two producer tiles.
-__device__ __forceinline__ bool dep_wait(WaitCtx& w, const StageDesc& s, const DepRange& r, bool blocking) {
+// Wait for the semaphores of one dependency segment.  Acquire ordering without a cache
+// invalidate: the semaphore reads are agent-scope atomic loads whose values this wave branches
+// on before it issues the dependent operand's loads.  Those loads cannot hit a stale line in
+// this XCD's L2: caches are invalidated when a kernel starts, nothing reads a line of the
+// intermediate before the tile that produces it has posted, and the host requires the
+// intermediate's rows to be 128-byte aligned, so a cache line never mixes the outputs of two
+// producer tiles.
+__device__ __forceinline__ void dep_wait(WaitCtx& w, const StageDesc& s, const DepRange& r) {
     const uint32_t target = s.sem_target_base + s.sem_value;
-    bool polled = false;
     for (uint32_t y = r.y0; y <= r.y1; ++y) {
         const uint32_t* sem = s.sems + policy_sem(s.dep_kind, r.x, y, s.prod_grid_y, s.stride) * SYNC_WORD_STRIDE;
-        uint32_t v = sem_load(sem);
-        if (!sem_reached(v, target)) {
-            if (!blocking) return false;
-            polled = true;
-            sem_wait(w, sem, target, v);
-        }
+        const uint32_t v = sem_load(sem);
+        if (!sem_reached(v, target)) sem_wait(w, sem, target, v);
     }
-    if (w.args->flags & DS_FLAG_COUNT) {
-        for (uint32_t y = r.y0; y <= r.y1; ++y) count_wait(*w.args, polled);
-    }
-    return true;
 }
 
 // ---- the tile ------------------------------------------------------------------------------
@@ -303,17 +294,44 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         seg_steps = uni(seg_steps);
     }
     // Called before the A slice of K step k (< KT) is requested into `stage`: if a dependency
-    // segment starts there, make sure its producer tiles have posted.  When they have not, the
+    // segment starts there, make sure its producer tiles have posted.  The semaphores are looked
+    // at 64 segments at a time (lane l tests the segment l places ahead, one load instruction
+    // for the wave), so a tile whose producers are long done pays one round trip for its whole
+    // K loop instead of one per segment.  When the segment at hand has not been posted, the
     // weights of the step are requested first (the load/wait reordering) and then the wave
     // really waits; the caller requests the slice (and, harmlessly, the weights again) afterwards.
+    uint32_t ready_until = 0;      // every segment that starts before this K step is known to be posted
     auto dep_before_request = [&](uint32_t k, uint32_t stage) __attribute__((always_inline)) {
         if constexpr (DEP) {
             if (k == seg_next) {
                 seg_next = seg_steps ? seg_next + seg_steps : 0xffffffffu;
                 DepRange dr;
-                if (dep_segment(s, m0, TM, k, dr) && !dep_wait(wctx, s, dr, false)) {
-                    if (reorder) issue_B(stage);
-                    dep_wait(wctx, s, dr, true);
+                if (!dep_segment(s, m0, TM, k, dr)) return;
+                bool polled = false;
+                if (k >= ready_until) {
+                    const uint32_t ka = k + lane * seg_steps;          // lane's segment start
+                    bool ok = true;
+                    DepRange la;
+                    if (ka < KT && (lane == 0 || seg_steps != 0) && dep_segment(s, m0, TM, ka, la)) {
+                        const uint32_t target = s.sem_target_base + s.sem_value;
+                        for (uint32_t y = la.y0; y <= la.y1; ++y) {
+                            const uint32_t* sem = s.sems + policy_sem(s.dep_kind, la.x, y, s.prod_grid_y, s.stride) * SYNC_WORD_STRIDE;
+                            ok = ok && sem_reached(__hip_atomic_load(sem, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), target);
+                        }
+                    }
+                    const uint64_t mask = __ballot(ok);
+                    const uint32_t n_ready = (~mask == 0) ? 64u : (uint32_t)__builtin_ctzll(~mask);
+                    if (n_ready == 0) {
+                        if (reorder) issue_B(stage);
+                        dep_wait(wctx, s, dr);
+                        polled = true;
+                        ready_until = k + 1;
+                    } else {
+                        ready_until = seg_steps ? k + n_ready * seg_steps : 0xffffffffu;
+                    }
+                }
+                if (args.flags & DS_FLAG_COUNT) {
+                    for (uint32_t y = dr.y0; y <= dr.y1; ++y) count_wait(args, polled);
                 }
             }
         }
