@@ -18,6 +18,12 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
 
+# HBM-side bytes of one chain from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by what the
+# same counter reads for a 1 GiB copy), per workload and launch mode; see profiles/*.md for the runs.
+MEASURED_TRAFFIC_BYTES = {
+    ("gpt3_mlp", 2048, "fused"): (1160433 + 82393) * 1024,
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -32,6 +38,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-rows", type=int, default=384, help="rows of X the CPU oracle is timed on")
     ap.add_argument("--modes", default="fine,fused,streamsync,plain")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
+                    help="also run a plain device-to-device copy of this many MiB three times, so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
     return ap.parse_args()
 
 
@@ -98,6 +107,14 @@ def main():
     if attn:
         extra = dict(attn, T=torch.empty((M, attn["heads"] * attn["head_dim"]), dtype=X.dtype, device="cuda"))
 
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
     kinds = {"row": ds.ROWSYNC, "tile": ds.TILESYNC, "strided": ds.STRIDEDSYNC}
     pol_names = (["row", "tile", "strided"] if attn else ["row", "tile"]) if args.policy == "auto" else [args.policy]
@@ -149,7 +166,7 @@ def main():
     else:
         roof = {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
-    roof["traffic"] = None
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, M, best_mode)) if args.tile == 0 else None
     roof["kernel"] = "chain_kernel (producer + consumer dispatches of one chain, which overlap)"
     roof["per_launch"] = {"flops": flops, "bytes": nbytes, "duration_us": lat}
 
