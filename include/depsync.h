@@ -172,7 +172,14 @@ typedef struct {
  *                          Q | K | V, head h at columns h*head_dim inside each block;
  *                          T[M x heads*head_dim] = per-head causal softmax(QK^T/sqrt(d)) V
  *                          over each of `batch` sequences of `seq` rows (M = batch*seq);
- *                          K2 = heads*head_dim, Y = T W2.
+ *                          K2 = heads*head_dim, Y = T W2.  Built for head_dim = 128 (other
+ *                          values: DEPSYNC_ENOTIMPL); with batch > 1, seq must be a multiple
+ *                          of 128 (else DEPSYNC_ENOTIMPL).  T, like H, must be 128-byte
+ *                          aligned with ldt a multiple of 64.  The chain then has three
+ *                          stages; with DEPSYNC_STRIDEDSYNC the attention stage waits on one
+ *                          semaphore per producer row tile shared by the Q, K and V column
+ *                          tiles of its head and the last GeMM waits per attention tile
+ *                          (Section V-C, "Strided + TileSync").
  */
 typedef struct {
     int32_t M, K1, N1, N2;
