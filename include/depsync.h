@@ -90,7 +90,8 @@ typedef enum {
     DEPSYNC_TILE_64x64 = 6,
     DEPSYNC_TILE_256x192 = 7,  /* 192-wide tiles divide widths of the form 3 * 2^k evenly */
     DEPSYNC_TILE_128x192 = 8,
-    DEPSYNC_TILE__COUNT = 9
+    DEPSYNC_TILE_256x64 = 9,   /* narrow outputs (64 channels)                           */
+    DEPSYNC_TILE__COUNT = 10
 } depsync_tile;
 
 /* Policy flags. */

@@ -99,6 +99,7 @@ double tile_cost_factor(int tile) {
         case DEPSYNC_TILE_64x128: return 1.6;
         case DEPSYNC_TILE_256x192: return 1.13;
         case DEPSYNC_TILE_128x192: return 1.00;
+        case DEPSYNC_TILE_256x64: return 1.5;
         default: return 2.4;
     }
 }
@@ -383,6 +384,7 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
         StageDesc& st = a.st[s];
         st.grid_x = p.grid_x[s];
         st.grid_y = p.grid_y[s];
+        st.queue_by_col = p.grid_x[s] >= 8 ? 1u : 0u;
         st.zero_page = pol->ws + WS_ZERO_PAGE;
         st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
         if (s > 0) {

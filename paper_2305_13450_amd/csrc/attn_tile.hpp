@@ -221,7 +221,14 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
                 T4 pk;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) pk[j] = (T)(o[db][g * 4 + j] * inv);
-                *(T4*)(out + db * 32 + g * 8 + h2 * 4) = pk;
+                if constexpr (SYNC) {   // written through to memory, like the GeMM tile's output
+                    uint64_t bits;
+                    __builtin_memcpy(&bits, &pk, 8);
+                    __hip_atomic_store(reinterpret_cast<uint64_t*>(out + db * 32 + g * 8 + h2 * 4), bits, __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+                } else {
+                    *(T4*)(out + db * 32 + g * 8 + h2 * 4) = pk;
+                }
             }
     }
 

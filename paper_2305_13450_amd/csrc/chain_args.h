@@ -35,6 +35,7 @@ struct StageDesc {
     uint32_t M, N, K;   // N = output columns (B_GATE_UP: B has 2N rows)
     uint32_t lda, ldb, ldc;
     uint32_t grid_x, grid_y;   // column tiles, row tiles
+    uint32_t queue_by_col;     // dispatch queue of tile (x,y): x mod 8 if set, else (y*grid_x + x) mod 8
     uint32_t op, amode, bmode, act;
     // conv geometry (A_CONV3X3): image height, width, input channels
     uint32_t H, W, Cin;

@@ -51,6 +51,7 @@ using Cfg64x128 = TileCfg<64, 128, 2, 2, 2, 3>;     // 2 x 72 KB
 using Cfg64x64 = TileCfg<64, 64, 2, 2, 2, 4>;       // 2 x 64 KB
 using Cfg256x192 = TileCfg<256, 192, 2, 2, 1, 2>;   // 112 KB
 using Cfg128x192 = TileCfg<128, 192, 2, 2, 2, 2>;   // 2 x 80 KB
+using Cfg256x64 = TileCfg<256, 64, 4, 1, 2, 2>;     // 2 x 80 KB
 
 template <class Cfg, typename T, uint32_t AMODE>
 static hipError_t launch_cfg(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
@@ -72,6 +73,7 @@ static hipError_t launch_family(int tile, bool sync, uint32_t n_blocks, hipStrea
         case 6: return launch_cfg<Cfg64x64, T, AMODE>(sync, n_blocks, stream, a);
         case 7: return launch_cfg<Cfg256x192, T, AMODE>(sync, n_blocks, stream, a);
         case 8: return launch_cfg<Cfg128x192, T, AMODE>(sync, n_blocks, stream, a);
+        case 9: return launch_cfg<Cfg256x64, T, AMODE>(sync, n_blocks, stream, a);
         default: return hipErrorInvalidValue;
     }
 }

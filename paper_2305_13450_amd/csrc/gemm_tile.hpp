@@ -68,6 +68,19 @@ typedef __attribute__((address_space(3))) void* lptr_t;
 __device__ __forceinline__ void dma16(const char* g, char* l) {
     __builtin_amdgcn_global_load_lds((gptr_t)g, (lptr_t)l, 16, 0, 0);
 }
+// Store one 16-bit output element.  With the synchronisation hooks compiled in, the store is an
+// agent-scope store: it is written through this XCD's L2 to memory, so that the post needs no
+// write-back of the whole L2 before the semaphore moves.
+template <bool THROUGH, typename T>
+__device__ __forceinline__ void store_out(T* p, T v) {
+    if constexpr (THROUGH) {
+        uint16_t bits;
+        __builtin_memcpy(&bits, &v, 2);
+        __hip_atomic_store(reinterpret_cast<uint16_t*>(p), bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        *p = v;
+    }
+}
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
@@ -419,7 +432,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         for (int v = 0; v < 16; ++v) {
                             const uint32_t row = m0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + rowh + (v % 4);
                             const float g = acc[i][2 * jp][v], u = acc[i][2 * jp + 1][v];
-                            if (row < sM && col < sN) Cp[(size_t)row * ldc + col] = (T)(silu_f(g) * u);
+                            if (row < sM && col < sN) store_out<SYNC>(Cp + (size_t)row * ldc + col, (T)(silu_f(g) * u));
                         }
                     }
             }
@@ -435,7 +448,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         float x = acc[i][j][v];
                         if (act == ACT_GELU) x = gelu_erf(x);
                         else if (act == ACT_RELU) x = fmaxf(x, 0.0f);
-                        if (row < sM && col < sN) Cp[(size_t)row * ldc + col] = (T)x;
+                        if (row < sM && col < sN) store_out<SYNC>(Cp + (size_t)row * ldc + col, (T)x);
                     }
                 }
         }

@@ -38,8 +38,9 @@ const TileShape* tile_shape(int tile) {
         {64, 64, 2, 32},
         {256, 192, 1, 96},
         {128, 192, 2, 96},
+        {256, 64, 2, 64},
     };
-    if (tile < 1 || tile > 8) return nullptr;
+    if (tile < 1 || tile > 9) return nullptr;
     return &shapes[tile];
 }
 

@@ -10,8 +10,8 @@
 //    it waits for are held by resident workgroups that never wait or are still ahead of every
 //    consumer in their queue, so every semaphore is eventually posted whatever the dispatcher
 //    does.
-//  * post: every wave drains its stores, the workgroup meets at a barrier, one lane does an
-//    agent-scope release increment of the tile's semaphore (Section III-D).
+//  * post: every wave drains its write-through stores, the workgroup meets at a barrier, one
+//    lane increments the tile's semaphore at agent scope (Section III-D).
 //  * wait: every wave polls the same semaphore word (all lanes read one address, the result
 //    is made scalar, so the spin loop is wave-uniform) and sleeps between polls.  No lane-0
 //    branch, no extra barrier, and no cache invalidate (see dep_wait in gemm_tile.hpp for why
@@ -115,8 +115,7 @@ __device__ __forceinline__ uint32_t policy_sem(uint32_t kind, uint32_t x, uint32
 // post (Section III-D): called by all threads of the workgroup after the tile's stores.
 __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s, uint32_t tile_lin, uint32_t x, uint32_t y) {
     if (s.post_kind == DEP_NONE) return;
-    // every wave's stores have left the wave (vmcnt) before the barrier; the one release below
-    // then writes the XCD's L2 back once for the whole tile
+    // every wave's (write-through) stores have completed before the barrier
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -124,12 +123,12 @@ __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s
             for (uint32_t i = 0; i < a.delay_iters; ++i) __builtin_amdgcn_s_sleep(127);
         }
         uint32_t idx = policy_sem(s.post_kind, x, y, s.grid_y, s.post_stride);
-        // Release, spelled out: write this XCD's L2 back and WAIT for the write-back before the
-        // semaphore moves.  A release-ordered atomic is not used because the compiler drops the
-        // wait between its write-back and its atomic when it sees no other vector memory
-        // operation pending (as here, right after the vmcnt(0) above), and then a consumer on
-        // another XCD can see the semaphore before the tile's data has reached memory.
-        asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
+        // Release: the tile's output was stored with agent-scope (write-through) stores, all of
+        // which have completed (vmcnt(0) of every wave, then the barrier), so no write-back of
+        // the L2 is needed before the semaphore moves; a relaxed increment is enough.  (A
+        // release-ordered atomic would write the whole L2 back, and the compiler drops the wait
+        // between that write-back and the increment when it sees no vector memory operation
+        // pending, which let consumers on other XCDs read stale memory.)
         __hip_atomic_fetch_add(&s.post_sems[idx * SYNC_WORD_STRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a.flags & DS_FLAG_COUNT)
             __hip_atomic_fetch_add(&a.status->posts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -151,7 +150,9 @@ __device__ __forceinline__ uint32_t xcc_id() {
 // Tile dispatch (Sections III-B and III-C).  Every stage has one queue per XCD (each XCD has
 // its own L2): queue q of a stage holds the stage's tiles whose column tile index is congruent
 // to q mod 8, in row-major order, so that the tiles an XCD works on share operand rows and
-// columns.  A workgroup of ANY launch of the chain takes a tile of the earliest stage that
+// columns.  A stage with fewer than 8 column tiles (a convolution with few output channels)
+// would leave queues empty that way; there queue q holds the tiles whose row-major index is
+// congruent to q mod 8.  A workgroup of ANY launch of the chain takes a tile of the earliest stage that
 // still has undrawn tiles, from the queue of the XCD it runs on if that one is not empty, else
 // from the next non-empty one.  Hence no consumer tile is handed out while a producer tile is
 // undrawn anywhere: a workgroup can only be waiting when every tile of the stage it waits for
@@ -159,7 +160,17 @@ __device__ __forceinline__ uint32_t xcc_id() {
 // A queue counter only grows: entry = counter - epoch * queue_length; a draw beyond the end
 // is undone, so after a chain every counter has advanced by exactly its queue length.
 __device__ __forceinline__ uint32_t queue_len(const StageDesc& st, uint32_t q) {
-    return ((st.grid_x + 7u - q) >> 3) * st.grid_y;
+    return st.queue_by_col ? ((st.grid_x + 7u - q) >> 3) * st.grid_y : (st.grid_x * st.grid_y + 7u - q) >> 3;
+}
+// Entry i of queue q -> tile (tx, ty).
+__device__ __forceinline__ void queue_entry(const StageDesc& st, uint32_t q, uint32_t i, uint32_t& tx, uint32_t& ty) {
+    if (st.queue_by_col) {
+        const uint32_t ncol = (st.grid_x + 7u - q) >> 3;
+        ty = i / ncol; tx = q + 8u * (i % ncol);
+    } else {
+        const uint32_t lin = q + 8u * i;
+        ty = lin / st.grid_x; tx = lin % st.grid_x;
+    }
 }
 
 template <bool SYNC>
@@ -204,7 +215,7 @@ __device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_sl
                     const uint32_t rot = (avail >> home) | (avail << (8u - home));
                     q = (home + (uint32_t)__builtin_ctz(rot & 0xffu)) & 7u;   // first non-empty from home
                 }
-                const uint32_t ncol = (st.grid_x + 7u - q) >> 3, len = ncol * st.grid_y;
+                const uint32_t len = queue_len(st, q);
                 if (len == 0) continue;
                 uint32_t i = __hip_atomic_fetch_add(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
                              a.epoch * len;
@@ -213,7 +224,7 @@ __device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_sl
                     continue;
                 }
                 if (s == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
-                stage = s; ty = i / ncol; tx = q + 8u * (i % ncol);
+                stage = s; queue_entry(st, q, i, tx, ty);
                 found = true;
             }
         }
