@@ -89,19 +89,21 @@ int device_cus(int n_cu) {
 }
 
 // Relative time per flop of the macro-tile shapes on a fully occupied CU, from measurements of
-// the GPT-3 MLP chain on MI355X (256x256 = 1): smaller tiles read more LDS and L2 bytes per flop.
+// the GPT-3 MLP chain at M = 2048 on MI355X (128x192 = 1): smaller tiles read more LDS and L2 bytes per flop.
 double tile_cost_factor(int tile) {
     switch (tile) {
-        case DEPSYNC_TILE_256x256: return 1.00;
-        case DEPSYNC_TILE_256x128: return 1.35;
-        case DEPSYNC_TILE_128x256: return 1.35;
+        case DEPSYNC_TILE_256x256: return 1.30;   // its synchronised variant spills registers around the tile loop
+        case DEPSYNC_TILE_256x128: return 1.12;
+        case DEPSYNC_TILE_128x256: return 1.10;
         case DEPSYNC_TILE_128x128: return 1.20;
         case DEPSYNC_TILE_64x128: return 1.6;
-        case DEPSYNC_TILE_256x192: return 1.13;
+        case DEPSYNC_TILE_64x64: return 2.3;
+        case DEPSYNC_TILE_256x192: return 1.18;
         case DEPSYNC_TILE_128x192: return 1.00;
-        case DEPSYNC_TILE_256x64: return 1.5;
+        case DEPSYNC_TILE_256x64: return 1.3;
         default: return 2.4;
     }
+}
 }
 
 // Pick one macro-tile for both stages by simulating the fine-grained schedule of the chain
@@ -416,12 +418,18 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     if (sync && (a.flags & DEPSYNC_FLAG_HW_ORDER) && mode == DEPSYNC_MODE_FINE && total > (uint32_t)p.slots)
         return DEPSYNC_EINVAL;
 
+    // With the dispatch queues a launch needs no more workgroups than fit on the chip at once:
+    // each keeps drawing tiles.  With tiles named by the block index (PLAIN, HW_ORDER) a launch
+    // has one workgroup per tile.
+    const bool queues = sync && !(a.flags & DEPSYNC_FLAG_HW_ORDER);
+    auto blocks = [&](uint32_t tiles) { return queues ? std::min<uint32_t>(tiles, (uint32_t)p.slots) : tiles; };
     if (mode == DEPSYNC_MODE_FUSED) {
         // all stages in one dispatch; needs one macro-tile shape for the whole chain
         for (int s = 1; s < p.n_stages; ++s)
             if (p.tile[s] != p.tile[0]) return DEPSYNC_ENOTIMPL;
         a.block_offset = 0;
-        HIP_TRY(launch_chain_kernel(p.tile[0], p.dtype, p.amode, true, total, sp, a));
+        a.stage_lo = 0; a.stage_hi = (uint32_t)p.n_stages - 1;
+        HIP_TRY(launch_chain_kernel(p.tile[0], p.dtype, p.amode, true, blocks(total), sp, a));
     } else {
         if (mode == DEPSYNC_MODE_FINE) {
             HIP_TRY(hipEventRecord(pol->ev_fork, sp));
@@ -432,7 +440,11 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
             // producer on the caller's stream; later stages on the second stream in FINE mode
             hipStream_t st = (mode == DEPSYNC_MODE_FINE && s > 0) ? sc : sp;
             a.block_offset = off;
-            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, p.n_tiles[s], st, a));
+            // a launch works on its own stage and, when launches overlap (FINE), first helps
+            // with whatever earlier stages have not been handed out yet
+            a.stage_lo = mode == DEPSYNC_MODE_FINE ? 0u : (uint32_t)s;
+            a.stage_hi = (uint32_t)s;
+            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, blocks(p.n_tiles[s]), st, a));
             off += p.n_tiles[s];
         }
         if (mode == DEPSYNC_MODE_FINE) {

@@ -62,9 +62,9 @@ __device__ __forceinline__ void attn_wait_qkv(WaitCtx& w, const StageDesc& s, ui
     }
 }
 
-template <typename T, bool SYNC>
+template <typename T, bool SYNC, class DR>
 __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc& s, uint32_t head, uint32_t qblk,
-                                          uint32_t rel_ticket, char* lds, uint64_t t_enter) {
+                                          uint32_t rel_ticket, char* lds, uint64_t t_enter, DR& dr) {
     using M = Mma<T>;
     using V8 = typename M::V8;
     typedef T T4 __attribute__((ext_vector_type(4)));
@@ -210,6 +210,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
         }
     }
 
+    dr.peek();   // the look at the dispatch queues for the next tile travels while the result is stored
     // ---- normalise and store: lane owns query qi, d = 32*db + 8*(v/4) + 4*h2 + v%4 ----
     if (wctx.ok && qi < seq) {
         const float inv = 1.0f / l_run;

@@ -90,6 +90,7 @@ struct ChainArgs {
     uint32_t* ticket;           // dispatch counters: [stage][XCD queue], 3 x 8
     uint32_t epoch;             // chains run on this workspace since its last reset
     uint32_t block_offset;      // HW order / PLAIN: ticket of this launch's block 0
+    uint32_t stage_lo, stage_hi; // stages the workgroups of this launch may draw tiles of
     uint32_t flags;             // DEPSYNC_FLAG_*
     uint32_t spin_limit;
     uint32_t delay_tile, delay_iters;

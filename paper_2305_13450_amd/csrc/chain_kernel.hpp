@@ -15,6 +15,24 @@
 
 namespace depsync {
 
+template <class Cfg, typename T, bool SYNC, uint32_t AMODE, class DR>
+__device__ __forceinline__ void run_tile(const ChainArgs& args, const TileId t, char* lds, uint64_t t_enter, DR& dr) {
+    const StageDesc& s = args.st[t.stage];
+    if constexpr (AMODE == A_DENSE) {
+        if (s.op == OP_ATTN) {   // middle stage of the attention chain
+            attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+            return;
+        }
+    }
+    if constexpr (SYNC) {
+        if (s.dep_kind != DEP_NONE) {
+            gemm_tile<Cfg, T, true, AMODE, true>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+            return;
+        }
+    }
+    gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+}
+
 template <class Cfg, typename T, bool SYNC, uint32_t AMODE>
 __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs args) {
     // One LDS object only: with a second one the compiler can no longer tell the DMA writes
@@ -22,24 +40,23 @@ __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs a
     static_assert(Cfg::LDS_BYTES >= ATT_LDS_BYTES, "the attention tile stages its K and V blocks in the same LDS");
     __shared__ __attribute__((aligned(1024))) char lds[Cfg::LDS_BYTES];
 
-    uint64_t t_enter = 0;
-    if (SYNC && (args.flags & DS_FLAG_TRACE)) t_enter = now_ticks();
-    const TileId t = draw_tile<SYNC>(args, reinterpret_cast<uint32_t*>(lds));
-    if (t.rel == 0xffffffffu) return;
-    const StageDesc& s = args.st[t.stage];
-    if constexpr (AMODE == A_DENSE) {
-        if (s.op == OP_ATTN) {   // middle stage of the attention chain
-            attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter);
-            return;
+    if constexpr (!SYNC) {
+        // hooks compiled out: one tile per workgroup, named by the hardware's block index
+        NoDrawer nd;
+        run_tile<Cfg, T, false, AMODE>(args, hw_order_tile(args), lds, 0, nd);
+    } else {
+        Drawer dr(args, reinterpret_cast<uint32_t*>(lds));
+        const bool hw_order = (args.flags & DS_FLAG_HW_ORDER) != 0;   // one tile, from the block index
+        if (hw_order) dr.open = args.stage_hi + 1;                    // nothing to draw
+        for (;;) {
+            uint64_t t_enter = 0;
+            if (args.flags & DS_FLAG_TRACE) t_enter = now_ticks();
+            const TileId t = hw_order ? hw_order_tile(args) : dr.next();
+            if (t.rel == 0xffffffffu) return;
+            run_tile<Cfg, T, true, AMODE>(args, t, lds, t_enter, dr);
+            if (hw_order) return;
         }
     }
-    if constexpr (SYNC) {
-        if (s.dep_kind != DEP_NONE) {
-            gemm_tile<Cfg, T, true, AMODE, true>(args, s, t.tx, t.ty, t.rel, lds, t_enter);
-            return;
-        }
-    }
-    gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds, t_enter);
 }
 
 //                        TM   TN  WM WN  workgroups per CU, LDS stages

@@ -167,9 +167,9 @@ __device__ __forceinline__ const char* uni_ptr(const void* p) {
 
 // DEP: this tile's A operand is produced by the previous stage of the chain (the tile waits
 // on semaphores before it requests a slice of A).
-template <class Cfg, typename T, bool SYNC, uint32_t AMODE, bool DEP>
+template <class Cfg, typename T, bool SYNC, uint32_t AMODE, bool DEP, class DR>
 __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc& s, uint32_t tx, uint32_t ty,
-                                          uint32_t rel_ticket, char* lds, uint64_t t_enter) {
+                                          uint32_t rel_ticket, char* lds, uint64_t t_enter, DR& dr) {
     using M = Mma<T>;
     using V8 = typename M::V8;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, FM = Cfg::FM, FN = Cfg::FN;
@@ -413,6 +413,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     }
     // every DMA into LDS has landed before the staging area is given up
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    dr.peek();   // the look at the dispatch queues for this workgroup's next tile travels during the epilogue
 
     // ---- epilogue: activation, round to 16 bits, store ----
     // Accumulator layout of the 32x32 block: lane holds column (lane % 32) and rows

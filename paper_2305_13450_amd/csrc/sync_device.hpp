@@ -5,7 +5,7 @@
 //    first and adds a one-thread "wait kernel" to order the launches (Section III-B).  HIP
 //    makes no such promise across hardware queues, so here EVERY workgroup of every launch of
 //    a chain draws its tile from shared dispatch queues in which all producer tiles come
-//    before the consumer tiles, each stage in row-major order (Section III-C); see draw_tile.
+//    before the consumer tiles, each stage in row-major order (Section III-C); see Drawer.
 //    A workgroup can only be spinning while it holds a consumer tile, and the producer tiles
 //    it waits for are held by resident workgroups that never wait or are still ahead of every
 //    consumer in their queue, so every semaphore is eventually posted whatever the dispatcher
@@ -173,38 +173,71 @@ __device__ __forceinline__ void queue_entry(const StageDesc& st, uint32_t q, uin
     }
 }
 
-template <bool SYNC>
-__device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_slot) {
+// Tile named by the hardware's block index (hooks compiled out, or DEPSYNC_FLAG_HW_ORDER).
+__device__ __forceinline__ TileId hw_order_tile(const ChainArgs& a) {
     TileId t;
-    if (!SYNC || (a.flags & DS_FLAG_HW_ORDER)) {
-        const uint32_t rel = a.block_offset + blockIdx.x;
-        uint32_t stage = 0;
-        if (a.n_stages > 1 && rel >= a.first_ticket[1]) stage = 1;
-        if (a.n_stages > 2 && rel >= a.first_ticket[2]) stage = 2;
-        const uint32_t lin = rel - a.first_ticket[stage], gx = a.st[stage].grid_x;
-        t.stage = stage; t.tx = lin % gx; t.ty = lin / gx; t.rel = rel;
-        return t;
-    }
-    if (threadIdx.x == 0) {
-        const uint32_t home = xcc_id();
-        uint32_t stage = 0, tx = 0, ty = 0;
-        bool found = false;
-        // Workgroups that were launched for the first stage go straight for their XCD's queue of
-        // that stage (one atomic in the common case).  Otherwise a workgroup looks at a stage's
-        // eight counters and only then increments one that still has entries: a failed
-        // increment (undone at once) can happen at most once per queue, so a crowd of
-        // workgroups arriving together cannot turn into a storm of atomics on empty queues.
-        bool direct = a.block_offset + blockIdx.x < a.first_ticket[1];
-        for (uint32_t s = 0; s < a.n_stages && !found; ++s) {
-            const StageDesc& st = a.st[s];
-            uint32_t* cnt = a.ticket + 8u * s * SYNC_WORD_STRIDE;
-            for (uint32_t attempt = 0; attempt < 10 && !found; ++attempt) {
-                uint32_t q = home;
-                if (!(direct && s == 0 && attempt == 0)) {
-                    uint32_t c[8];
+    const uint32_t rel = a.block_offset + blockIdx.x;
+    uint32_t stage = 0;
+    if (a.n_stages > 1 && rel >= a.first_ticket[1]) stage = 1;
+    if (a.n_stages > 2 && rel >= a.first_ticket[2]) stage = 2;
+    const uint32_t lin = rel - a.first_ticket[stage], gx = a.st[stage].grid_x;
+    t.stage = stage; t.tx = lin % gx; t.ty = lin / gx; t.rel = rel;
+    return t;
+}
+
+// Dispatch state of one workgroup.  Workgroups are persistent: a launch has no more of them
+// than fit on the chip at once and each keeps drawing tiles until the stages it may work on
+// (stage_lo..stage_hi of the launch) are handed out.  That keeps the XCDs balanced whatever
+// the tiles' durations are: workgroup i always runs on XCD i mod 8, so with one workgroup per
+// tile an XCD that happened to get the long tiles would still have to run its share of the
+// rest.  The draws are made by the first lane of wave 1 (wave 0's first lane does the post).
+// A draw first looks at the eight counters of the earliest stage not known to be handed out
+// and only then increments one that still has entries, so exhausted queues see loads, not
+// atomics; the look for the NEXT tile is started when the current tile's K loop ends (peek)
+// and is in flight during the epilogue.
+constexpr uint32_t DRAW_THREAD = 64;
+
+struct Drawer {
+    const ChainArgs& a;
+    uint32_t* slot;        // four words of LDS used to broadcast a tile to the workgroup
+    uint32_t home;         // XCD this workgroup runs on
+    uint32_t open;         // first stage not yet known to be handed out completely
+    uint32_t c[8];         // counters of stage `open` as read by peek()
+    bool peeked;
+    bool first;
+
+    __device__ __forceinline__ Drawer(const ChainArgs& args, uint32_t* lds_slot)
+        : a(args), slot(lds_slot), home(xcc_id()), open(args.stage_lo), peeked(false), first(true) {}
+
+    __device__ __forceinline__ void load_counters() {
+        const uint32_t* cnt = a.ticket + 8u * open * SYNC_WORD_STRIDE;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        c[j] = __hip_atomic_load(cnt + j * SYNC_WORD_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int j = 0; j < 8; ++j)
+            c[j] = __hip_atomic_load(cnt + j * SYNC_WORD_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+
+    // Start reading the counters for the next draw (the values are not looked at here, so the
+    // loads stay in flight behind whatever the wave does next).
+    __device__ __forceinline__ void peek() {
+        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi) return;
+        load_counters();
+        peeked = true;
+    }
+
+    // DRAW_THREAD: draw a tile (blocking).
+    __device__ __forceinline__ bool draw(uint32_t& stage, uint32_t& tx, uint32_t& ty) {
+        // a workgroup launched for the first stage it may work on goes straight for its XCD's
+        // queue the first time (one round trip)
+        bool direct = first && a.block_offset + blockIdx.x < a.first_ticket[a.stage_lo + 1];
+        first = false;
+        for (; open <= a.stage_hi; ++open, peeked = false) {
+            const StageDesc& st = a.st[open];
+            uint32_t* cnt = a.ticket + 8u * open * SYNC_WORD_STRIDE;
+            for (uint32_t attempt = 0; attempt < 16; ++attempt) {
+                uint32_t q = home;
+                if (!direct) {
+                    if (!peeked) load_counters();
+                    peeked = false;
                     uint32_t avail = 0;
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
@@ -215,6 +248,7 @@ __device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_sl
                     const uint32_t rot = (avail >> home) | (avail << (8u - home));
                     q = (home + (uint32_t)__builtin_ctz(rot & 0xffu)) & 7u;   // first non-empty from home
                 }
+                direct = false;
                 const uint32_t len = queue_len(st, q);
                 if (len == 0) continue;
                 uint32_t i = __hip_atomic_fetch_add(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
@@ -223,23 +257,38 @@ __device__ __forceinline__ TileId draw_tile(const ChainArgs& a, uint32_t* lds_sl
                     __hip_atomic_fetch_sub(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     continue;
                 }
-                if (s == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
-                stage = s; queue_entry(st, q, i, tx, ty);
-                found = true;
+                if (open == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
+                stage = open; queue_entry(st, q, i, tx, ty);
+                return true;
             }
+            // 16 lost races in a row: whatever is left of this stage is being taken by others
         }
-        lds_slot[0] = stage; lds_slot[1] = tx; lds_slot[2] = ty; lds_slot[3] = found ? 1u : 0u;
+        return false;
     }
-    __syncthreads();
-    t.stage = __builtin_amdgcn_readfirstlane(lds_slot[0]);
-    t.tx = __builtin_amdgcn_readfirstlane(lds_slot[1]);
-    t.ty = __builtin_amdgcn_readfirstlane(lds_slot[2]);
-    const uint32_t found = __builtin_amdgcn_readfirstlane(lds_slot[3]);
-    __syncthreads();   // the slot is part of the operand staging area: everyone has read it before reuse
-    // Exactly as many workgroups are launched as there are tiles, so a draw cannot come back
-    // empty; if the counters were corrupted it does, and the workgroup leaves without a tile.
-    t.rel = found ? a.first_ticket[t.stage] + t.ty * a.st[t.stage].grid_x + t.tx : 0xffffffffu;
-    return t;
-}
+
+    // All threads: the next tile of this workgroup (rel = 0xffffffff when there is none).
+    __device__ __forceinline__ TileId next() {
+        __syncthreads();   // the slot is part of the operand staging area: the last tile is done with it
+        if (threadIdx.x == DRAW_THREAD) {
+            uint32_t stage = 0, tx = 0, ty = 0;
+            const bool found = draw(stage, tx, ty);
+            slot[0] = stage; slot[1] = tx; slot[2] = ty; slot[3] = found ? 1u : 0u;
+        }
+        __syncthreads();
+        TileId t;
+        t.stage = __builtin_amdgcn_readfirstlane(slot[0]);
+        t.tx = __builtin_amdgcn_readfirstlane(slot[1]);
+        t.ty = __builtin_amdgcn_readfirstlane(slot[2]);
+        const uint32_t found = __builtin_amdgcn_readfirstlane(slot[3]);
+        __syncthreads();   // everyone has read the slot before the next tile's operands land on it
+        t.rel = found ? a.first_ticket[t.stage] + t.ty * a.st[t.stage].grid_x + t.tx : 0xffffffffu;
+        return t;
+    }
+};
+
+// Stand-in where tiles come from the hardware's block index (nothing to look ahead for).
+struct NoDrawer {
+    __device__ __forceinline__ void peek() {}
+};
 
 }  // namespace depsync
