@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--policy", default="auto", choices=["auto", "row", "tile", "strided"])
     ap.add_argument("--tile", type=int, default=0, help="depsync_tile id, 0 = library's choice")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-autotune", action="store_true", help="use the library's model-based tile choice")
     ap.add_argument("--cpu-rows", type=int, default=384, help="rows of X the CPU oracle is timed on")
     ap.add_argument("--modes", default="fine,fused,streamsync,plain")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
@@ -125,6 +126,10 @@ def main():
     # `steps` launches (the chip's clock follows its power and temperature history, so variants
     # timed one after the other are not comparable); a variant's latency is the median of its blocks.
     pols = {pn: ds.SyncPolicy(kinds[pn]) for pn in pol_names}
+    if args.tile == 0 and not args.no_autotune:
+        # outside the timed region: let the library time its macro-tile shapes on this chain once
+        for pn in pol_names:
+            ds.gemm_chain_autotune(X, W1t, H, W2t, Y, pols[pn], mid=mid, stream=sp, reps=3, **extra)
     plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pols[pol_names[0]], mid=mid, tile=args.tile, **extra)
     variants = [(pn, mn) for pn in pol_names for mn in want
                 if mn in ("fine", "fused") or pn == pol_names[0]]   # stream-sync / plain: first policy only

@@ -29,7 +29,7 @@ EXPORTS = [
     "dep_gemm_chain", "dep_conv_chain", "depsync_gemm_chain_plan", "depsync_conv_chain_plan",
     "depsync_row_major", "depsync_policy_sem", "depsync_policy_value", "depsync_wave_model",
     "depsync_sync_count", "depsync_simulate_chain", "depsync_strerror", "depsync_last_hip_error",
-    "depsync_tile_shape", "depsync_device_info",
+    "depsync_tile_shape", "depsync_device_info", "depsync_gemm_chain_autotune", "depsync_conv_chain_autotune",
 ]
 
 
@@ -116,6 +116,8 @@ def _lib() -> ctypes.CDLL:
         L.dep_conv_chain.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, vp, vp]
         L.depsync_gemm_chain_plan.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
         L.depsync_conv_chain_plan.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
+        L.depsync_gemm_chain_autotune.argtypes = [ctypes.POINTER(GemmChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
+        L.depsync_conv_chain_autotune.argtypes = [ctypes.POINTER(ConvChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
         L.depsync_row_major.argtypes = [i32] * 4
         L.depsync_policy_sem.argtypes = [i32] * 6
         L.depsync_policy_value.argtypes = [i32] * 4
@@ -257,6 +259,24 @@ def gemm_chain_plan(X, W1t, H, W2t, Y, policy: Optional[SyncPolicy], mid: int = 
     _check(_lib().depsync_gemm_chain_plan(ctypes.byref(d), policy.handle if policy else None, n_cu,
                                           ctypes.byref(info)), "depsync_gemm_chain_plan")
     return info
+
+
+def gemm_chain_autotune(X, W1t, H, W2t, Y, policy: SyncPolicy, mid: int = MID_GELU, stream=None, reps: int = 3,
+                        **attn) -> int:
+    """Time every macro-tile shape on this chain and make the fastest the library's choice for it."""
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, TILE_AUTO, **attn)
+    tile = ctypes.c_int(0)
+    _check(_lib().depsync_gemm_chain_autotune(ctypes.byref(d), policy.handle, _stream_handle(stream), reps,
+                                              ctypes.byref(tile)), "depsync_gemm_chain_autotune")
+    return tile.value
+
+
+def conv_chain_autotune(x, w1, mid, w2, out, policy: SyncPolicy, stream=None, reps: int = 3) -> int:
+    d = _conv_desc(x, w1, mid, w2, out, TILE_AUTO)
+    tile = ctypes.c_int(0)
+    _check(_lib().depsync_conv_chain_autotune(ctypes.byref(d), policy.handle, _stream_handle(stream), reps,
+                                              ctypes.byref(tile)), "depsync_conv_chain_autotune")
+    return tile.value
 
 
 def _conv_desc(x, w1, mid, w2, out, tile) -> ConvChainDesc:

@@ -5,6 +5,8 @@
 #include <algorithm>
 #include <cstdint>
 #include <cstring>
+#include <map>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -104,6 +106,27 @@ double tile_cost_factor(int tile) {
         default: return 2.4;
     }
 }
+
+// Tiles found fastest by depsync_*_chain_autotune, per chain shape (and policy kind, which
+// changes what overlaps).  Looked up before the model below when the caller leaves the tile
+// to the library.
+struct TuneKey {
+    int64_t v[10];
+    bool operator<(const TuneKey& o) const { return std::lexicographical_compare(v, v + 10, o.v, o.v + 10); }
+};
+std::map<TuneKey, int> g_tuned;
+std::mutex g_tuned_mutex;
+
+TuneKey tune_key(const depsync_gemm_chain_desc* d, const sync_policy* pol) {
+    return TuneKey{{0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq}};
+}
+TuneKey tune_key(const depsync_conv_chain_desc* d, const sync_policy* pol) {
+    return TuneKey{{1, d->B, d->H, d->W, d->C, d->K1, d->K2, d->dtype, pol ? pol->kind : -1, 0}};
+}
+int tuned_tile(const TuneKey& k) {
+    std::lock_guard<std::mutex> g(g_tuned_mutex);
+    auto it = g_tuned.find(k);
+    return it == g_tuned.end() ? 0 : it->second;
 }
 
 // Pick one macro-tile for both stages by simulating the fine-grained schedule of the chain
@@ -182,6 +205,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     const int cus = device_cus(n_cu);
     if (cus <= 0) return DEPSYNC_EHIP;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
+    if (!tile) tile = tuned_tile(tune_key(d, pol));
     if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
     const TileShape* ts = tile_shape(tile);
     if (!ts) return DEPSYNC_EINVAL;
@@ -276,6 +300,7 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     if (cus <= 0) return DEPSYNC_EHIP;
     const uint32_t M = (uint32_t)Mpix;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
+    if (!tile) tile = tuned_tile(tune_key(d, pol));
     if (!tile) {
         // halo: a consumer row tile reads W+1 rows beyond each end
         tile = choose_tile(M, d->K1, 9 * d->C, d->K2, 9 * d->K1, false, cus, 1);
@@ -635,6 +660,65 @@ int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync
     s1.H = d->H; s1.W = d->W; s1.Cin = d->K1;
     fill_common(a, pol, p, epoch);
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
+}
+
+}  // extern "C"
+
+namespace {
+// Time every macro-tile shape the chain can run with (one-dispatch mode, `reps` launches after
+// one warm-up, HIP events on the caller's stream) and remember the fastest.
+template <class Desc, class Run>
+int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* tile_out, Run run) {
+    if (!d || !pol) return DEPSYNC_EINVAL;
+    if (reps <= 0) reps = 3;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e); }
+    int best = 0, rc = DEPSYNC_OK;
+    float best_ms = 0.f;
+    for (int t = 1; t < DEPSYNC_TILE__COUNT && rc == DEPSYNC_OK; ++t) {
+        Desc dd = *d;
+        dd.tile_prod = dd.tile_cons = t;
+        int r = run(&dd);                       // warm-up; also tells whether this shape is usable
+        if (r == DEPSYNC_EINVAL || r == DEPSYNC_ENOTIMPL || r == DEPSYNC_ENOMEM) continue;
+        if (r != DEPSYNC_OK) { rc = r; break; }
+        hipError_t e = hipEventRecord(e0, sp);
+        for (int i = 0; i < reps && r == DEPSYNC_OK; ++i) r = run(&dd);
+        if (e == hipSuccess) e = hipEventRecord(e1, sp);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) { rc = hip_fail(e); break; }
+        if (r != DEPSYNC_OK) { rc = r; break; }
+        if (best == 0 || ms < best_ms) { best = t; best_ms = ms; }
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (rc != DEPSYNC_OK) return rc;
+    if (best == 0) return DEPSYNC_EINVAL;
+    {
+        std::lock_guard<std::mutex> g(g_tuned_mutex);
+        g_tuned[tune_key(d, pol)] = best;
+    }
+    if (tile_out) *tile_out = best;
+    return DEPSYNC_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int depsync_gemm_chain_autotune(const depsync_gemm_chain_desc* d, sync_policy_t* pol, void* stream, int reps,
+                                int* tile_out) {
+    return autotune(d, pol, static_cast<hipStream_t>(stream), reps, tile_out, [&](const depsync_gemm_chain_desc* dd) {
+        return dep_gemm_chain(dd, pol, DEPSYNC_MODE_FUSED, stream, nullptr);
+    });
+}
+
+int depsync_conv_chain_autotune(const depsync_conv_chain_desc* d, sync_policy_t* pol, void* stream, int reps,
+                                int* tile_out) {
+    return autotune(d, pol, static_cast<hipStream_t>(stream), reps, tile_out, [&](const depsync_conv_chain_desc* dd) {
+        return dep_conv_chain(dd, pol, DEPSYNC_MODE_FUSED, stream, nullptr);
+    });
 }
 
 const char* depsync_strerror(int status) {

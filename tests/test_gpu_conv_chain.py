@@ -119,3 +119,19 @@ def test_posted_tiles_are_visible_on_every_xcd_repeated():
                 differ += int(not (torch.equal(out, ref_out) and torch.equal(mid, ref_mid)))
             assert differ == 0, (kind, mode, differ)
         pol.destroy()
+
+
+def test_conv_autotune_picks_a_tile_the_library_then_uses():
+    t = inputs.conv(2, 20, 24, 64, 128, 64, seed=29)
+    x, w1, w2 = t["x"].cuda(), t["w1"].cuda(), t["w2"].cuda()
+    mid = torch.empty((2, 20, 24, 128), dtype=x.dtype, device="cuda")
+    out = torch.empty((2, 20, 24, 64), dtype=x.dtype, device="cuda")
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    tile = ds.conv_chain_autotune(x, w1, mid, w2, out, pol, reps=2)
+    assert ds.conv_chain_plan(x, w1, mid, w2, out, pol).tile_prod == tile
+    mref, oref = oracle.conv_chain(inputs.to_f64(t["x"]), inputs.to_f64(t["w1"]), inputs.to_f64(t["w2"]))
+    a = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_FINE)
+    b = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_STREAMSYNC)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    assert rel_err(a[1], oref) <= TOL_BF16
+    pol.destroy()

@@ -233,3 +233,21 @@ def test_invalid_arguments_are_rejected_before_any_launch():
         ds.dep_gemm_chain(X.view(-1)[1:1 + 63 * 128].view(63, 128), W1t, H[:63], W2t, Y[:63], pol)
     assert e.value.status == ds.EINVAL
     pol.destroy()
+
+
+def test_autotune_picks_a_tile_the_library_then_uses():
+    M, K1, N1, N2 = 320, 256, 768, 384      # a shape no other test uses (the choice is kept per shape)
+    t = inputs.mlp(M, K1, N1, N2, seed=23)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    X, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
+    H = torch.empty((M, N1), dtype=X.dtype, device="cuda")
+    Y = torch.empty((M, N2), dtype=X.dtype, device="cuda")
+    pol = ds.SyncPolicy(ds.TILESYNC)
+    tile = ds.gemm_chain_autotune(X, W1t, H, W2t, Y, pol, reps=2)
+    assert 1 <= tile < 10
+    assert ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol).tile_prod == tile
+    res = [run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode) for mode in MODES]
+    for Hm, Ym in res:
+        assert mid_err(Hm, Href) <= TOL_MID and rel_err(Ym, Yref) <= TOL_BF16
+        assert torch.equal(Hm, res[0][0]) and torch.equal(Ym, res[0][1])
+    pol.destroy()
