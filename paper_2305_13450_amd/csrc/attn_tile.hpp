@@ -233,7 +233,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
             }
     }
 
-    if (SYNC) post_tile(args, s, qblk * heads + head, head, qblk);
+    if (SYNC) post_tile<true>(args, s, qblk * heads + head, head, qblk);
     if (tracing && tid == 0) {
         TraceRec r;
         r.rel = rel_ticket; r.where = hw_where(2u); r.tx = head; r.ty = qblk;

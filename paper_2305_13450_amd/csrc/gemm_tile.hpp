@@ -175,6 +175,11 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     constexpr int TM = Cfg::TM, TN = Cfg::TN, FM = Cfg::FM, FN = Cfg::FN;
     constexpr int NIA = Cfg::NIA, NIB = Cfg::NIB;
     static_assert(!DEP || SYNC, "dependencies exist only with the synchronisation hooks compiled in");
+    // A tile without a dependency is a chain's first stage, whose output the next stage waits
+    // for: it is stored write-through so that the post needs no L2 write-back.  A dependent GeMM
+    // tile is the last stage of every chain built here and stores normally (should it ever have
+    // to post, post_tile writes the L2 back for it).
+    constexpr bool THROUGH = SYNC && !DEP;
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = uni(tid >> 6);
@@ -433,7 +438,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         for (int v = 0; v < 16; ++v) {
                             const uint32_t row = m0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + rowh + (v % 4);
                             const float g = acc[i][2 * jp][v], u = acc[i][2 * jp + 1][v];
-                            if (row < sM && col < sN) store_out<SYNC>(Cp + (size_t)row * ldc + col, (T)(silu_f(g) * u));
+                            if (row < sM && col < sN) store_out<THROUGH>(Cp + (size_t)row * ldc + col, (T)(silu_f(g) * u));
                         }
                     }
             }
@@ -449,13 +454,13 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         float x = acc[i][j][v];
                         if (act == ACT_GELU) x = gelu_erf(x);
                         else if (act == ACT_RELU) x = fmaxf(x, 0.0f);
-                        if (row < sM && col < sN) store_out<SYNC>(Cp + (size_t)row * ldc + col, (T)x);
+                        if (row < sM && col < sN) store_out<THROUGH>(Cp + (size_t)row * ldc + col, (T)x);
                     }
                 }
         }
     }
 
-    if (SYNC) post_tile(args, s, ty * s.grid_x + tx, tx, ty);
+    if (SYNC) post_tile<THROUGH>(args, s, ty * s.grid_x + tx, tx, ty);
     if (tracing && tid == 0) {
         TraceRec r;
         r.rel = rel_ticket; r.where = hw_where(DEP ? 1u : 0u); r.tx = tx; r.ty = ty;

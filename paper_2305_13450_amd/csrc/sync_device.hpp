@@ -113,6 +113,7 @@ __device__ __forceinline__ uint32_t policy_sem(uint32_t kind, uint32_t x, uint32
 }
 
 // post (Section III-D): called by all threads of the workgroup after the tile's stores.
+template <bool THROUGH>
 __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s, uint32_t tile_lin, uint32_t x, uint32_t y) {
     if (s.post_kind == DEP_NONE) return;
     // every wave's (write-through) stores have completed before the barrier
@@ -128,7 +129,9 @@ __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s
         // the L2 is needed before the semaphore moves; a relaxed increment is enough.  (A
         // release-ordered atomic would write the whole L2 back, and the compiler drops the wait
         // between that write-back and the increment when it sees no vector memory operation
-        // pending, which let consumers on other XCDs read stale memory.)
+        // pending, which let consumers on other XCDs read stale memory.)  A tile that was stored
+        // with ordinary stores has the write-back and its wait spelled out here.
+        if constexpr (!THROUGH) asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
         __hip_atomic_fetch_add(&s.post_sems[idx * SYNC_WORD_STRIDE], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (a.flags & DS_FLAG_COUNT)
             __hip_atomic_fetch_add(&a.status->posts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
