@@ -1,10 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the dependent-chain hot path on one MI355X.
 
-A "step" is one pass of the whole hot path over one batch of synthetic input: the two
-dependent GeMMs of the GPT-3 MLP shard (X[M,12288] W1[12288,6144] -> GeLU -> W2[6144,12288],
-bf16, M = 2048) launched with fine-grained synchronisation (two streams, or all stages in one dispatch).
+A "step" is one pass of the whole hot path over one batch of synthetic input: by default the two
+dependent GeMMs of the GPT-3 MLP shard (X[M,12288] W1[12288,6144] -> GeLU -> W2[6144,12288], bf16,
+M = 2048) launched with fine-grained synchronisation (two streams, or all stages in one dispatch).
 Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+`--sweep FILE` instead runs every configuration of the workload set (GeMM chains at all M, the
+attention chain, the VGG conv pairs) and writes a markdown table to FILE.
 """
 import argparse
 import json
@@ -32,7 +35,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--rounds", type=int, default=3, help="interleaved timing blocks per variant (comparison table)")
     ap.add_argument("--m", type=int, default=2048, help="tokens (rows of X)")
-    ap.add_argument("--workload", default="gpt3_mlp", choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "cfg1"])
+    ap.add_argument("--workload", default="gpt3_mlp", choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "cfg1", "vgg_conv"])
+    ap.add_argument("--hw", type=int, default=56, help="vgg_conv: image height = width")
+    ap.add_argument("--channels", type=int, default=256, help="vgg_conv: channels of all three tensors")
+    ap.add_argument("--batch", type=int, default=16, help="vgg_conv: images")
     ap.add_argument("--policy", default="auto", choices=["auto", "row", "tile", "strided"])
     ap.add_argument("--tile", type=int, default=0, help="depsync_tile id, 0 = library's choice")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -42,6 +48,7 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB three times, so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
+    ap.add_argument("--sweep", default=None, metavar="FILE", help="run all configurations, write a markdown table")
     return ap.parse_args()
 
 
@@ -59,6 +66,213 @@ def time_block(torch, call, sp, steps):
     return e0.elapsed_time(e1) * 1e3 / steps
 
 
+class Workload:
+    """Device buffers of one chain plus closures to plan, tune and launch it."""
+
+    def __init__(self, torch, ds, inputs, kind, M=2048, hw=56, channels=256, batch=16):
+        self.kind, self.M = kind, M
+        self.conv = kind == "vgg_conv"
+        self.attn = None
+        self.ds = ds
+        if self.conv:
+            t = inputs.conv(batch, hw, hw, channels, channels, channels)
+            self.t = t
+            self.x, self.w1, self.w2 = t["x"].cuda(), t["w1"].cuda(), t["w2"].cuda()
+            self.mid_t = torch.empty((batch, hw, hw, channels), dtype=self.x.dtype, device="cuda")
+            self.out = torch.empty_like(self.mid_t)
+            self.name = f"VGG conv pair {hw}x{hw}x{channels} -> ReLU -> {channels}, batch {batch}, 3x3 s1 p1, NHWC bf16"
+            self.policies = ["strided", "row", "tile"]
+            return
+        if kind == "gpt3_mlp":
+            t = inputs.mlp(M=M, K1=12288, N1=6144, N2=12288); self.mid = ds.MID_GELU; W1 = t["W1"]
+            self.name = f"GPT-3 MLP shard X[{M}x12288] W1[12288x6144] GeLU W2[6144x12288] bf16"
+        elif kind == "llama_mlp":
+            t = inputs.swiglu(M=M, K1=8192, Nh=2752, N2=8192); self.mid = ds.MID_SWIGLU; W1 = t["Wgu"]
+            self.name = f"LLaMA-65B MLP shard X[{M}x8192] [Wg|Wu][8192x5504] SwiGLU W2[2752x8192] bf16"
+        elif kind == "gpt3_attn":
+            c = inputs.CFG4; self.mid = ds.MID_CAUSAL_ATTN
+            t = inputs.attention(M, c["K1"], c["heads"], c["d"], c["N2"])
+            W1 = t["Wqkv"]; t["W2"] = t["Wo"]
+            self.attn = dict(batch=1, seq=M, heads=c["heads"], head_dim=c["d"])
+            self.name = (f"GPT-3 attention shard X[{M}x12288] Wqkv[12288x4608] causal attention 12 heads x 128 "
+                         f"(batch 1, seq {M}) Wo[1536x12288] bf16")
+        else:
+            shape = dict(inputs.CFG1); self.M = M = shape["M"]; self.mid = ds.MID_GELU
+            t = inputs.mlp(**shape); W1 = t["W1"]
+            self.name = "cfg1 X[256x1024] W1[1024x4096] GeLU W2[4096x1024] bf16"
+        self.t, self.W1 = t, W1
+        self.X = t["X"].cuda()
+        self.W1t = W1.t().contiguous().cuda()
+        self.W2t = t["W2"].t().contiguous().cuda()
+        n1 = self.W1t.shape[0] // 2 if self.mid == ds.MID_SWIGLU else self.W1t.shape[0]
+        self.H = torch.empty((M, n1), dtype=self.X.dtype, device="cuda")
+        self.Y = torch.empty((M, self.W2t.shape[0]), dtype=self.X.dtype, device="cuda")
+        self.extra = {}
+        if self.attn:
+            self.extra = dict(self.attn, T=torch.empty((M, self.attn["heads"] * self.attn["head_dim"]),
+                                                       dtype=self.X.dtype, device="cuda"))
+        self.policies = ["row", "tile", "strided"] if self.attn else ["row", "tile"]
+
+    def plan(self, pol, tile=0):
+        ds = self.ds
+        if self.conv:
+            return ds.conv_chain_plan(self.x, self.w1, self.mid_t, self.w2, self.out, pol, tile=tile)
+        return ds.gemm_chain_plan(self.X, self.W1t, self.H, self.W2t, self.Y, pol, mid=self.mid, tile=tile, **self.extra)
+
+    def autotune(self, pol, sp):
+        ds = self.ds
+        if self.conv:
+            return ds.conv_chain_autotune(self.x, self.w1, self.mid_t, self.w2, self.out, pol, stream=sp, reps=3)
+        return ds.gemm_chain_autotune(self.X, self.W1t, self.H, self.W2t, self.Y, pol, mid=self.mid, stream=sp,
+                                      reps=3, **self.extra)
+
+    def caller(self, pol, mode, tile, sp, sc):
+        ds = self.ds
+        if self.conv:
+            def call():
+                ds.dep_conv_chain(self.x, self.w1, self.mid_t, self.w2, self.out, pol, mode=mode, tile=tile,
+                                  stream_producer=sp, stream_consumer=sc)
+        else:
+            def call():
+                ds.dep_gemm_chain(self.X, self.W1t, self.H, self.W2t, self.Y, pol, mode=mode, mid=self.mid, tile=tile,
+                                  stream_producer=sp, stream_consumer=sc, **self.extra)
+        return call
+
+    def cpu_oracle(self, rows):
+        """Run the fp64 oracle on a bounded sample; returns (seconds, fraction of the chain's flops, text)."""
+        import inputs
+        import oracle
+        t = self.t
+        if self.conv:
+            B = t["x"].shape[0]
+            xs = inputs.to_f64(t["x"][:1])
+            w1, w2 = inputs.to_f64(t["w1"]), inputs.to_f64(t["w2"])
+            t0 = time.perf_counter()
+            oracle.conv_chain(xs, w1, w2)
+            return time.perf_counter() - t0, 1.0 / B, f"fp64 oracle timed on the first of {B} images (images are independent)"
+        rows = min(rows, self.M)
+        Xs = inputs.to_f64(t["X"][:rows])
+        W1f, W2f = inputs.to_f64(self.W1), inputs.to_f64(t["W2"])
+        t0 = time.perf_counter()
+        if self.attn:
+            # causal: the first `rows` tokens of the sequence need nothing from later tokens
+            oracle.attn_chain(Xs, W1f, W2f, 1, rows, self.attn["heads"], self.attn["head_dim"])
+        elif self.mid == self.ds.MID_SWIGLU:
+            oracle.swiglu_chain(Xs, W1f, W2f)
+        else:
+            oracle.gemm_chain(Xs, W1f, W2f, oracle.ACT_GELU)
+        dt = time.perf_counter() - t0
+        why = "rows are independent" + (", the attention of a prefix being a prefix of the attention" if self.attn else "")
+        return dt, rows / self.M, f"fp64 oracle timed on the first {rows} of {self.M} rows of X ({why})"
+
+
+def trace_occupancy(ds, torch, wl, kind, mode, tile, sp, sc, n_tiles, slots):
+    """Slot utilisation of one chain and occupancy of its final wave, from the per-tile trace
+    (None, None when the chain has more tiles than the trace holds)."""
+    if n_tiles > 8192:
+        return None, None
+    pol = ds.SyncPolicy(kind, flags=ds.FLAG_TRACE)
+    call = wl.caller(pol, mode, tile, sp, sc)
+    for _ in range(3):
+        call()
+    torch.cuda.synchronize()
+    recs = pol.read_trace(n_tiles)
+    pol.destroy()
+    t0 = min(r.t_enter for r in recs)
+    t1 = max(r.t_end for r in recs)
+    busy = sum(r.t_end - r.t_ready for r in recs)
+    util = busy / (slots * max(t1 - t0, 1))
+    last = recs[-(n_tiles // 4 or 1):]
+    dur = sorted(r.t_end - r.t_ready for r in last)[len(last) // 2]        # median tile of the last stage
+    lo = t1 - dur
+    final = sum(max(0, min(r.t_end, t1) - max(r.t_ready, lo)) for r in recs) / (slots * max(dur, 1))
+    return util, final
+
+
+def measure(args, torch, ds, wl, sp, sc, want, pol_names=None, tile=0, autotune=True):
+    kinds = {"row": ds.ROWSYNC, "tile": ds.TILESYNC, "strided": ds.STRIDEDSYNC}
+    modes = {"fine": ds.MODE_FINE, "fused": ds.MODE_FUSED, "streamsync": ds.MODE_STREAMSYNC, "plain": ds.MODE_PLAIN}
+    pol_names = pol_names or wl.policies
+    # Every (policy, launch mode) variant is warmed up, then timed in `rounds` interleaved blocks of
+    # `steps` launches (the chip's clock follows its power and temperature history, so variants
+    # timed one after the other are not comparable); a variant's latency is the median of its blocks.
+    pols = {pn: ds.SyncPolicy(kinds[pn]) for pn in pol_names}
+    if tile == 0 and autotune:
+        # outside the timed region: let the library time its macro-tile shapes on this chain once
+        for pn in pol_names:
+            wl.autotune(pols[pn], sp)
+    variants = [(pn, mn) for pn in pol_names for mn in want
+                if mn in ("fine", "fused") or pn == pol_names[0]]   # stream-sync / plain: first policy only
+    calls = {(pn, mn): wl.caller(pols[pn], modes[mn], tile, sp, sc) for pn, mn in variants}
+    for v in variants:
+        for _ in range(args.warmup):
+            calls[v]()
+    blocks = {v: [] for v in variants}
+    for _ in range(args.rounds):
+        for v in variants:
+            blocks[v].append(time_block(torch, calls[v], sp, args.steps))
+    results = {v: sorted(b)[len(b) // 2] for v, b in blocks.items()}
+    # the fine-grained variants: two streams (FINE) or one dispatch (FUSED), per policy
+    fine = {v: results[v] for v in variants if v[1] in ("fine", "fused")}
+    best = min(fine, key=fine.get) if fine else variants[0]
+    # the headline: W warm-up launches, then exactly K timed launches of the best variant
+    for _ in range(args.warmup):
+        calls[best]()
+    lat = time_block(torch, calls[best], sp, args.steps)
+    best_plan = wl.plan(pols[best[0]], tile)
+    for pol in pols.values():
+        pol.status()
+        pol.destroy()
+    return dict(plan=best_plan, results=results, blocks=blocks, best=best, lat=lat, kinds=kinds, modes=modes,
+                ss=results.get((pol_names[0], "streamsync")), plain=results.get((pol_names[0], "plain")))
+
+
+def roofline(plan, lat_us):
+    flops, nbytes = plan.flops, plan.bytes
+    tflops = flops / (lat_us * 1e-6) / 1e12
+    if (nbytes / 8e12) > (flops / (PEAK_BF16_TFLOPS * 1e12)):
+        roof = {"bound": "hbm", "achieved": nbytes / (lat_us * 1e-6) / 1e9, "peak": 8000.0, "unit": "GB/s"}
+    else:
+        roof = {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    return roof, tflops
+
+
+def sweep(args, torch, ds, inputs):
+    """All configurations -> markdown table."""
+    sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    cases = [("cfg1", dict())]
+    cases += [("gpt3_mlp", dict(M=m)) for m in inputs.CFG2["Ms"]]
+    cases += [("llama_mlp", dict(M=m)) for m in inputs.CFG3["Ms"]]
+    cases += [("gpt3_attn", dict(M=m)) for m in inputs.CFG4["Ms"]]
+    cases += [("vgg_conv", dict(hw=hw, channels=ch, batch=b)) for hw, ch in inputs.CFG5["stages"] for b in (1, 16)]
+    lines = ["| workload | tile | P / (mid) / C tiles | slots | waves ss / fine | best fine-grained us (policy/launch) | "
+             "stream-sync us | plain us | speedup vs ss | vs plain | TFLOP/s | roofline | slot util. | final wave |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    fmt = lambda v: "-" if v is None else f"{v:.2f}"
+    for kind, kw in cases:
+        wl = Workload(torch, ds, inputs, kind, **kw)
+        r = measure(args, torch, ds, wl, sp, sc, ["fine", "fused", "streamsync", "plain"])
+        plan, lat = r["plan"], r["lat"]
+        roof, tflops = roofline(plan, lat)
+        n_tiles = plan.n_prod + plan.n_mid + plan.n_cons
+        util, final = trace_occupancy(ds, torch, wl, r["kinds"][r["best"][0]], r["modes"][r["best"][1]], 0, sp, sc,
+                                      n_tiles, plan.slots)
+        tm, tn = ds.tile_shape(plan.tile_prod)
+        mid = f" / {plan.n_mid}" if plan.n_mid else ""
+        lines.append(
+            f"| {wl.name} | {tm}x{tn} | {plan.n_prod}{mid} / {plan.n_cons} | {plan.slots} | "
+            f"{plan.waves_streamsync} / {plan.waves_fine} | {lat:.1f} ({r['best'][0]}/{r['best'][1]}) | {r['ss']:.1f} | "
+            f"{r['plain']:.1f} | {r['ss'] / lat:.3f} | {r['plain'] / lat:.3f} | {tflops:.0f} | "
+            f"{roof['bound']} {100 * roof['frac']:.1f} % | {fmt(util)} | {fmt(final)} |")
+        print(lines[-1], file=sys.stderr, flush=True)
+        del wl
+        torch.cuda.empty_cache()
+    with open(args.sweep, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print(json.dumps({"sweep": args.sweep, "rows": len(lines) - 2}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -73,40 +287,11 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     n_cu, clock_khz = ds.device_info()
+    if args.sweep:
+        return sweep(args, torch, ds, inputs)
 
-    M = args.m
-    attn = None
-    if args.workload == "gpt3_mlp":
-        shape = dict(M=M, K1=12288, N1=6144, N2=12288); mid = ds.MID_GELU
-        t = inputs.mlp(**shape)
-        W1 = t["W1"]
-        name = f"GPT-3 MLP shard X[{M}x12288] W1[12288x6144] GeLU W2[6144x12288] bf16"
-    elif args.workload == "llama_mlp":
-        shape = dict(M=M, K1=8192, Nh=2752, N2=8192); mid = ds.MID_SWIGLU
-        t = inputs.swiglu(**shape)
-        W1 = t["Wgu"]
-        name = f"LLaMA-65B MLP shard X[{M}x8192] [Wg|Wu][8192x5504] SwiGLU W2[2752x8192] bf16"
-    elif args.workload == "gpt3_attn":
-        c = inputs.CFG4; mid = ds.MID_CAUSAL_ATTN
-        t = inputs.attention(M, c["K1"], c["heads"], c["d"], c["N2"])
-        W1 = t["Wqkv"]; t["W2"] = t["Wo"]
-        attn = dict(batch=1, seq=M, heads=c["heads"], head_dim=c["d"])
-        name = (f"GPT-3 attention shard X[{M}x12288] Wqkv[12288x4608] causal attention 12 heads x 128 "
-                f"(batch 1, seq {M}) Wo[1536x12288] bf16")
-    else:
-        shape = dict(inputs.CFG1); M = shape["M"]; mid = ds.MID_GELU
-        t = inputs.mlp(**shape)
-        W1 = t["W1"]
-        name = "cfg1 X[256x1024] W1[1024x4096] GeLU W2[4096x1024] bf16"
-    X = t["X"].cuda()
-    W1t = W1.t().contiguous().cuda()
-    W2t = t["W2"].t().contiguous().cuda()
-    n1 = W1t.shape[0] // 2 if mid == ds.MID_SWIGLU else W1t.shape[0]
-    H = torch.empty((M, n1), dtype=X.dtype, device="cuda")
-    Y = torch.empty((M, W2t.shape[0]), dtype=X.dtype, device="cuda")
-    extra = {}
-    if attn:
-        extra = dict(attn, T=torch.empty((M, attn["heads"] * attn["head_dim"]), dtype=X.dtype, device="cuda"))
+    wl = Workload(torch, ds, inputs, args.workload, M=args.m, hw=args.hw, channels=args.channels, batch=args.batch)
+    M = wl.M
 
     if args.copy_calibration:
         src = torch.empty(args.copy_calibration << 20, dtype=torch.uint8, device="cuda").random_()
@@ -117,101 +302,45 @@ def main():
         del src, dst
 
     sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
-    kinds = {"row": ds.ROWSYNC, "tile": ds.TILESYNC, "strided": ds.STRIDEDSYNC}
-    pol_names = (["row", "tile", "strided"] if attn else ["row", "tile"]) if args.policy == "auto" else [args.policy]
-    modes = {"fine": ds.MODE_FINE, "fused": ds.MODE_FUSED, "streamsync": ds.MODE_STREAMSYNC, "plain": ds.MODE_PLAIN}
+    pol_names = wl.policies if args.policy == "auto" else [args.policy]
     want = [m for m in args.modes.split(",") if m]
-
-    # Every (policy, launch mode) variant is warmed up, then timed in `rounds` interleaved blocks of
-    # `steps` launches (the chip's clock follows its power and temperature history, so variants
-    # timed one after the other are not comparable); a variant's latency is the median of its blocks.
-    pols = {pn: ds.SyncPolicy(kinds[pn]) for pn in pol_names}
-    if args.tile == 0 and not args.no_autotune:
-        # outside the timed region: let the library time its macro-tile shapes on this chain once
-        for pn in pol_names:
-            ds.gemm_chain_autotune(X, W1t, H, W2t, Y, pols[pn], mid=mid, stream=sp, reps=3, **extra)
-    plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pols[pol_names[0]], mid=mid, tile=args.tile, **extra)
-    variants = [(pn, mn) for pn in pol_names for mn in want
-                if mn in ("fine", "fused") or pn == pol_names[0]]   # stream-sync / plain: first policy only
-
-    def caller(pn, mn):
-        pol, mode = pols[pn], modes[mn]
-        def call():
-            ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=mode, mid=mid, tile=args.tile,
-                              stream_producer=sp, stream_consumer=sc, **extra)
-        return call
-    calls = {v: caller(*v) for v in variants}
-    for v in variants:
-        for _ in range(args.warmup):
-            calls[v]()
-    blocks = {v: [] for v in variants}
-    for _ in range(args.rounds):
-        for v in variants:
-            blocks[v].append(time_block(torch, calls[v], sp, args.steps))
-    results = {v: sorted(b)[len(b) // 2] for v, b in blocks.items()}
-
-    # the fine-grained variants: two streams (FINE) or one dispatch (FUSED), per policy
-    fine = {v: results[v] for v in variants if v[1] in ("fine", "fused")}
-    best = min(fine, key=fine.get) if fine else variants[0]
-    best_pol, best_mode = best
-    # the headline: W warm-up launches, then exactly K timed launches of the best variant
-    for _ in range(args.warmup):
-        calls[best]()
-    lat = time_block(torch, calls[best], sp, args.steps)
-    ss = results.get((pol_names[0], "streamsync"))
-    plain = results.get((pol_names[0], "plain"))
-    for pol in pols.values():
-        pol.status()
-        pol.destroy()
-    flops, nbytes = plan.flops, plan.bytes
-    tflops = flops / (lat * 1e-6) / 1e12
-    hbm_bound = (nbytes / 8e12) > (flops / (PEAK_BF16_TFLOPS * 1e12))
-    if hbm_bound:
-        roof = {"bound": "hbm", "achieved": nbytes / (lat * 1e-6) / 1e9, "peak": 8000.0, "unit": "GB/s"}
-    else:
-        roof = {"bound": "mfma", "achieved": tflops, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s"}
-    roof["frac"] = roof["achieved"] / roof["peak"]
+    r = measure(args, torch, ds, wl, sp, sc, want, pol_names, tile=args.tile, autotune=not args.no_autotune)
+    plan, lat, results, blocks = r["plan"], r["lat"], r["results"], r["blocks"]
+    best_pol, best_mode = r["best"]
+    ss, plain = r["ss"], r["plain"]
+    roof, tflops = roofline(plan, lat)
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, M, best_mode)) if args.tile == 0 else None
-    roof["kernel"] = "chain_kernel (producer + consumer dispatches of one chain, which overlap)"
-    roof["per_launch"] = {"flops": flops, "bytes": nbytes, "duration_us": lat}
+    roof["kernel"] = "chain_kernel (all dispatches of one chain; one dispatch in fused mode)"
+    roof["per_launch"] = {"flops": plan.flops, "bytes": plan.bytes, "duration_us": lat}
+    n_tiles = plan.n_prod + plan.n_mid + plan.n_cons
+    util, final = trace_occupancy(ds, torch, wl, r["kinds"][best_pol], r["modes"][best_mode], args.tile, sp, sc,
+                                  n_tiles, plan.slots)
 
     out = {
         "metric": "dependent-chain latency, fine-grained sync, best of {two-stream, one-dispatch} x sync policies (mean of steps)",
         "value": lat, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": lat / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": name, "M": M, "policy": best_pol, "launch": best_mode, "tile": ds.tile_shape(plan.tile_prod),
-                   "tiles_producer": plan.n_prod, "tiles_consumer": plan.n_cons, "slots": plan.slots,
-                   "waves_streamsync": plan.waves_streamsync, "waves_fine": plan.waves_fine},
+        "config": {"workload": wl.name, "M": M, "policy": best_pol, "launch": best_mode, "tile": ds.tile_shape(plan.tile_prod),
+                   "tiles_producer": plan.n_prod, "tiles_middle": plan.n_mid, "tiles_consumer": plan.n_cons,
+                   "slots": plan.slots, "waves_streamsync": plan.waves_streamsync, "waves_fine": plan.waves_fine},
         "latency_us": {f"{pn}/{mn}": round(v, 2) for (pn, mn), v in results.items()},
         "latency_blocks_us": {f"{pn}/{mn}": [round(x, 1) for x in b] for (pn, mn), b in blocks.items()},
         "speedup_vs_streamsync": (ss / lat) if ss else None,
         "speedup_vs_plain": (plain / lat) if plain else None,
         "tflops": tflops, "pct_bf16_mfma_peak": 100 * tflops / PEAK_BF16_TFLOPS,
+        "slot_utilisation": util, "final_wave_occupancy": final,
         "device": {"cus": n_cu, "clock_mhz": clock_khz / 1e3},
         "roofline": roof,
     }
 
     if not args.no_cpu_baseline:
         import oracle
-        rows = min(args.cpu_rows, M)
-        Xs = inputs.to_f64(t["X"][:rows])
-        W1f, W2f = inputs.to_f64(W1), inputs.to_f64(t["W2"])
-        t0 = time.perf_counter()
-        if attn:
-            # causal: the first `rows` tokens of the sequence need nothing from later tokens
-            oracle.attn_chain(Xs, W1f, W2f, 1, rows, attn["heads"], attn["head_dim"])
-        elif mid == ds.MID_SWIGLU:
-            oracle.swiglu_chain(Xs, W1f, W2f)
-        else:
-            oracle.gemm_chain(Xs, W1f, W2f, oracle.ACT_GELU)
-        dt = time.perf_counter() - t0
+        dt, frac, what = wl.cpu_oracle(args.cpu_rows)
         out["cpu_baseline"] = {
-            "value": dt * 1e6 * (M / rows), "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
-            "sample": f"fp64 oracle timed on the first {rows} of {M} rows of X (rows are independent"
-                      f"{', the attention of a prefix being a prefix of the attention' if attn else ''}); "
-                      f"{dt:.2f} s measured, scaled by {M}/{rows} to the full chain",
-            "measured_s": dt, "gflops": flops * (rows / M) / dt / 1e9,
+            "value": dt * 1e6 / frac, "unit": "us", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{what}; {dt:.2f} s measured, scaled by {1 / frac:.3g} to the full chain",
+            "measured_s": dt, "gflops": plan.flops * frac / dt / 1e9,
         }
     print(json.dumps(out))
 

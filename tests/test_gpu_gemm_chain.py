@@ -251,3 +251,28 @@ def test_autotune_picks_a_tile_the_library_then_uses():
         assert mid_err(Hm, Href) <= TOL_MID and rel_err(Ym, Yref) <= TOL_BF16
         assert torch.equal(Hm, res[0][0]) and torch.equal(Ym, res[0][1])
     pol.destroy()
+
+
+def test_trace_records_cover_every_tile_in_order():
+    # DEPSYNC_FLAG_TRACE: one record per tile with enter <= start <= ready <= end, producers
+    # finishing before the consumers that wait for their whole row start computing
+    M, K1, N1, N2 = 512, 256, 1024, 512
+    t = inputs.mlp(M, K1, N1, N2, seed=31)
+    X, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
+    H = torch.empty((M, N1), dtype=X.dtype, device="cuda")
+    Y = torch.empty((M, N2), dtype=X.dtype, device="cuda")
+    pol = ds.SyncPolicy(ds.ROWSYNC, flags=ds.FLAG_TRACE)
+    plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol, tile=ds.TILE_128x128)
+    for mode in (ds.MODE_FINE, ds.MODE_FUSED, ds.MODE_STREAMSYNC):
+        ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=mode, tile=ds.TILE_128x128)
+        torch.cuda.synchronize()
+        recs = pol.read_trace(plan.n_prod + plan.n_cons)
+        assert [r.rel for r in recs] == list(range(plan.n_prod + plan.n_cons))
+        for r in recs:
+            assert r.t_enter <= r.t_start <= r.t_ready <= r.t_end
+            assert (r.where >> 8) & 0xff < 8           # XCD id
+        prod, cons = recs[:plan.n_prod], recs[plan.n_prod:]
+        assert {(r.tx, r.ty) for r in prod} == {(x, y) for x in range(plan.prod_grid_x) for y in range(plan.prod_grid_y)}
+        for c in cons:   # RowSync: a consumer tile is ready only after every producer tile of its row has ended
+            assert c.t_ready >= max(p.t_end for p in prod if p.ty == c.ty) - 100   # ticks of 10 ns
+    pol.destroy()
