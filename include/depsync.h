@@ -117,6 +117,12 @@ typedef struct {
                              a few seconds), 0xffffffff = wait without bound                    */
     uint32_t delay_tile;  /* debug: producer tile (row-major index) + 1 to delay; 0 = none    */
     uint32_t delay_iters; /* debug: s_sleep iterations the delayed tile spends before its post */
+    uint32_t ksplit;      /* workgroups per output tile, each over an equal part of K (the grid's z
+                             of Tables I and IV).  0 = the library splits stages that would leave
+                             most of the chip idle; 1 = never; n = n parts wherever K divides so
+                             that parts start on dependency boundaries.  The parts leave fp32
+                             partial tiles in a scratch buffer the policy owns; the last to arrive
+                             adds them in K order, so results do not depend on timing.           */
 } depsync_policy_params;
 
 #define DEPSYNC_FLAG_TRACE 16u        /* record per-tile start / ready / end times (FINE and

@@ -45,7 +45,7 @@ class DepsyncError(RuntimeError):
 class PolicyParams(ctypes.Structure):
     _fields_ = [("stride", ctypes.c_uint32), ("count", ctypes.c_uint32), ("flags", ctypes.c_uint32),
                 ("spin_limit", ctypes.c_uint32), ("delay_tile", ctypes.c_uint32),
-                ("delay_iters", ctypes.c_uint32)]
+                ("delay_iters", ctypes.c_uint32), ("ksplit", ctypes.c_uint32)]
 
 
 class Status(ctypes.Structure):
@@ -169,9 +169,9 @@ class SyncPolicy:
     """Owner of a sync_policy_t (policy kind + semaphore workspace)."""
 
     def __init__(self, kind: int, stride: int = 0, count: int = 0, flags: int = 0, spin_limit: int = 0,
-                 delay_tile: int = 0, delay_iters: int = 0):
+                 delay_tile: int = 0, delay_iters: int = 0, ksplit: int = 0):
         self.kind = kind
-        params = PolicyParams(stride, count, flags, spin_limit, delay_tile, delay_iters)
+        params = PolicyParams(stride, count, flags, spin_limit, delay_tile, delay_iters, ksplit)
         h = ctypes.c_void_p()
         _check(_lib().sync_policy_create(kind, ctypes.byref(params), ctypes.byref(h)), "sync_policy_create")
         self._h = h

@@ -31,7 +31,9 @@ constexpr uint32_t WS_MAX_SEMS = 1u << 16;
 constexpr uint32_t WS_SEM_WORDS = WS_MAX_SEMS * SYNC_WORD_STRIDE;
 constexpr uint32_t WS_TRACE = WS_SEMS + WS_SEM_WORDS;     // TraceRec[WS_TRACE_CAP], 12 words each
 constexpr uint32_t WS_TRACE_CAP = 8192;
-constexpr uint32_t WS_WORDS = WS_TRACE + WS_TRACE_CAP * (sizeof(TraceRec) / 4);
+constexpr uint32_t WS_ARRIVE = WS_TRACE + WS_TRACE_CAP * (sizeof(TraceRec) / 4);   // split-K arrival counters
+constexpr uint32_t WS_MAX_ARRIVE = 1u << 15;
+constexpr uint32_t WS_WORDS = WS_ARRIVE + WS_MAX_ARRIVE;
 
 int hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -56,6 +58,8 @@ struct sync_policy {
     uint64_t geom_sig;
     uint32_t epoch;
     uint32_t launches;
+    float* scratch;        // split-K partial tiles, grown on demand
+    size_t scratch_floats;
     uint32_t sems_dirty;   // semaphores that may be non-zero (largest count used since they were last cleared)
     bool need_reset;
 };
@@ -72,6 +76,10 @@ struct Plan {
     uint32_t sem_value[3];
     uint32_t stride[3];
     uint32_t out_tm[3], out_tn[3];   // rows / columns of its own output one tile of stage s covers
+    uint32_t ksplit[3];              // workgroups per output tile (split along K)
+    uint32_t arrive_off[3];          // first arrival counter of the stage
+    size_t partial_off[3];           // first float of the stage's partial tiles
+    size_t partial_floats;           // scratch the chain needs
     uint32_t n_sems;
     int slots;
     double flops, bytes;
@@ -167,6 +175,42 @@ int policy_dep_kind_conv(int kind) {
     }
 }
 
+// Workgroups per output tile for a stage with `tiles` output tiles and `kt` K steps whose
+// dependency segments start every `seg` steps: split when the stage would leave at least half
+// of the slots idle, as far as one wave of slots allows, keeping every part at least 8 steps
+// long and starting on a segment boundary.
+uint32_t choose_split(const sync_policy* pol, uint32_t tiles, uint32_t slots, uint32_t kt, uint32_t seg) {
+    const uint32_t want = pol ? pol->params.ksplit : 0;
+    if (want == 1 || seg == 0) return 1;
+    static const uint32_t cand[] = {8, 6, 4, 3, 2};
+    for (uint32_t S : cand) {
+        if (kt % S || (kt / S) % seg) continue;
+        if (want > 1) { if (S <= want) return S; continue; }
+        if (tiles * S <= slots && kt / S >= 8) return S;
+    }
+    return 1;
+}
+
+// Fill in tile counts, arrival counters and partial-tile offsets once grids and splits are known.
+int finish_split(Plan& p) {
+    uint32_t arr = 0;
+    size_t fl = 0;
+    for (int s = 0; s < p.n_stages; ++s) {
+        const uint32_t real = p.grid_x[s] * p.grid_y[s];
+        p.n_tiles[s] = real * p.ksplit[s];
+        p.arrive_off[s] = arr;
+        p.partial_off[s] = fl;
+        if (p.ksplit[s] > 1) {
+            const TileShape* ts = tile_shape(p.tile[s]);
+            arr += real;
+            fl += (size_t)real * p.ksplit[s] * ts->rows * ts->cols;
+        }
+    }
+    if (arr > WS_MAX_ARRIVE) return DEPSYNC_ENOMEM;
+    p.partial_floats = fl;
+    return DEPSYNC_OK;
+}
+
 int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu, Plan& p) {
     if (!d) return DEPSYNC_EINVAL;
     if (d->M <= 0 || d->K1 <= 0 || d->N1 <= 0 || d->N2 <= 0) return DEPSYNC_EINVAL;
@@ -227,7 +271,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
         p.grid_y[1] = (uint32_t)d->batch * cdiv(d->seq, 128);
         p.out_tm[1] = 128; p.out_tn[1] = 128;
     }
-    for (int s = 0; s < p.n_stages; ++s) p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
+    for (int s = 0; s < p.n_stages; ++s) { p.n_tiles[s] = p.grid_x[s] * p.grid_y[s]; p.ksplit[s] = 1; }
 
     // dependency of stage s on stage s-1, per policy
     const int kind = pol ? pol->kind : DEPSYNC_ROWSYNC;
@@ -267,6 +311,14 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     p.n_sems = off;
     if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
+    // split along K where a stage is much smaller than the chip (not the attention stage)
+    p.ksplit[0] = choose_split(pol, p.n_tiles[0], p.slots, d->K1 / 64, 1);
+    {
+        const uint32_t dk = p.dep_kind[last];
+        const uint32_t seg = (dk == DEP_ROW) ? 1u : p.out_tn[last - 1] / 64;
+        p.ksplit[last] = choose_split(pol, p.n_tiles[last], p.slots, K2 / 64, seg);
+    }
+    if (int rc = finish_split(p); rc != DEPSYNC_OK) return rc;
     const double M = d->M, w1c = gate_up ? 2.0 * d->N1 : d->N1;
     p.flops = 2.0 * M * w1c * d->K1 + 2.0 * M * d->N2 * K2;
     p.bytes = 2.0 * (M * d->K1 + w1c * d->K1 + 2.0 * M * d->N1 + (double)d->N2 * K2 + M * d->N2);
@@ -317,7 +369,7 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     p.grid_x[0] = cdiv(d->K1, ts->cols);
     p.grid_x[1] = cdiv(d->K2, ts->cols);
     p.out_tm[0] = ts->rows; p.out_tn[0] = ts->cols;
-    for (int s = 0; s < 2; ++s) p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
+    for (int s = 0; s < 2; ++s) { p.n_tiles[s] = p.grid_x[s] * p.grid_y[s]; p.ksplit[s] = 1; }
     const int kind = pol ? pol->kind : DEPSYNC_STRIDEDSYNC;
     p.dep_kind[1] = policy_dep_kind_conv(kind);
     if (p.dep_kind[1] == DEP_CONV_TILE) {
@@ -331,6 +383,15 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     p.n_sems = p.sem_count[1];
     if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
+    p.ksplit[0] = choose_split(pol, p.n_tiles[0], p.slots, 9u * d->C / 64, 1);
+    {
+        uint32_t seg = 1;                                   // CONV_ROW: the whole halo is waited for by every part
+        // per filter row or per (filter row, channel tile): the wait at a filter row's first tap
+        // also covers its other two taps, so parts must be whole filter rows
+        if (p.dep_kind[1] != DEP_CONV_ROW) seg = 3u * d->K1 / 64;
+        p.ksplit[1] = choose_split(pol, p.n_tiles[1], p.slots, 9u * d->K1 / 64, seg);
+    }
+    if (int rc = finish_split(p); rc != DEPSYNC_OK) return rc;
     const double Md = (double)M;
     p.flops = 2.0 * Md * d->K1 * 9.0 * d->C + 2.0 * Md * d->K2 * 9.0 * d->K1;
     p.bytes = 2.0 * (Md * d->C + 9.0 * d->C * d->K1 + 2.0 * Md * d->K1 + 9.0 * d->K1 * d->K2 + Md * d->K2);
@@ -387,6 +448,21 @@ int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t*
     return DEPSYNC_OK;
 }
 
+// Make the policy's scratch buffer large enough for the chain's split-K partial tiles.
+int ensure_scratch(sync_policy* pol, const Plan& p) {
+    if (p.partial_floats <= pol->scratch_floats) return DEPSYNC_OK;
+    HIP_TRY(hipDeviceSynchronize());               // earlier chains may still use the old buffer
+    if (pol->scratch) (void)hipFree(pol->scratch);
+    pol->scratch = nullptr;
+    pol->scratch_floats = 0;
+    float* buf = nullptr;
+    hipError_t e = hipMalloc(reinterpret_cast<void**>(&buf), p.partial_floats * sizeof(float));
+    if (e != hipSuccess) return e == hipErrorOutOfMemory ? DEPSYNC_ENOMEM : hip_fail(e);
+    pol->scratch = buf;
+    pol->scratch_floats = p.partial_floats;
+    return DEPSYNC_OK;
+}
+
 void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) {
     a.n_stages = p.n_stages;
     uint32_t t = 0;
@@ -412,6 +488,9 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
         st.grid_x = p.grid_x[s];
         st.grid_y = p.grid_y[s];
         st.queue_by_col = p.grid_x[s] >= 8 ? 1u : 0u;
+        st.ksplit = p.ksplit[s];
+        st.partials = pol->scratch ? pol->scratch + p.partial_off[s] : nullptr;
+        st.arrive = pol->ws + WS_ARRIVE + p.arrive_off[s];
         st.zero_page = pol->ws + WS_ZERO_PAGE;
         st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
         if (s > 0) {
@@ -513,6 +592,8 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
     p->geom_sig = 0;
     p->launches = 0;
     p->sems_dirty = 0;
+    p->scratch = nullptr;
+    p->scratch_floats = 0;
     p->need_reset = false;
     *out = p;
     return DEPSYNC_OK;
@@ -525,6 +606,7 @@ int sync_policy_destroy(sync_policy_t* pol) {
     (void)hipEventDestroy(pol->ev_join);
     (void)hipStreamDestroy(pol->own_stream);
     (void)hipFree(pol->ws);
+    if (pol->scratch) (void)hipFree(pol->scratch);
     delete pol;
     return DEPSYNC_OK;
 }
@@ -533,6 +615,7 @@ int dep_chain_reset(sync_policy_t* pol, void* stream) {
     if (!pol) return DEPSYNC_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, st));
+    HIP_TRY(launch_fill_u32(pol->ws + WS_ARRIVE, 0u, WS_MAX_ARRIVE, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS + 1, 0xffffffffu, 1, st));   // first_timeout = -1
     HIP_TRY(launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, st));
@@ -625,6 +708,7 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
     s1.M = d->M; s1.N = d->N2; s1.K = attn ? d->heads * 128 : d->N1;
     s1.lda = (uint32_t)(attn ? d->ldt : d->ldh); s1.ldb = (uint32_t)d->ldw2; s1.ldc = (uint32_t)d->ldy;
     s1.op = OP_GEMM; s1.amode = A_DENSE; s1.bmode = B_DENSE; s1.act = ACT_NONE;
+    if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
     fill_common(a, pol, p, epoch);
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
 }
@@ -658,6 +742,7 @@ int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync
     s1.lda = d->K1; s1.ldb = 9u * d->K1; s1.ldc = d->K2;
     s1.op = OP_GEMM; s1.amode = A_CONV3X3; s1.bmode = B_DENSE; s1.act = ACT_NONE;
     s1.H = d->H; s1.W = d->W; s1.Cin = d->K1;
+    if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
     fill_common(a, pol, p, epoch);
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
 }

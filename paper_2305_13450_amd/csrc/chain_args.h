@@ -36,6 +36,12 @@ struct StageDesc {
     uint32_t lda, ldb, ldc;
     uint32_t grid_x, grid_y;   // column tiles, row tiles
     uint32_t queue_by_col;     // dispatch queue of tile (x,y): x mod 8 if set, else (y*grid_x + x) mod 8
+    // split-K: each output tile is computed by `ksplit` workgroups over equal K ranges; they leave
+    // fp32 partial tiles in `partials` and count in `arrive`, and the last one to arrive adds the
+    // partials in K order, applies the epilogue and posts.  The dispatch sees grid_y * ksplit rows.
+    uint32_t ksplit;
+    float* partials;           // [tile][ksplit][TM*TN] fp32, fragment order
+    uint32_t* arrive;          // one counter per tile, zero between chains
     uint32_t op, amode, bmode, act;
     // conv geometry (A_CONV3X3): image height, width, input channels
     uint32_t H, W, Cin;

@@ -93,11 +93,12 @@ struct DepRange {
 };
 
 // Does the A slice of K step kt start a new dependency segment, and on what?
-__device__ __forceinline__ bool dep_segment(const StageDesc& s, uint32_t m0, uint32_t tm, uint32_t kt, DepRange& r) {
+// kb: first K step of this workgroup's K range (0 unless the stage is split along K).
+__device__ __forceinline__ bool dep_segment(const StageDesc& s, uint32_t m0, uint32_t tm, uint32_t kt, uint32_t kb, DepRange& r) {
     const uint32_t m_last = min(m0 + tm, s.M) - 1;
     switch (s.dep_kind) {
         case DEP_ROW:
-            if (kt != 0) return false;
+            if (kt != kb) return false;
             r.y0 = m0 / s.prod_tm; r.y1 = m_last / s.prod_tm; r.x = 0;
             return true;
         case DEP_TILE:
@@ -105,12 +106,14 @@ __device__ __forceinline__ bool dep_segment(const StageDesc& s, uint32_t m0, uin
             const uint32_t k0 = kt * 64;
             if (k0 % s.prod_tn != 0) return false;
             r.x = k0 / s.prod_tn;
-            if (s.dep_kind == DEP_STRIDED && r.x >= s.stride) return false;  // same semaphore as x - stride
+            // same semaphore as x - stride, which this workgroup has already waited for if that
+            // segment lies inside its K range
+            if (s.dep_kind == DEP_STRIDED && r.x >= s.stride && (r.x - s.stride) * (s.prod_tn / 64) >= kb) return false;
             r.y0 = m0 / s.prod_tm; r.y1 = m_last / s.prod_tm;
             return true;
         }
         case DEP_CONV_ROW: {
-            if (kt != 0) return false;
+            if (kt != kb) return false;
             const int lo = (int)m0 - (int)s.W - 1, hi = (int)m_last + (int)s.W + 1;
             r.y0 = (uint32_t)max(lo, 0) / s.prod_tm;
             r.y1 = (uint32_t)min(hi, (int)s.M - 1) / s.prod_tm; r.x = 0;
@@ -168,7 +171,7 @@ __device__ __forceinline__ const char* uni_ptr(const void* p) {
 // DEP: this tile's A operand is produced by the previous stage of the chain (the tile waits
 // on semaphores before it requests a slice of A).
 template <class Cfg, typename T, bool SYNC, uint32_t AMODE, bool DEP, class DR>
-__device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc& s, uint32_t tx, uint32_t ty,
+__device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc& s, uint32_t tx, uint32_t tyz,
                                           uint32_t rel_ticket, char* lds, uint64_t t_enter, DR& dr) {
     using M = Mma<T>;
     using V8 = typename M::V8;
@@ -187,8 +190,11 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const uint32_t sM = uni(s.M), sN = uni(s.N);
     const bool gate_up = (s.bmode == B_GATE_UP);
     const uint32_t tn_out = gate_up ? TN / 2 : TN;       // output columns this tile owns
+    const uint32_t S = uni(s.ksplit);                      // workgroups per output tile (split along K)
+    const uint32_t ty = tyz / S, kz = tyz % S;
     const uint32_t m0 = ty * TM, n0 = tx * tn_out;
     const uint32_t KT = uni(s.K / 64);
+    const uint32_t kb = kz * (KT / S), ke = kb + KT / S;   // this workgroup's K steps
     const char* const Abase = uni_ptr(s.A);
     const char* const Bbase = uni_ptr(s.B);
     // conv geometry (unused otherwise)
@@ -296,7 +302,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const bool reorder = !(args.flags & DS_FLAG_NO_REORDER);
 
     // Dependency segments start at multiples of seg_steps K steps (0: only at step 0).
-    uint32_t seg_steps = 0, seg_next = 0;
+    uint32_t seg_steps = 0, seg_next = kb;   // the host makes K ranges start on segment boundaries
     if constexpr (DEP) {
         switch (s.dep_kind) {
             case DEP_TILE: case DEP_STRIDED: seg_steps = s.prod_tn / 64; break;
@@ -324,13 +330,13 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
             if (k == seg_next) {
                 seg_next = seg_steps ? seg_next + seg_steps : 0xffffffffu;
                 DepRange dr;
-                if (!dep_segment(s, m0, TM, k, dr)) return;
+                if (!dep_segment(s, m0, TM, k, kb, dr)) return;
                 bool polled = false;
                 if (k >= ready_until) {
                     const uint32_t ka = k + lane * seg_steps;          // lane's segment start
                     bool ok = true;
                     DepRange la;
-                    if (ka < KT && (lane == 0 || seg_steps != 0) && dep_segment(s, m0, TM, ka, la)) {
+                    if (ka < ke && (lane == 0 || seg_steps != 0) && dep_segment(s, m0, TM, ka, kb, la)) {
                         const uint32_t target = s.sem_target_base + s.sem_value;
                         for (uint32_t y = la.y0; y <= la.y1; ++y) {
                             const uint32_t* sem = s.sems + policy_sem(s.dep_kind, la.x, y, s.prod_grid_y, s.stride) * SYNC_WORD_STRIDE;
@@ -362,8 +368,8 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     static_assert((NST - 2) * ND <= 48, "outstanding DMA instructions must fit the vmcnt counter");
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p) {
-        set_next(min((uint32_t)p, KT - 1));
-        if ((uint32_t)p < KT) dep_before_request(p, p);
+        set_next(min(kb + (uint32_t)p, ke - 1));
+        if (kb + (uint32_t)p < ke) dep_before_request(kb + p, p);
         if (p == 0 && tracing) t_ready = now_ticks();
         issue_B(p);
         issue_A(p);
@@ -375,15 +381,15 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // next 16-wide K slice are read from LDS while the current slice's MFMAs run.  The body is
     // free of branches: past the end the last slice is simply requested again into an idle stage.
     uint32_t cur = 0, req = NST - 1;      // stage being computed on / stage being filled
-    for (uint32_t kt = 0; kt < KT; ++kt) {
+    for (uint32_t kt = kb; kt < ke; ++kt) {
         // step kt's DMA group is complete when at most the NST-2 younger groups are outstanding
         // (a bare s_barrier: __syncthreads() would also wait for the younger groups)
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NST - 2) * ND) : "memory");
         // now stage `cur` is complete for all waves and nobody still reads stage `req`
 
         const uint32_t kreq = kt + (NST - 1);
-        set_next(min(kreq, KT - 1));
-        if (kreq < KT) dep_before_request(kreq, req);
+        set_next(min(kreq, ke - 1));
+        if (kreq < ke) dep_before_request(kreq, req);
 
         const char* la = lds + cur * Cfg::STAGE_BYTES;
         const char* lb = la + Cfg::A_BYTES;
@@ -420,10 +426,58 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     dr.peek();   // the look at the dispatch queues for this workgroup's next tile travels during the epilogue
 
+    // ---- split-K: leave the partial tile, and carry on only as the last part to arrive ----
+    bool finish = true;
+    if (S > 1) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        const uint32_t tile_lin = ty * s.grid_x + tx;
+        float* const part = s.partials + (size_t)tile_lin * S * (TM * TN);
+        // fragment order: each lane stores 16 bytes next to its neighbours' (1 KB per instruction)
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    f32x4 v4 = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
+                    *(f32x4*)(part + (size_t)kz * (TM * TN) + ((((i * FN + j) * 4 + q) * 256 + tid) << 2)) = v4;
+                }
+        // the partial must be in memory before the count moves: write this XCD's L2 back
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
+        if (tid == 0) {
+            asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
+            const uint32_t old = __hip_atomic_fetch_add(s.arrive + tile_lin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            slot[0] = old;
+        }
+        __syncthreads();
+        finish = __builtin_amdgcn_readfirstlane(slot[0]) == S - 1;
+        __syncthreads();
+        if (finish) {
+            // Every part's partial is in memory (each counted after its write-back) and none of
+            // these lines has been read on this XCD since the kernel started.  Sum in K order,
+            // whoever came last, so that the result does not depend on the arrival order.
+            if (tid == 0) __hip_atomic_store(s.arrive + tile_lin, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+            for (int i = 0; i < FM; ++i)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
+                        for (uint32_t z = 0; z < S; ++z)
+                            sum += *(const f32x4*)(part + (size_t)z * (TM * TN) + ((((i * FN + j) * 4 + q) * 256 + tid) << 2));
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = sum[e];
+                    }
+        }
+    }
+
     // ---- epilogue: activation, round to 16 bits, store ----
     // Accumulator layout of the 32x32 block: lane holds column (lane % 32) and rows
     // 8*(v/4) + 4*(lane/32) + v%4 for v = 0..15.
-    if (wctx.ok) {
+    if (wctx.ok && finish) {
         T* Cp = (T*)s.C;
         const uint32_t ldc = s.ldc, act = s.act;
         const uint32_t colw = lane & 31u, rowh = (lane >> 5) * 4u;
@@ -460,10 +514,10 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         }
     }
 
-    if (SYNC) post_tile<THROUGH>(args, s, ty * s.grid_x + tx, tx, ty);
+    if (SYNC && finish) post_tile<THROUGH>(args, s, ty * s.grid_x + tx, tx, ty);
     if (tracing && tid == 0) {
         TraceRec r;
-        r.rel = rel_ticket; r.where = hw_where(DEP ? 1u : 0u); r.tx = tx; r.ty = ty;
+        r.rel = rel_ticket; r.where = hw_where(DEP ? 1u : 0u); r.tx = tx; r.ty = tyz;
         r.t_enter = t_enter; r.t_start = t_start; r.t_ready = t_ready; r.t_end = now_ticks();
         args.trace[rel_ticket] = r;
     }

@@ -140,7 +140,7 @@ __device__ __forceinline__ void post_tile(const ChainArgs& a, const StageDesc& s
 
 // The tile a workgroup runs.
 struct TileId {
-    uint32_t stage, tx, ty;
+    uint32_t stage, tx, ty;   // ty counts rows of the dispatch grid: row tile * ksplit + K part
     uint32_t rel;      // first_ticket[stage] + row-major index: unique per tile, used in the status
 };
 
@@ -163,7 +163,8 @@ __device__ __forceinline__ uint32_t xcc_id() {
 // A queue counter only grows: entry = counter - epoch * queue_length; a draw beyond the end
 // is undone, so after a chain every counter has advanced by exactly its queue length.
 __device__ __forceinline__ uint32_t queue_len(const StageDesc& st, uint32_t q) {
-    return st.queue_by_col ? ((st.grid_x + 7u - q) >> 3) * st.grid_y : (st.grid_x * st.grid_y + 7u - q) >> 3;
+    const uint32_t rows = st.grid_y * st.ksplit;
+    return st.queue_by_col ? ((st.grid_x + 7u - q) >> 3) * rows : (st.grid_x * rows + 7u - q) >> 3;
 }
 // Entry i of queue q -> tile (tx, ty).
 __device__ __forceinline__ void queue_entry(const StageDesc& st, uint32_t q, uint32_t i, uint32_t& tx, uint32_t& ty) {

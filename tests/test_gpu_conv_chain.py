@@ -52,11 +52,13 @@ def test_conv_chain_delayed_halo_row_is_waited_for():
     # not change the result under any policy.
     t = inputs.conv(1, 28, 28, 128, 128, 128, seed=6)
     mid_ref, out_ref = _oracle(t)
-    base = ds.SyncPolicy(ds.ROWSYNC)
-    _, out0 = run_conv_chain(t["x"], t["w1"], t["w2"], base, ds.MODE_STREAMSYNC, tile=ds.TILE_64x64)
-    assert rel_err(out0, out_ref) <= TOL_BF16
-    base.destroy()
     for kind in KINDS:
+        # the reference of each policy: the same kernels under stream sync (how a stage is split along
+        # K depends on where the policy's dependency segments start, so policies may differ in rounding)
+        base = ds.SyncPolicy(kind)
+        _, out0 = run_conv_chain(t["x"], t["w1"], t["w2"], base, ds.MODE_STREAMSYNC, tile=ds.TILE_64x64)
+        assert rel_err(out0, out_ref) <= TOL_BF16
+        base.destroy()
         for delay_tile in (1, 6, 13, 26):      # producer tiles (2 channel tiles per row tile)
             pol = ds.SyncPolicy(kind, delay_tile=delay_tile, delay_iters=200)
             _, out = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
@@ -135,3 +137,18 @@ def test_conv_autotune_picks_a_tile_the_library_then_uses():
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
     assert rel_err(a[1], oref) <= TOL_BF16
     pol.destroy()
+
+
+@pytest.mark.parametrize("kind", [ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC])
+def test_conv_chain_split_k(kind):
+    # 9 * C / 64 = 18 K steps: three parts are one filter row each
+    t = inputs.conv(1, 14, 14, 128, 128, 64, seed=43)
+    mref, oref = oracle.conv_chain(inputs.to_f64(t["x"]), inputs.to_f64(t["w1"]), inputs.to_f64(t["w2"]))
+    for ksplit in (3, 6):
+        pol = ds.SyncPolicy(kind, ksplit=ksplit)
+        res = [run_conv_chain(t["x"], t["w1"], t["w2"], pol, mode, tile=ds.TILE_64x64)
+               for mode in (ds.MODE_FINE, ds.MODE_FUSED, ds.MODE_STREAMSYNC, ds.MODE_PLAIN)]
+        for mid, out in res:
+            assert rel_err(out, oref) <= TOL_BF16
+            assert torch.equal(mid, res[0][0]) and torch.equal(out, res[0][1])
+        pol.destroy()

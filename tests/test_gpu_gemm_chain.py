@@ -111,7 +111,7 @@ def test_stridedsync_on_gemm_chain():
     # 6 producer column tiles of 64; tiles x, x+2, x+4 share a semaphore (stride 2, count 3)
     t = inputs.mlp(192, 128, 384, 128, seed=17)
     Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
-    pol = ds.SyncPolicy(ds.STRIDEDSYNC, count=3, flags=ds.FLAG_COUNT)
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC, count=3, flags=ds.FLAG_COUNT, ksplit=1)   # counts per whole tile
     H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_64x64)
     assert rel_err(Y, Yref) <= TOL_BF16
     st = pol.status()
@@ -126,7 +126,7 @@ def test_sync_counts_of_the_fig1_shaped_chain(golden):
     t = inputs.mlp(3 * 128, 128, 2 * 128, 2 * 128, seed=19)
     _, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
     for kind, key in ((ds.TILESYNC, "syncs_tilesync"), (ds.ROWSYNC, "syncs_rowsync")):
-        pol = ds.SyncPolicy(kind, flags=ds.FLAG_COUNT)
+        pol = ds.SyncPolicy(kind, flags=ds.FLAG_COUNT, ksplit=1)   # the figure has no split along K
         _, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=ds.TILE_128x128)
         st = pol.status()
         assert rel_err(Y, Yref) <= TOL_BF16
@@ -261,7 +261,7 @@ def test_trace_records_cover_every_tile_in_order():
     X, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
     H = torch.empty((M, N1), dtype=X.dtype, device="cuda")
     Y = torch.empty((M, N2), dtype=X.dtype, device="cuda")
-    pol = ds.SyncPolicy(ds.ROWSYNC, flags=ds.FLAG_TRACE)
+    pol = ds.SyncPolicy(ds.ROWSYNC, flags=ds.FLAG_TRACE, ksplit=1)
     plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol, tile=ds.TILE_128x128)
     for mode in (ds.MODE_FINE, ds.MODE_FUSED, ds.MODE_STREAMSYNC):
         ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=mode, tile=ds.TILE_128x128)
@@ -275,4 +275,48 @@ def test_trace_records_cover_every_tile_in_order():
         assert {(r.tx, r.ty) for r in prod} == {(x, y) for x in range(plan.prod_grid_x) for y in range(plan.prod_grid_y)}
         for c in cons:   # RowSync: a consumer tile is ready only after every producer tile of its row has ended
             assert c.t_ready >= max(p.t_end for p in prod if p.ty == c.ty) - 100   # ticks of 10 ns
+    pol.destroy()
+
+
+@pytest.mark.parametrize("ksplit", [2, 3, 4, 8])
+@pytest.mark.parametrize("kind", [ds.ROWSYNC, ds.TILESYNC])
+def test_split_k_matches_oracle_and_does_not_depend_on_timing(ksplit, kind):
+    # every output tile computed by `ksplit` workgroups over parts of K, the last to arrive adding
+    # the fp32 partial tiles in K order: ragged M and N, K a multiple of 64 * 24
+    M, K1, N1, N2 = 200, 1536, 1536, 328
+    t = inputs.mlp(M, K1, N1, N2, seed=37)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    for tile in (ds.TILE_64x64, ds.TILE_128x128, ds.TILE_128x192):
+        print(f"split-K ksplit={ksplit} kind={kind} tile={tile}", flush=True)
+        pol = ds.SyncPolicy(kind, ksplit=ksplit)
+        plan = ds.gemm_chain_plan(t["X"].cuda(), t["W1"].t().contiguous().cuda(), torch.empty((M, N1), dtype=torch.bfloat16, device="cuda"),
+                                  t["W2"].t().contiguous().cuda(), torch.empty((M, N2), dtype=torch.bfloat16, device="cuda"), pol, tile=tile)
+        tm, tn = ds.tile_shape(tile)
+        assert plan.n_prod == -(-M // tm) * -(-N1 // tn) * ksplit          # K1 / 64 = 24 divides by 2, 3, 4, 8
+        res = [run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode, tile=tile) for mode in MODES]
+        for H, Y in res:
+            assert mid_err(H, Href) <= TOL_MID and rel_err(Y, Yref) <= TOL_BF16
+            assert torch.equal(H, res[0][0]) and torch.equal(Y, res[0][1])
+        pol.destroy()
+        # a delayed part must not change the sum
+        pol = ds.SyncPolicy(kind, ksplit=ksplit, flags=ds.FLAG_REVERSE_ORDER)
+        H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FINE, tile=tile)
+        assert torch.equal(H, res[0][0]) and torch.equal(Y, res[0][1])
+        pol.destroy()
+
+
+def test_split_k_is_chosen_for_skinny_chains_and_swiglu():
+    # few tiles on a big chip: the library splits on its own; the gated activation is applied
+    # after the partial sums are added
+    t = inputs.swiglu(48, 2048, 192, 256, seed=41)
+    Href, Yref = oracle.swiglu_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["Wgu"]), inputs.to_f64(t["W2"]))
+    pol = ds.SyncPolicy(ds.TILESYNC)
+    res = [run_gemm_chain(t["X"], t["Wgu"], t["W2"], pol, mode, mid=ds.MID_SWIGLU, tile=ds.TILE_64x128) for mode in MODES]
+    X = t["X"].cuda()
+    plan = ds.gemm_chain_plan(X, t["Wgu"].t().contiguous().cuda(), res[0][0], t["W2"].t().contiguous().cuda(), res[0][1], pol,
+                              mid=ds.MID_SWIGLU, tile=ds.TILE_64x128)
+    assert plan.n_prod > plan.prod_grid_x * plan.prod_grid_y               # split
+    for H, Y in res:
+        assert mid_err(H, Href) <= TOL_MID and mid_err(Y, Yref) <= 1e-2
+        assert torch.equal(H, res[0][0]) and torch.equal(Y, res[0][1])
     pol.destroy()
