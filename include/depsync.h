@@ -255,11 +255,13 @@ int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_
                             int n_cu, depsync_plan_info* out);
 
 /* Tile selection by measurement (the role of the paper's policy/order search of Section IV-A,
- * narrowed to the macro-tile shape): runs the chain in one-dispatch mode on `stream` with every
- * macro-tile shape it supports (one warm-up launch, then `reps` timed launches each; reps <= 0
- * means 3), synchronises, and remembers the fastest shape for this chain shape, element type and
- * policy kind for the rest of the process: later calls that leave the tile to the library
- * (DEPSYNC_TILE_AUTO) use it, in every launch mode.  The intermediate and output buffers are
+ * narrowed to the macro-tile shape and the split along K): runs the chain in one-dispatch mode
+ * on `stream` with every macro-tile shape it supports, with and without the library's own
+ * split along K (two passes; a warm-up launch, then at least `reps` timed launches each, more
+ * for chains too short to time; reps <= 0 means 3), synchronises, and remembers the fastest
+ * combination for this chain shape, element type and policy kind for the rest of the process:
+ * later calls that leave the tile to the library (DEPSYNC_TILE_AUTO) use it, in every launch
+ * mode.  The intermediate and output buffers are
  * overwritten.  The tile ids in `d` are ignored; *tile_out (nullable) receives the choice.     */
 int depsync_gemm_chain_autotune(const depsync_gemm_chain_desc* d, sync_policy_t* pol, void* stream,
                                 int reps, int* tile_out);

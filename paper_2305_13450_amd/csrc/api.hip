@@ -177,16 +177,17 @@ int policy_dep_kind_conv(int kind) {
 
 // Workgroups per output tile for a stage with `tiles` output tiles and `kt` K steps whose
 // dependency segments start every `seg` steps: split when the stage would leave at least half
-// of the slots idle, as far as one wave of slots allows, keeping every part at least 8 steps
-// long and starting on a segment boundary.
-uint32_t choose_split(const sync_policy* pol, uint32_t tiles, uint32_t slots, uint32_t kt, uint32_t seg) {
+// of the slots idle, as far as one wave of slots allows, keeping every part at least 16 steps
+// long (the partial tiles and the arrival count cost about 10 us per stage) and starting on a
+// segment boundary.  `tuned_off`: the autotuner found this chain faster without.
+uint32_t choose_split(const sync_policy* pol, bool tuned_off, uint32_t tiles, uint32_t slots, uint32_t kt, uint32_t seg) {
     const uint32_t want = pol ? pol->params.ksplit : 0;
-    if (want == 1 || seg == 0) return 1;
+    if (want == 1 || seg == 0 || (want == 0 && tuned_off)) return 1;
     static const uint32_t cand[] = {8, 6, 4, 3, 2};
     for (uint32_t S : cand) {
         if (kt % S || (kt / S) % seg) continue;
         if (want > 1) { if (S <= want) return S; continue; }
-        if (tiles * S <= slots && kt / S >= 8) return S;
+        if (tiles * S <= slots && kt / S >= 16) return S;
     }
     return 1;
 }
@@ -249,7 +250,8 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     const int cus = device_cus(n_cu);
     if (cus <= 0) return DEPSYNC_EHIP;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    if (!tile) tile = tuned_tile(tune_key(d, pol));
+    bool tuned_off = false;
+    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; }
     if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
     const TileShape* ts = tile_shape(tile);
     if (!ts) return DEPSYNC_EINVAL;
@@ -312,11 +314,11 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
     // split along K where a stage is much smaller than the chip (not the attention stage)
-    p.ksplit[0] = choose_split(pol, p.n_tiles[0], p.slots, d->K1 / 64, 1);
+    p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.slots, d->K1 / 64, 1);
     {
         const uint32_t dk = p.dep_kind[last];
         const uint32_t seg = (dk == DEP_ROW) ? 1u : p.out_tn[last - 1] / 64;
-        p.ksplit[last] = choose_split(pol, p.n_tiles[last], p.slots, K2 / 64, seg);
+        p.ksplit[last] = choose_split(pol, tuned_off, p.n_tiles[last], p.slots, K2 / 64, seg);
     }
     if (int rc = finish_split(p); rc != DEPSYNC_OK) return rc;
     const double M = d->M, w1c = gate_up ? 2.0 * d->N1 : d->N1;
@@ -352,7 +354,8 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     if (cus <= 0) return DEPSYNC_EHIP;
     const uint32_t M = (uint32_t)Mpix;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    if (!tile) tile = tuned_tile(tune_key(d, pol));
+    bool tuned_off = false;
+    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; }
     if (!tile) {
         // halo: a consumer row tile reads W+1 rows beyond each end
         tile = choose_tile(M, d->K1, 9 * d->C, d->K2, 9 * d->K1, false, cus, 1);
@@ -383,13 +386,13 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     p.n_sems = p.sem_count[1];
     if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
-    p.ksplit[0] = choose_split(pol, p.n_tiles[0], p.slots, 9u * d->C / 64, 1);
+    p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.slots, 9u * d->C / 64, 1);
     {
         uint32_t seg = 1;                                   // CONV_ROW: the whole halo is waited for by every part
         // per filter row or per (filter row, channel tile): the wait at a filter row's first tap
         // also covers its other two taps, so parts must be whole filter rows
         if (p.dep_kind[1] != DEP_CONV_ROW) seg = 3u * d->K1 / 64;
-        p.ksplit[1] = choose_split(pol, p.n_tiles[1], p.slots, 9u * d->K1 / 64, seg);
+        p.ksplit[1] = choose_split(pol, tuned_off, p.n_tiles[1], p.slots, 9u * d->K1 / 64, seg);
     }
     if (int rc = finish_split(p); rc != DEPSYNC_OK) return rc;
     const double Md = (double)M;
@@ -423,7 +426,8 @@ uint64_t geom_signature(const Plan& p) {
     uint64_t h = 1469598103934665603ull;
     auto mix = [&](uint64_t v) { h = (h ^ v) * 1099511628211ull; };
     mix(p.n_stages);
-    for (int s = 0; s < p.n_stages; ++s) { mix(p.grid_x[s]); mix(p.grid_y[s]); mix(p.sem_count[s]); mix(p.sem_value[s]); mix(p.dep_kind[s]); }
+    // everything the dispatch queues' lengths and the semaphore targets depend on
+    for (int s = 0; s < p.n_stages; ++s) { mix(p.grid_x[s]); mix(p.grid_y[s]); mix(p.ksplit[s]); mix(p.sem_count[s]); mix(p.sem_value[s]); mix(p.dep_kind[s]); }
     return h;
 }
 
@@ -750,8 +754,9 @@ int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync
 }  // extern "C"
 
 namespace {
-// Time every macro-tile shape the chain can run with (one-dispatch mode, `reps` launches after
-// one warm-up, HIP events on the caller's stream) and remember the fastest.
+// Time every macro-tile shape the chain can run with, each with and without the library's split
+// along K (one-dispatch mode, HIP events on the caller's stream, two passes, blocks long enough
+// to time), and remember the fastest combination.
 template <class Desc, class Run>
 int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* tile_out, Run run) {
     if (!d || !pol) return DEPSYNC_EINVAL;
@@ -759,24 +764,41 @@ int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* til
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));
     if (hipError_t e = hipEventCreate(&e1); e != hipSuccess) { (void)hipEventDestroy(e0); return hip_fail(e); }
+    const uint32_t user_split = pol->params.ksplit;
     int best = 0, rc = DEPSYNC_OK;
     float best_ms = 0.f;
-    for (int t = 1; t < DEPSYNC_TILE__COUNT && rc == DEPSYNC_OK; ++t) {
-        Desc dd = *d;
-        dd.tile_prod = dd.tile_cons = t;
-        int r = run(&dd);                       // warm-up; also tells whether this shape is usable
-        if (r == DEPSYNC_EINVAL || r == DEPSYNC_ENOTIMPL || r == DEPSYNC_ENOMEM) continue;
-        if (r != DEPSYNC_OK) { rc = r; break; }
+    auto time_block = [&](const Desc* dd, int n, float* per_run) -> int {
+        int r = DEPSYNC_OK;
         hipError_t e = hipEventRecord(e0, sp);
-        for (int i = 0; i < reps && r == DEPSYNC_OK; ++i) r = run(&dd);
+        for (int i = 0; i < n && r == DEPSYNC_OK; ++i) r = run(dd);
         if (e == hipSuccess) e = hipEventRecord(e1, sp);
         if (e == hipSuccess) e = hipEventSynchronize(e1);
         float ms = 0.f;
         if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
-        if (e != hipSuccess) { rc = hip_fail(e); break; }
-        if (r != DEPSYNC_OK) { rc = r; break; }
-        if (best == 0 || ms < best_ms) { best = t; best_ms = ms; }
+        if (e != hipSuccess) return hip_fail(e);
+        *per_run = ms / (float)n;
+        return r;
+    };
+    for (int pass = 0; pass < 2 && rc == DEPSYNC_OK; ++pass) {
+        for (int t = 1; t < DEPSYNC_TILE__COUNT && rc == DEPSYNC_OK; ++t) {
+            for (int off = 0; off < (user_split == 0 ? 2 : 1) && rc == DEPSYNC_OK; ++off) {
+                pol->params.ksplit = off ? 1u : user_split;
+                Desc dd = *d;
+                dd.tile_prod = dd.tile_cons = t;
+                int r = run(&dd);                   // warm-up; also tells whether this shape is usable
+                if (r == DEPSYNC_EINVAL || r == DEPSYNC_ENOTIMPL || r == DEPSYNC_ENOMEM) continue;
+                if (r != DEPSYNC_OK) { rc = r; break; }
+                float ms = 0.f;
+                r = time_block(&dd, reps, &ms);
+                if (r == DEPSYNC_OK && ms * reps < 1.0f)   // too short to compare: about 2 ms worth
+                    r = time_block(&dd, (int)(2.0f / std::max(ms, 0.005f)) + 1, &ms);
+                if (r != DEPSYNC_OK) { rc = r; break; }
+                const int cand = t | (off ? 0x100 : 0);
+                if (best == 0 || ms < best_ms) { best = cand; best_ms = ms; }
+            }
+        }
     }
+    pol->params.ksplit = user_split;
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rc != DEPSYNC_OK) return rc;
@@ -785,7 +807,7 @@ int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* til
         std::lock_guard<std::mutex> g(g_tuned_mutex);
         g_tuned[tune_key(d, pol)] = best;
     }
-    if (tile_out) *tile_out = best;
+    if (tile_out) *tile_out = best & 0xff;
     return DEPSYNC_OK;
 }
 }  // namespace

@@ -320,3 +320,20 @@ def test_split_k_is_chosen_for_skinny_chains_and_swiglu():
         assert mid_err(H, Href) <= TOL_MID and mid_err(Y, Yref) <= 1e-2
         assert torch.equal(H, res[0][0]) and torch.equal(Y, res[0][1])
     pol.destroy()
+
+
+def test_one_policy_reused_with_and_without_split_k():
+    # the dispatch queues' lengths change with the split: the workspace must notice (regression)
+    M, K1, N1, N2 = 128, 2048, 512, 256
+    t = inputs.mlp(M, K1, N1, N2, seed=47)
+    X, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
+    H = torch.empty((M, N1), dtype=X.dtype, device="cuda")
+    Y = torch.empty((M, N2), dtype=X.dtype, device="cuda")
+    pol = ds.SyncPolicy(ds.TILESYNC, spin_limit=1 << 14)
+    tile = ds.gemm_chain_autotune(X, W1t, H, W2t, Y, pol, reps=1)      # alternates split / no split on one policy
+    assert pol.status().timed_out == 0
+    Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)[1]
+    ds.dep_gemm_chain(X, W1t, H, W2t, Y, pol, mode=ds.MODE_FUSED)
+    torch.cuda.synchronize()
+    assert rel_err(Y, Yref) <= TOL_BF16 and pol.status().timed_out == 0 and tile >= 1
+    pol.destroy()
