@@ -81,6 +81,18 @@ __device__ __forceinline__ void store_out(T* p, T v) {
         *p = v;
     }
 }
+// Store eight consecutive 16-bit output elements (16-byte aligned).
+template <bool THROUGH, typename V8>
+__device__ __forceinline__ void store_out16(void* p, V8 v) {
+    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+    if constexpr (THROUGH) {
+        u32x4 bits;
+        __builtin_memcpy(&bits, &v, 16);
+        asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(p), "v"(bits) : "memory");
+    } else {
+        *(V8*)p = v;
+    }
+}
 __device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
@@ -476,41 +488,62 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
 
     // ---- epilogue: activation, round to 16 bits, store ----
     // Accumulator layout of the 32x32 block: lane holds column (lane % 32) and rows
-    // 8*(v/4) + 4*(lane/32) + v%4 for v = 0..15.
+    // 8*(v/4) + 4*(lane/32) + v%4 for v = 0..15, i.e. a lane's values run DOWN a column.  Each
+    // wave therefore transposes its sub-tile through its own piece of the (now idle) operand
+    // staging area and writes it out as 16-byte row segments: a twelfth of the store
+    // instructions, and whole lines instead of 2-byte pieces for the write-through stores.
+    __syncthreads();   // every wave has read its last operand fragments
     if (wctx.ok && finish) {
-        T* Cp = (T*)s.C;
-        const uint32_t ldc = s.ldc, act = s.act;
+        constexpr int PAD = (4 * Cfg::WTM * (Cfg::WTN * 2 + 16) <= Cfg::LDS_BYTES) ? 16 : 0;
+        constexpr int PITCH = Cfg::WTN * 2 + PAD;                   // bytes per sub-tile row in LDS
+        static_assert(4 * Cfg::WTM * PITCH <= Cfg::LDS_BYTES, "the transposed sub-tiles fit the staging area");
+        char* const reg = lds + wave * (Cfg::WTM * PITCH);
+        const uint32_t act = s.act;
         const uint32_t colw = lane & 31u, rowh = (lane >> 5) * 4u;
+        const uint32_t wtn_out = gate_up ? Cfg::WTN / 2 : Cfg::WTN;  // output columns of this wave
         if (gate_up) {
             if constexpr (FN >= 2) {
 #pragma unroll
                 for (int i = 0; i < FM; ++i)
 #pragma unroll
-                    for (int jp = 0; jp < FN / 2; ++jp) {
-                        const uint32_t col = n0 + (wn * Cfg::WTN) / 2 + jp * 32 + colw;
+                    for (int jp = 0; jp < FN / 2; ++jp)
 #pragma unroll
                         for (int v = 0; v < 16; ++v) {
-                            const uint32_t row = m0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + rowh + (v % 4);
+                            const uint32_t r = i * 32 + 8 * (v / 4) + rowh + (v % 4), c = jp * 32 + colw;
                             const float g = acc[i][2 * jp][v], u = acc[i][2 * jp + 1][v];
-                            if (row < sM && col < sN) store_out<THROUGH>(Cp + (size_t)row * ldc + col, (T)(silu_f(g) * u));
+                            *(T*)(reg + r * PITCH + c * 2) = (T)(silu_f(g) * u);
                         }
-                    }
             }
         } else {
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    const uint32_t col = n0 + wn * Cfg::WTN + j * 32 + colw;
+                for (int j = 0; j < FN; ++j)
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
-                        const uint32_t row = m0 + wm * Cfg::WTM + i * 32 + 8 * (v / 4) + rowh + (v % 4);
+                        const uint32_t r = i * 32 + 8 * (v / 4) + rowh + (v % 4), c = j * 32 + colw;
                         float x = acc[i][j][v];
                         if (act == ACT_GELU) x = gelu_erf(x);
                         else if (act == ACT_RELU) x = fmaxf(x, 0.0f);
-                        if (row < sM && col < sN) store_out<THROUGH>(Cp + (size_t)row * ldc + col, (T)x);
+                        *(T*)(reg + r * PITCH + c * 2) = (T)x;
                     }
-                }
+        }
+        // the region is private to the wave: its own LDS writes are ordered before its reads
+        T* Cp = (T*)s.C;
+        const uint32_t ldc = s.ldc;
+        const uint32_t cpr = wtn_out / 8;                            // 16-byte chunks per row
+        const uint32_t row0 = m0 + wm * Cfg::WTM, col0 = n0 + wn * wtn_out;
+        for (uint32_t idx = lane; idx < Cfg::WTM * cpr; idx += 64) {
+            const uint32_t r = idx / cpr, ch = idx % cpr;
+            const uint32_t row = row0 + r, col = col0 + ch * 8;
+            if (row >= sM || col >= sN) continue;
+            const V8 val = *(const V8*)(reg + r * PITCH + ch * 16);
+            T* dst = Cp + (size_t)row * ldc + col;
+            if (col + 8 <= sN) {
+                store_out16<THROUGH>(dst, val);
+            } else {
+                for (uint32_t e = 0; e < sN - col; ++e) store_out<THROUGH>(dst + e, (T)val[e]);
+            }
         }
     }
 
