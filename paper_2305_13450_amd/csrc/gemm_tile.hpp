@@ -528,6 +528,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         *(T*)(reg + r * PITCH + c * 2) = (T)x;
                     }
         }
+        dr.grab();   // the counters read by peek() have arrived by now: start the next tile's draw
         // the region is private to the wave: its own LDS writes are ordered before its reads
         T* Cp = (T*)s.C;
         const uint32_t ldc = s.ldc;

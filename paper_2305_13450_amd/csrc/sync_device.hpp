@@ -209,9 +209,11 @@ struct Drawer {
     uint32_t c[8];         // counters of stage `open` as read by peek()
     bool peeked;
     bool first;
+    bool pending;          // grab() has an increment in flight
+    uint32_t pend_q, pend_val;
 
     __device__ __forceinline__ Drawer(const ChainArgs& args, uint32_t* lds_slot)
-        : a(args), slot(lds_slot), home(xcc_id()), open(args.stage_lo), peeked(false), first(true) {}
+        : a(args), slot(lds_slot), home(xcc_id()), open(args.stage_lo), peeked(false), first(true), pending(false), pend_q(0), pend_val(0) {}
 
     __device__ __forceinline__ void load_counters() {
         const uint32_t* cnt = a.ticket + 8u * open * SYNC_WORD_STRIDE;
@@ -228,12 +230,46 @@ struct Drawer {
         peeked = true;
     }
 
+    // A while after peek(): if the counters it read show entries left, start the increment on
+    // the chosen queue so that its round trip, too, passes during the tile's stores.  Nothing is
+    // started on a queue that looked empty, so exhausted queues still see loads only.
+    __device__ __forceinline__ void grab() {
+        if (threadIdx.x != DRAW_THREAD || !peeked || open > a.stage_hi) return;
+        const StageDesc& st = a.st[open];
+        uint32_t avail = 0;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t len = queue_len(st, j);
+            if (c[j] - a.epoch * len < len) avail |= 1u << j;
+        }
+        if (avail == 0) return;                              // draw() will move on to the next stage
+        const uint32_t rot = (avail >> home) | (avail << (8u - home));
+        pend_q = (home + (uint32_t)__builtin_ctz(rot & 0xffu)) & 7u;
+        pend_val = __hip_atomic_fetch_add(a.ticket + (8u * open + pend_q) * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED,
+                                          __HIP_MEMORY_SCOPE_AGENT);
+        pending = true;
+        peeked = false;
+    }
+
     // DRAW_THREAD: draw a tile (blocking).
     __device__ __forceinline__ bool draw(uint32_t& stage, uint32_t& tx, uint32_t& ty) {
         // a workgroup launched for the first stage it may work on goes straight for its XCD's
         // queue the first time (one round trip)
         bool direct = first && a.block_offset + blockIdx.x < a.first_ticket[a.stage_lo + 1];
         first = false;
+        if (pending) {                                       // the increment grab() started
+            pending = false;
+            const StageDesc& st = a.st[open];
+            const uint32_t len = queue_len(st, pend_q);
+            uint32_t i = pend_val - a.epoch * len;
+            if (i < len) {
+                if (open == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
+                stage = open; queue_entry(st, pend_q, i, tx, ty);
+                return true;
+            }
+            __hip_atomic_fetch_sub(a.ticket + (8u * open + pend_q) * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);   // emptied since the look: undo, look again
+        }
         for (; open <= a.stage_hi; ++open, peeked = false) {
             const StageDesc& st = a.st[open];
             uint32_t* cnt = a.ticket + 8u * open * SYNC_WORD_STRIDE;
@@ -293,6 +329,7 @@ struct Drawer {
 // Stand-in where tiles come from the hardware's block index (nothing to look ahead for).
 struct NoDrawer {
     __device__ __forceinline__ void peek() {}
+    __device__ __forceinline__ void grab() {}
 };
 
 }  // namespace depsync
