@@ -24,7 +24,9 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
 # HBM-side bytes of one chain from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by what the
 # same counter reads for a 1 GiB copy), per workload and launch mode; see profiles/*.md for the runs.
 MEASURED_TRAFFIC_BYTES = {
-    ("gpt3_mlp", 2048, "fused"): (1160433 + 82393) * 1024,
+    ("gpt3_mlp", 2048, "fused"): (1082264 + 86384) * 1024,
+    ("gpt3_attn", 2048, "fused"): (1036536 + 104904) * 1024,
+    ("vgg_conv", 2048, "fused"): (360834 + 55184) * 1024,     # 56x56x256, batch 16 (the default conv shape)
 }
 
 
@@ -309,7 +311,8 @@ def main():
     best_pol, best_mode = r["best"]
     ss, plain = r["ss"], r["plain"]
     roof, tflops = roofline(plan, lat)
-    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, M, best_mode)) if args.tile == 0 else None
+    default_shape = args.workload != "vgg_conv" or (args.hw, args.channels, args.batch) == (56, 256, 16)
+    roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, M, best_mode)) if default_shape else None
     roof["kernel"] = "chain_kernel (all dispatches of one chain; one dispatch in fused mode)"
     roof["per_launch"] = {"flops": plan.flops, "bytes": plan.bytes, "duration_us": lat}
     n_tiles = plan.n_prod + plan.n_mid + plan.n_cons
