@@ -28,7 +28,8 @@ namespace depsync {
 constexpr int ATT_BQ = 128;      // query rows per tile (32 per wave)
 constexpr int ATT_BK = 64;       // keys per block
 constexpr int ATT_D = 128;       // head dimension
-constexpr int ATT_LDS_BYTES = 2 * ATT_BK * ATT_D * 2;   // K block + V^T block
+constexpr int ATT_BLK_BYTES = ATT_BK * ATT_D * 2;       // one block of K or V rows (16 KB)
+constexpr int ATT_LDS_BYTES = 4 * ATT_BLK_BYTES;        // two K buffers, raw V rows, V^T
 
 // Wait for everything an attention tile reads from the QKV GeMM: producer row tiles y0..y1,
 // and in each the column tiles holding this head's Q, K and V columns.
@@ -107,28 +108,38 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     float m_run = -INFINITY, l_run = 0.0f;
     const float sc = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
 
-    char* ldsK = lds;                          // [64 keys][128 d], 16-byte chunks swizzled by key & 15
-    char* ldsV = lds + ATT_BK * ATT_D * 2;     // V^T [128 d][64 keys], 8-byte chunks swizzled by d & 15
+    // LDS: two K buffers [64 keys][128 d] (16-byte chunks swizzled by key & 15), one buffer of
+    // V rows in the same layout and the V^T block [128 d][64 keys] (8-byte chunks swizzled by d & 15).
+    // While block kb is used, the K and V rows of block kb+1 are DMA'd into LDS (no registers
+    // held); V is transposed LDS to LDS at the top of the next iteration.
     const uint32_t wave_q_last = min(q0 + wave * 32 + 31, seq - 1);
     const uint32_t nblk = q_last / ATT_BK + 1;                    // key blocks the tile touches
+    char* const ldsVraw = lds + 2 * ATT_BLK_BYTES;
+    char* const ldsV = lds + 3 * ATT_BLK_BYTES;
+    auto fetch = [&](uint32_t kb) __attribute__((always_inline)) {
+        const uint32_t k0 = kb * ATT_BK;
+        char* ldsKn = lds + (kb & 1u) * ATT_BLK_BYTES;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                             // 4 x 16 bytes per lane for K, and for V
+            const uint32_t idx = i * 256 + tid, row = idx >> 4, slot = idx & 15u, chunk = slot ^ (row & 15u);
+            const uint32_t krow = seq_row0 + min(k0 + row, seq - 1);
+            const char* g = (const char*)(QKV + (size_t)krow * ld + E + head * ATT_D);
+            dma16(g + chunk * 16, ldsKn + (i * 256 + wave * 64) * 16);
+            dma16(g + E * 2 + chunk * 16, ldsVraw + (i * 256 + wave * 64) * 16);   // V rows, same swizzle
+        }
+    };
+    fetch(0);
 
     for (uint32_t kb = 0; kb < nblk; ++kb) {
         const uint32_t k0 = kb * ATT_BK;
-        __syncthreads();                                          // previous block fully consumed
-        // K block: DMA, 4 x 16 bytes per lane
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t idx = i * 256 + tid, row = idx >> 4, slot = idx & 15u, chunk = slot ^ (row & 15u);
-            const uint32_t krow = seq_row0 + min(k0 + row, seq - 1);
-            const char* g = (const char*)(QKV + (size_t)krow * ld + E + head * ATT_D + chunk * 8);
-            dma16(g, ldsK + (i * 256 + wave * 64) * 16);
-        }
-        // V block, transposed on the way into LDS: each lane takes 8 d values of one key
+        char* ldsK = lds + (kb & 1u) * ATT_BLK_BYTES;
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wave's part of block kb has landed
+        __syncthreads();   // block kb's rows are in LDS for everyone; everyone is done with block kb-1
+        // V transposed, LDS to LDS: each lane takes 8 d values of one key, four times
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const uint32_t idx = i * 256 + tid, key = idx & 63u, dch = idx >> 6;      // dch: 8-wide d chunk 0..15
-            const uint32_t vrow = seq_row0 + min(k0 + key, seq - 1);
-            const V8 vv = *(const V8*)(QKV + (size_t)vrow * ld + 2 * E + head * ATT_D + dch * 8);
+            const V8 vv = *(const V8*)(ldsVraw + key * 256u + ((dch ^ (key & 15u)) << 4));
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const uint32_t d = dch * 8 + e;
@@ -136,8 +147,8 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
                 *(T*)(ldsV + off) = vv[e];
             }
         }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
+        __syncthreads();   // V^T complete; the raw V rows and the other K buffer are free again
+        if (kb + 1 < nblk) fetch(kb + 1);
 
         if (k0 <= wave_q_last) {        // blocks entirely above this wave's diagonal contribute nothing
             // ---- S^T for the two 32-key halves of the block ----
