@@ -152,3 +152,17 @@ def test_conv_chain_split_k(kind):
             assert rel_err(out, oref) <= TOL_BF16
             assert torch.equal(mid, res[0][0]) and torch.equal(out, res[0][1])
         pol.destroy()
+
+
+def test_conv_chain_fp16():
+    # the paper's precision: same kernels instantiated for fp16, tighter tolerance
+    t = inputs.conv(2, 17, 19, 64, 128, 64, seed=53, dtype=torch.float16)
+    mref, oref = oracle.conv_chain(inputs.to_f64(t["x"]), inputs.to_f64(t["w1"]), inputs.to_f64(t["w2"]))
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    res = [run_conv_chain(t["x"], t["w1"], t["w2"], pol, mode)
+           for mode in (ds.MODE_FINE, ds.MODE_FUSED, ds.MODE_STREAMSYNC, ds.MODE_PLAIN)]
+    for mid, out in res:
+        assert mid_err(mid, mref, ulp=2.0 ** -11) <= TOL_MID
+        assert rel_err(out, oref) <= 4e-3
+        assert torch.equal(mid, res[0][0]) and torch.equal(out, res[0][1])
+    pol.destroy()
