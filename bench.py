@@ -43,6 +43,8 @@ def parse():
     ap.add_argument("--batch", type=int, default=16, help="vgg_conv: images")
     ap.add_argument("--policy", default="auto", choices=["auto", "row", "tile", "strided"])
     ap.add_argument("--tile", type=int, default=0, help="depsync_tile id, 0 = library's choice")
+    ap.add_argument("--w-layout", default="rows", choices=["rows", "kblocked"],
+                    help="GeMM chains: weights row-major [N x K] or packed [K/64][N][64]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-autotune", action="store_true", help="use the library's model-based tile choice")
     ap.add_argument("--cpu-rows", type=int, default=384, help="rows of X the CPU oracle is timed on")
@@ -71,7 +73,7 @@ def time_block(torch, call, sp, steps):
 class Workload:
     """Device buffers of one chain plus closures to plan, tune and launch it."""
 
-    def __init__(self, torch, ds, inputs, kind, M=2048, hw=56, channels=256, batch=16):
+    def __init__(self, torch, ds, inputs, kind, M=2048, hw=56, channels=256, batch=16, w_layout="rows"):
         self.kind, self.M = kind, M
         self.conv = kind == "vgg_conv"
         self.attn = None
@@ -109,6 +111,9 @@ class Workload:
         n1 = self.W1t.shape[0] // 2 if self.mid == ds.MID_SWIGLU else self.W1t.shape[0]
         self.H = torch.empty((M, n1), dtype=self.X.dtype, device="cuda")
         self.Y = torch.empty((M, self.W2t.shape[0]), dtype=self.X.dtype, device="cuda")
+        if w_layout == "kblocked":      # weights are static: packed once, outside every timed region
+            self.W1t, self.W2t = ds.pack_weights_kblocked(self.W1t), ds.pack_weights_kblocked(self.W2t)
+            self.name += ", weights K-blocked"
         self.extra = {}
         if self.attn:
             self.extra = dict(self.attn, T=torch.empty((M, self.attn["heads"] * self.attn["head_dim"]),
@@ -292,7 +297,8 @@ def main():
     if args.sweep:
         return sweep(args, torch, ds, inputs)
 
-    wl = Workload(torch, ds, inputs, args.workload, M=args.m, hw=args.hw, channels=args.channels, batch=args.batch)
+    wl = Workload(torch, ds, inputs, args.workload, M=args.m, hw=args.hw, channels=args.channels, batch=args.batch,
+                  w_layout=args.w_layout)
     M = wl.M
 
     if args.copy_calibration:
@@ -311,7 +317,7 @@ def main():
     best_pol, best_mode = r["best"]
     ss, plain = r["ss"], r["plain"]
     roof, tflops = roofline(plan, lat)
-    default_shape = args.workload != "vgg_conv" or (args.hw, args.channels, args.batch) == (56, 256, 16)
+    default_shape = args.w_layout == "rows" and (args.workload != "vgg_conv" or (args.hw, args.channels, args.batch) == (56, 256, 16))
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, M, best_mode)) if default_shape else None
     roof["kernel"] = "chain_kernel (all dispatches of one chain; one dispatch in fused mode)"
     roof["per_launch"] = {"flops": plan.flops, "bytes": plan.bytes, "duration_us": lat}

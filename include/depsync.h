@@ -79,6 +79,13 @@ typedef enum {
 
 typedef enum { DEPSYNC_BF16 = 0, DEPSYNC_FP16 = 1 } depsync_dtype;
 
+/* Layout of the weight operands of a GeMM chain (both are K-contiguous per output column n):
+ *   ROWS     [N x K] row-major with a leading dimension (the nn.Linear layout);
+ *   KBLOCKED [K/64][N][64]: blocks of 64 K-elements, all N rows of a block adjacent, so that
+ *            the slice one tile reads per pipeline step is one contiguous run of memory
+ *            (weights are static: packed once; ldw1 / ldw2 are ignored).                     */
+typedef enum { DEPSYNC_W_ROWS = 0, DEPSYNC_W_KBLOCKED = 1 } depsync_w_layout;
+
 /* Macro-tile shapes (rows x columns of the output computed by one workgroup). */
 typedef enum {
     DEPSYNC_TILE_AUTO = 0,
@@ -200,6 +207,7 @@ typedef struct {
     void* T;         int64_t ldt;   /* CAUSAL_ATTN only: [M x heads*head_dim]                */
     int32_t batch, seq, heads, head_dim; /* CAUSAL_ATTN only                                 */
     int32_t tile_prod, tile_cons;   /* depsync_tile; 0 = chosen by the library               */
+    int32_t w_layout;               /* depsync_w_layout of W1t and W2t                       */
 } depsync_gemm_chain_desc;
 
 /*

@@ -21,6 +21,7 @@ MID_NONE, MID_GELU, MID_RELU, MID_SWIGLU, MID_CAUSAL_ATTN = 0, 1, 2, 3, 4
 BF16, FP16 = 0, 1
 (TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128, TILE_64x128, TILE_64x64,
  TILE_256x192, TILE_128x192, TILE_256x64) = range(10)
+W_ROWS, W_KBLOCKED = 0, 1
 FLAG_NO_REORDER, FLAG_COUNT, FLAG_REVERSE_ORDER, FLAG_HW_ORDER, FLAG_TRACE = 1, 2, 4, 8, 16
 OK, EINVAL, ENOMEM, EHIP, ETIMEOUT, ENOTIMPL = 0, -1, -2, -3, -4, -5
 
@@ -84,7 +85,7 @@ class GemmChainDesc(ctypes.Structure):
                 ("T", ctypes.c_void_p), ("ldt", ctypes.c_int64),
                 ("batch", ctypes.c_int32), ("seq", ctypes.c_int32), ("heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32),
-                ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32)]
+                ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32), ("w_layout", ctypes.c_int32)]
 
 
 class ConvChainDesc(ctypes.Structure):
@@ -217,12 +218,33 @@ def sync_policy_create(kind: int, **params) -> SyncPolicy:
     return SyncPolicy(kind, **params)
 
 
+def pack_weights_kblocked(Wt):
+    """[N x K] (K contiguous) -> the K-blocked layout [K/64][N][64]: a pure re-arrangement."""
+    n, k = Wt.shape
+    if k % 64:
+        raise ValueError("K must be a multiple of 64")
+    return Wt.reshape(n, k // 64, 64).permute(1, 0, 2).contiguous()
+
+
+def _dev_w(t, name: str):
+    """A weight operand: 2-D [N x K] row-major, or 3-D [K/64][N][64] (K-blocked).  -> (ptr, ld, N, K, blocked)"""
+    if t.dim() == 3:
+        if not t.is_cuda or not t.is_contiguous() or t.shape[2] != 64:
+            raise ValueError(f"{name}: K-blocked weights must be a contiguous [K/64, N, 64] device tensor")
+        return t.data_ptr(), 0, t.shape[1], t.shape[0] * 64, True
+    ptr, ld = _dev2d(t, name)
+    return ptr, ld, t.shape[0], t.shape[1], False
+
+
 def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, head_dim=0) -> GemmChainDesc:
     d = GemmChainDesc()
     d.X, d.ldx = _dev2d(X, "X")
-    d.W1t, d.ldw1 = _dev2d(W1t, "W1t")
+    d.W1t, d.ldw1, w1n, w1k, b1 = _dev_w(W1t, "W1t")
     d.H, d.ldh = _dev2d(H, "H")
-    d.W2t, d.ldw2 = _dev2d(W2t, "W2t")
+    d.W2t, d.ldw2, w2n, w2k, b2 = _dev_w(W2t, "W2t")
+    if b1 != b2:
+        raise ValueError("both weight operands must use the same layout")
+    d.w_layout = W_KBLOCKED if b1 else W_ROWS
     d.Y, d.ldy = _dev2d(Y, "Y")
     d.M, d.K1 = X.shape
     d.N1 = H.shape[1]
@@ -238,7 +260,7 @@ def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, he
     d.tile_prod = d.tile_cons = tile
     rows1 = 2 * d.N1 if mid == MID_SWIGLU else d.N1
     k2 = heads * head_dim if mid == MID_CAUSAL_ATTN else d.N1
-    if tuple(W1t.shape) != (rows1, d.K1) or tuple(W2t.shape) != (d.N2, k2) or H.shape[0] != d.M or Y.shape[0] != d.M:
+    if (w1n, w1k) != (rows1, d.K1) or (w2n, w2k) != (d.N2, k2) or H.shape[0] != d.M or Y.shape[0] != d.M:
         raise ValueError("operand shapes do not form a chain")
     return d
 

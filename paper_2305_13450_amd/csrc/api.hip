@@ -126,7 +126,7 @@ std::map<TuneKey, int> g_tuned;
 std::mutex g_tuned_mutex;
 
 TuneKey tune_key(const depsync_gemm_chain_desc* d, const sync_policy* pol) {
-    return TuneKey{{0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq}};
+    return TuneKey{{d->w_layout ? 2 : 0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq}};
 }
 TuneKey tune_key(const depsync_conv_chain_desc* d, const sync_policy* pol) {
     return TuneKey{{1, d->B, d->H, d->W, d->C, d->K1, d->K2, d->dtype, pol ? pol->kind : -1, 0}};
@@ -232,15 +232,18 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     }
     const uint32_t K2 = attn ? E : (uint32_t)d->N1;
     if (d->K1 % 64 || K2 % 64) return DEPSYNC_EINVAL;
-    if (d->ldx < d->K1 || d->ldw1 < d->K1 || d->ldh < d->N1 || d->ldw2 < (int64_t)K2 || d->ldy < d->N2)
+    if (d->w_layout != DEPSYNC_W_ROWS && d->w_layout != DEPSYNC_W_KBLOCKED) return DEPSYNC_EINVAL;
+    const bool wrows = d->w_layout == DEPSYNC_W_ROWS;
+    if (d->ldx < d->K1 || (wrows && d->ldw1 < d->K1) || d->ldh < d->N1 || (wrows && d->ldw2 < (int64_t)K2) || d->ldy < d->N2)
         return DEPSYNC_EINVAL;
-    if (d->ldx % 8 || d->ldw1 % 8 || d->ldh % 8 || d->ldw2 % 8 || d->ldy % 8) return DEPSYNC_EINVAL;
+    if (d->ldx % 8 || (wrows && (d->ldw1 % 8 || d->ldw2 % 8)) || d->ldh % 8 || d->ldy % 8) return DEPSYNC_EINVAL;
     // rows of the intermediate must be whole 128-byte cache lines (see dep_wait in gemm_tile.hpp)
     if (d->ldh % 64 || (reinterpret_cast<uintptr_t>(d->H) & 127u)) return DEPSYNC_EINVAL;
     const uint64_t lim = 1ull << 32;
     const uint64_t w1_rows = gate_up ? 2ull * d->N1 : (uint64_t)d->N1;
-    if ((uint64_t)d->M * d->ldx * 2 >= lim || w1_rows * d->ldw1 * 2 >= lim || (uint64_t)d->M * d->ldh * 2 >= lim ||
-        (uint64_t)d->N2 * d->ldw2 * 2 >= lim || (uint64_t)d->M * d->ldy * 2 >= lim)
+    const uint64_t ldw1 = wrows ? (uint64_t)d->ldw1 : (uint64_t)d->K1, ldw2 = wrows ? (uint64_t)d->ldw2 : (uint64_t)K2;
+    if ((uint64_t)d->M * d->ldx * 2 >= lim || w1_rows * ldw1 * 2 >= lim || (uint64_t)d->M * d->ldh * 2 >= lim ||
+        (uint64_t)d->N2 * ldw2 * 2 >= lim || (uint64_t)d->M * d->ldy * 2 >= lim)
         return DEPSYNC_EINVAL;
     if (d->tile_prod < 0 || d->tile_prod >= DEPSYNC_TILE__COUNT || d->tile_cons < 0 ||
         d->tile_cons >= DEPSYNC_TILE__COUNT)
@@ -695,6 +698,9 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
     s0.A = d->X; s0.B = d->W1t; s0.C = d->H;
     s0.M = d->M; s0.N = d->N1; s0.K = d->K1;
     s0.lda = (uint32_t)d->ldx; s0.ldb = (uint32_t)d->ldw1; s0.ldc = (uint32_t)d->ldh;
+    const bool kblocked = d->w_layout == DEPSYNC_W_KBLOCKED;
+    s0.b_row_bytes = kblocked ? 128u : 2u * (uint32_t)d->ldw1;
+    s0.b_kstep_bytes = kblocked ? 128u * (uint32_t)(gate_up ? 2 * d->N1 : d->N1) : 128u;
     s0.op = OP_GEMM; s0.amode = A_DENSE; s0.bmode = gate_up ? B_GATE_UP : B_DENSE;
     s0.act = d->mid == DEPSYNC_MID_GELU ? ACT_GELU : d->mid == DEPSYNC_MID_RELU ? ACT_RELU
              : gate_up ? ACT_SWIGLU : ACT_NONE;
@@ -711,6 +717,8 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
     s1.A = attn ? d->T : d->H; s1.B = d->W2t; s1.C = d->Y;
     s1.M = d->M; s1.N = d->N2; s1.K = attn ? d->heads * 128 : d->N1;
     s1.lda = (uint32_t)(attn ? d->ldt : d->ldh); s1.ldb = (uint32_t)d->ldw2; s1.ldc = (uint32_t)d->ldy;
+    s1.b_row_bytes = kblocked ? 128u : 2u * (uint32_t)d->ldw2;
+    s1.b_kstep_bytes = kblocked ? 128u * (uint32_t)d->N2 : 128u;
     s1.op = OP_GEMM; s1.amode = A_DENSE; s1.bmode = B_DENSE; s1.act = ACT_NONE;
     if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
     fill_common(a, pol, p, epoch);
@@ -738,12 +746,14 @@ int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync
     s0.A = d->in; s0.B = d->w1; s0.C = d->mid;
     s0.M = M; s0.N = d->K1; s0.K = 9u * d->C;
     s0.lda = d->C; s0.ldb = 9u * d->C; s0.ldc = d->K1;
+    s0.b_row_bytes = 18u * d->C; s0.b_kstep_bytes = 128u;
     s0.op = OP_GEMM; s0.amode = A_CONV3X3; s0.bmode = B_DENSE; s0.act = ACT_RELU;
     s0.H = d->H; s0.W = d->W; s0.Cin = d->C;
     StageDesc& s1 = a.st[1];
     s1.A = d->mid; s1.B = d->w2; s1.C = d->out;
     s1.M = M; s1.N = d->K2; s1.K = 9u * d->K1;
     s1.lda = d->K1; s1.ldb = 9u * d->K1; s1.ldc = d->K2;
+    s1.b_row_bytes = 18u * d->K1; s1.b_kstep_bytes = 128u;
     s1.op = OP_GEMM; s1.amode = A_CONV3X3; s1.bmode = B_DENSE; s1.act = ACT_NONE;
     s1.H = d->H; s1.W = d->W; s1.Cin = d->K1;
     if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;

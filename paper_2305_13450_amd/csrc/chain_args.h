@@ -34,6 +34,9 @@ struct StageDesc {
     void* C;            // [M x N] rows of ldc elements
     uint32_t M, N, K;   // N = output columns (B_GATE_UP: B has 2N rows)
     uint32_t lda, ldb, ldc;
+    // B addressing in bytes: row n, K step kt (64 elements) at n * b_row_bytes + kt * b_kstep_bytes.
+    // Row-major [N x K]: (2 * ldb, 128).  K-blocked [K/64][N][64]: (128, 128 * rows of B).
+    uint32_t b_row_bytes, b_kstep_bytes;
     uint32_t grid_x, grid_y;   // column tiles, row tiles
     uint32_t queue_by_col;     // dispatch queue of tile (x,y): x mod 8 if set, else (y*grid_x + x) mod 8
     // split-K: each output tile is computed by `ksplit` workgroups over equal K ranges; they leave

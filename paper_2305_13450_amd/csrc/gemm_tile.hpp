@@ -209,6 +209,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const uint32_t kb = kz * (KT / S), ke = kb + KT / S;   // this workgroup's K steps
     const char* const Abase = uni_ptr(s.A);
     const char* const Bbase = uni_ptr(s.B);
+    const uint32_t bkstep = uni(s.b_kstep_bytes);
     // conv geometry (unused otherwise)
     const uint32_t cH = uni(s.H), cW = uni(s.W), cCin = uni(s.Cin);
     const char* const zero_page = uni_ptr(s.zero_page);
@@ -245,19 +246,21 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         } else {
             row = min(n0 + q, sN - 1);
         }
-        offB[i] = row * s.ldb * 2u + c * 16u;
+        offB[i] = row * s.b_row_bytes + c * 16u;
     }
 
     // Source of the K step that is being requested ("next" step): a byte offset for B and the
     // dense A, and for the conv the filter tap (fr, fs in -1..1) and the byte shift of that tap.
     struct NextStep {
         uint32_t kbytes;     // kt * 128
+        uint32_t kbytes_b;   // byte offset of the K step in B
         uint32_t tap, c0;    // conv: filter tap 0..8 and first input channel of the step
         int fr, fs;
         long shift;
     } nx;
     auto set_next = [&](uint32_t kt) __attribute__((always_inline)) {
         nx.kbytes = kt * 128u;
+        nx.kbytes_b = kt * bkstep;
         if constexpr (AMODE == A_CONV3X3) {
             const uint32_t k0 = kt * 64u;
             nx.tap = k0 / cCin; nx.c0 = k0 % cCin;
@@ -268,7 +271,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // One 1 KB DMA instruction of the B (weights) or A operand of the next K step into `stage`.
     auto dma_B = [&](uint32_t stage, int i) __attribute__((always_inline)) {
         char* l = lds + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (NIB * 1024);
-        dma16(Bbase + nx.kbytes + offB[i], l + i * 1024);
+        dma16(Bbase + nx.kbytes_b + offB[i], l + i * 1024);
     };
     auto dma_A = [&](uint32_t stage, int i) __attribute__((always_inline)) {
         char* l = lds + stage * Cfg::STAGE_BYTES + wave * (NIA * 1024);

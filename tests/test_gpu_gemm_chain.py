@@ -337,3 +337,32 @@ def test_one_policy_reused_with_and_without_split_k():
     torch.cuda.synchronize()
     assert rel_err(Y, Yref) <= TOL_BF16 and pol.status().timed_out == 0 and tile >= 1
     pol.destroy()
+
+
+@pytest.mark.parametrize("mid", [ds.MID_GELU, ds.MID_SWIGLU])
+def test_k_blocked_weight_layout_gives_the_same_bits(mid):
+    # weights re-arranged to [K/64][N][64] (each pipeline step of a tile reads one contiguous run):
+    # a pure change of addressing, so the results equal the row-major ones bit for bit
+    M, K1, N1, N2 = 200, 512, 384, 328
+    if mid == ds.MID_SWIGLU:
+        t = inputs.swiglu(M, K1, N1, N2, seed=59); W1 = t["Wgu"]
+    else:
+        t = inputs.mlp(M, K1, N1, N2, seed=59); W1 = t["W1"]
+    X, W1t, W2t = t["X"].cuda(), W1.t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
+    W1b, W2b = ds.pack_weights_kblocked(W1t), ds.pack_weights_kblocked(W2t)
+    assert W1b.shape == (K1 // 64, W1t.shape[0], 64)
+    for tile in (ds.TILE_64x128, ds.TILE_128x128, ds.TILE_256x128):
+        outs = []
+        for a, b in ((W1t, W2t), (W1b, W2b)):
+            pol = ds.SyncPolicy(ds.TILESYNC)
+            H = torch.full((M, N1), float("nan"), dtype=X.dtype, device="cuda")
+            Y = torch.full((M, N2), float("nan"), dtype=X.dtype, device="cuda")
+            for mode in MODES:
+                ds.dep_gemm_chain(X, a, H, b, Y, pol, mode=mode, mid=mid, tile=tile)
+                torch.cuda.synchronize()
+                outs.append((H.clone(), Y.clone()))
+            pol.destroy()
+        for H, Y in outs[1:]:
+            assert torch.equal(H, outs[0][0]) and torch.equal(Y, outs[0][1])
+    with pytest.raises(ValueError):      # both operands must use one layout
+        ds.dep_gemm_chain(X, W1b, H, W2t, Y, ds.SyncPolicy(ds.ROWSYNC), mid=mid)
