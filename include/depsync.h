@@ -98,7 +98,9 @@ typedef enum {
     DEPSYNC_TILE_256x192 = 7,  /* 192-wide tiles divide widths of the form 3 * 2^k evenly */
     DEPSYNC_TILE_128x192 = 8,
     DEPSYNC_TILE_256x64 = 9,   /* narrow outputs (64 channels)                           */
-    DEPSYNC_TILE__COUNT = 10
+    DEPSYNC_TILE_64x64_DEEP = 10, /* 64x64 with an 8-stage operand pipeline, one workgroup per
+                                  CU: for chains of few tiles that stream weights from HBM */
+    DEPSYNC_TILE__COUNT = 11
 } depsync_tile;
 
 /* Policy flags. */

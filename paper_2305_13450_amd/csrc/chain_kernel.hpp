@@ -69,6 +69,7 @@ using Cfg64x64 = TileCfg<64, 64, 2, 2, 2, 4>;       // 2 x 64 KB
 using Cfg256x192 = TileCfg<256, 192, 2, 2, 1, 2>;   // 112 KB
 using Cfg128x192 = TileCfg<128, 192, 2, 2, 2, 2>;   // 2 x 80 KB
 using Cfg256x64 = TileCfg<256, 64, 4, 1, 2, 2>;     // 2 x 80 KB
+using Cfg64x64Deep = TileCfg<64, 64, 2, 2, 1, 8>;   // 128 KB: seven K steps in flight
 
 template <class Cfg, typename T, uint32_t AMODE>
 static hipError_t launch_cfg(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
@@ -91,6 +92,7 @@ static hipError_t launch_family(int tile, bool sync, uint32_t n_blocks, hipStrea
         case 7: return launch_cfg<Cfg256x192, T, AMODE>(sync, n_blocks, stream, a);
         case 8: return launch_cfg<Cfg128x192, T, AMODE>(sync, n_blocks, stream, a);
         case 9: return launch_cfg<Cfg256x64, T, AMODE>(sync, n_blocks, stream, a);
+        case 10: return launch_cfg<Cfg64x64Deep, T, AMODE>(sync, n_blocks, stream, a);
         default: return hipErrorInvalidValue;
     }
 }

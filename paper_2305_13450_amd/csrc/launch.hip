@@ -39,8 +39,9 @@ const TileShape* tile_shape(int tile) {
         {256, 192, 1, 96},
         {128, 192, 2, 96},
         {256, 64, 2, 64},
+        {64, 64, 1, 32},
     };
-    if (tile < 1 || tile > 9) return nullptr;
+    if (tile < 1 || tile > 10) return nullptr;
     return &shapes[tile];
 }
 
