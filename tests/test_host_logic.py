@@ -133,3 +133,35 @@ def test_conv_planner():
     assert info.flops == pytest.approx(2 * 2.0 * 4 * 56 * 56 * 256 * 9 * 256)
     d.C = 96
     assert ds._lib().depsync_conv_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.EINVAL
+
+
+def test_planner_splits_small_stages_along_k_on_segment_boundaries():
+    info = ds.PlanInfo()
+    # 32 producer tiles on 512 slots, 192 K steps: eight parts of 24 steps; the consumer (64 tiles,
+    # 96 steps, RowSync) takes six parts of 16 steps (eight would be shorter than 16 steps)
+    d = _fake_gemm_desc(64, 12288, 6144, 12288, tile=ds.TILE_128x192)
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    assert (info.prod_grid_x * info.prod_grid_y, info.n_prod) == (32, 32 * 8)
+    assert (info.cons_grid_x * info.cons_grid_y, info.n_cons) == (64, 64 * 6)
+    # a full-size stage is left alone
+    d = _fake_gemm_desc(2048, 12288, 6144, 12288, tile=ds.TILE_128x192)
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    assert (info.n_prod, info.n_cons) == (512, 1024)
+    # conv, waits per filter row: parts must be whole filter rows (3 x 512 / 64 = 24 of the 72 steps)
+    c = ds.ConvChainDesc()
+    c.B, c.H, c.W, c.C, c.K1, c.K2, c.dtype = 1, 14, 14, 512, 512, 512, ds.BF16
+    c.inp = c.w1 = c.mid = c.w2 = c.out = 0x1000
+    c.tile_prod = c.tile_cons = ds.TILE_64x64
+    assert ds._lib().depsync_conv_chain_plan(ctypes.byref(c), None, 256, ctypes.byref(info)) == ds.OK
+    assert info.prod_grid_x * info.prod_grid_y == 32
+    assert info.n_prod == 32 * 4 and info.n_cons == 32 * 3      # first conv: four parts of 18 steps; second: filter rows
+
+
+def test_k_blocked_layout_is_validated():
+    info = ds.PlanInfo()
+    d = _fake_gemm_desc(256, 1024, 4096, 1024)
+    d.w_layout = ds.W_KBLOCKED
+    d.ldw1 = d.ldw2 = 0                                        # ignored for packed weights
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    d.w_layout = 7
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.EINVAL
