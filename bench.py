@@ -53,6 +53,8 @@ def parse():
                     help="also run a plain device-to-device copy of this many MiB three times, so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
     ap.add_argument("--sweep", default=None, metavar="FILE", help="run all configurations, write a markdown table")
+    ap.add_argument("--ablation", default=None, metavar="FILE",
+                    help="time the chosen workload with the optimisations of Section IV-C switched off one at a time")
     return ap.parse_args()
 
 
@@ -280,6 +282,50 @@ def sweep(args, torch, ds, inputs):
     print(json.dumps({"sweep": args.sweep, "rows": len(lines) - 2}))
 
 
+def ablation(args, torch, ds, wl):
+    """Latency of the workload under each launch mode and with the paper's optimisations (Section IV-C:
+    load/wait reordering, custom tile order) switched off, interleaved blocks, markdown table."""
+    sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    kinds = {"row": ds.ROWSYNC, "tile": ds.TILESYNC, "strided": ds.STRIDEDSYNC}
+    modes = {"fine": ds.MODE_FINE, "fused": ds.MODE_FUSED, "streamsync": ds.MODE_STREAMSYNC, "plain": ds.MODE_PLAIN}
+    pols, calls, rows = [], {}, []
+    tuner = ds.SyncPolicy(kinds[wl.policies[0]])
+    tile = args.tile or wl.autotune(tuner, sp)          # one tile shape for every row of the table
+    tuner.destroy()
+    for pn in wl.policies:
+        for label, flags, mn in ((f"{pn}, one dispatch", 0, "fused"), (f"{pn}, two streams", 0, "fine"),
+                                 (f"{pn}, one dispatch, wait before the weights are requested", ds.FLAG_NO_REORDER, "fused"),
+                                 (f"{pn}, one dispatch, one workgroup per tile in hardware order", ds.FLAG_HW_ORDER, "fused")):
+            pol = ds.SyncPolicy(kinds[pn], flags=flags)
+            pols.append(pol)
+            calls[label] = wl.caller(pol, modes[mn], tile, sp, sc)
+    base = ds.SyncPolicy(kinds[wl.policies[0]])
+    pols.append(base)
+    calls["stream sync (same kernels, one stream)"] = wl.caller(base, modes["streamsync"], tile, sp, sc)
+    calls["plain (hooks compiled out)"] = wl.caller(base, modes["plain"], tile, sp, sc)
+    ok = {}
+    for k, c in calls.items():
+        try:
+            for _ in range(args.warmup):
+                c()
+            torch.cuda.synchronize()
+            ok[k] = c
+        except ds.DepsyncError as e:                     # e.g. hardware order with more tiles than slots
+            rows.append(f"| {k} | not run: {e} |")
+    blocks = {k: [] for k in ok}
+    for _ in range(args.rounds):
+        for k, c in ok.items():
+            blocks[k].append(time_block(torch, c, sp, args.steps))
+    for k, b in blocks.items():
+        rows.append(f"| {k} | {sorted(b)[len(b) // 2]:.1f} |")
+    for pol in pols:
+        pol.destroy()
+    tm, tn = ds.tile_shape(tile)
+    with open(args.ablation, "w") as f:
+        f.write(f"{wl.name}, macro-tile {tm}x{tn}\n\n| variant | chain latency (us) |\n|---|---|\n" + "\n".join(rows) + "\n")
+    print(json.dumps({"ablation": args.ablation, "rows": len(rows)}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -308,6 +354,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.ablation:
+        return ablation(args, torch, ds, wl)
 
     sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
     pol_names = wl.policies if args.policy == "auto" else [args.policy]
