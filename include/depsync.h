@@ -267,7 +267,7 @@ int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_
 /* Tile selection by measurement (the role of the paper's policy/order search of Section IV-A,
  * narrowed to the macro-tile shape and the split along K): runs the chain in one-dispatch mode
  * on `stream` with every macro-tile shape it supports, with and without the library's own
- * split along K (two passes; a warm-up launch, then at least `reps` timed launches each, more
+ * split along K, with tiles drawn from the dispatch queues or named by the block index (two passes; a warm-up launch, then at least `reps` timed launches each, more
  * for chains too short to time; reps <= 0 means 3), synchronises, and remembers the fastest
  * combination for this chain shape, element type and policy kind for the rest of the process:
  * later calls that leave the tile to the library (DEPSYNC_TILE_AUTO) use it, in every launch
@@ -277,6 +277,25 @@ int depsync_gemm_chain_autotune(const depsync_gemm_chain_desc* d, sync_policy_t*
                                 int reps, int* tile_out);
 int depsync_conv_chain_autotune(const depsync_conv_chain_desc* d, sync_policy_t* pol, void* stream,
                                 int reps, int* tile_out);
+
+/* The remembered choice for this chain shape, element type and policy kind, read or set without
+ * measuring (to carry a tuning result from one process to the next).  `tile` is a DEPSYNC_TILE_*
+ * id, 0 when nothing is remembered (setting 0 forgets the entry); `flags`: DEPSYNC_TUNED_*.
+ * Only the shape fields of `d` are read (no pointer in it is dereferenced).  Setting a tile the
+ * chain cannot run with makes later launches that leave the tile to the library fail with
+ * DEPSYNC_EINVAL; a wrong flag can only cost time.  DEPSYNC_EINVAL for null arguments, an
+ * unknown tile id or unknown flag bits.                                                       */
+enum {
+    DEPSYNC_TUNED_NO_SPLIT = 1,   /* do not split stages along K (Section V-C's partial waves are
+                                   * left to the overlap of the stages alone)                   */
+    DEPSYNC_TUNED_HW_ORDER = 2    /* one-dispatch mode names tiles by the block index instead of
+                                   * drawing them from the dispatch queues (Section IV-C, the
+                                   * optimisation that avoids a custom tile order)              */
+};
+int depsync_gemm_chain_tuned(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int* tile, int* flags);
+int depsync_conv_chain_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int* tile, int* flags);
+int depsync_gemm_chain_set_tuned(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int tile, int flags);
+int depsync_conv_chain_set_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int tile, int flags);
 
 /* ---- host mirrors of the device index arithmetic (Fig. 4b; Section II-A) -------------- */
 

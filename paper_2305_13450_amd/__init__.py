@@ -31,6 +31,7 @@ EXPORTS = [
     "depsync_row_major", "depsync_policy_sem", "depsync_policy_value", "depsync_wave_model",
     "depsync_sync_count", "depsync_simulate_chain", "depsync_strerror", "depsync_last_hip_error",
     "depsync_tile_shape", "depsync_device_info", "depsync_gemm_chain_autotune", "depsync_conv_chain_autotune",
+    "depsync_gemm_chain_tuned", "depsync_conv_chain_tuned", "depsync_gemm_chain_set_tuned", "depsync_conv_chain_set_tuned",
 ]
 
 
@@ -119,6 +120,10 @@ def _lib() -> ctypes.CDLL:
         L.depsync_conv_chain_plan.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
         L.depsync_gemm_chain_autotune.argtypes = [ctypes.POINTER(GemmChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
         L.depsync_conv_chain_autotune.argtypes = [ctypes.POINTER(ConvChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
+        L.depsync_gemm_chain_tuned.argtypes = [ctypes.POINTER(GemmChainDesc), vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.depsync_conv_chain_tuned.argtypes = [ctypes.POINTER(ConvChainDesc), vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
+        L.depsync_gemm_chain_set_tuned.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, i32]
+        L.depsync_conv_chain_set_tuned.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, i32]
         L.depsync_row_major.argtypes = [i32] * 4
         L.depsync_policy_sem.argtypes = [i32] * 6
         L.depsync_policy_value.argtypes = [i32] * 4
@@ -299,6 +304,36 @@ def conv_chain_autotune(x, w1, mid, w2, out, policy: SyncPolicy, stream=None, re
     _check(_lib().depsync_conv_chain_autotune(ctypes.byref(d), policy.handle, _stream_handle(stream), reps,
                                               ctypes.byref(tile)), "depsync_conv_chain_autotune")
     return tile.value
+
+
+TUNED_NO_SPLIT, TUNED_HW_ORDER = 1, 2
+
+
+def gemm_chain_tuned(X, W1t, H, W2t, Y, policy: SyncPolicy, mid: int = MID_GELU, **attn):
+    """(tile, flags) the library remembers for this chain; tile 0 when it remembers nothing."""
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, TILE_AUTO, **attn)
+    tile, flags = ctypes.c_int(0), ctypes.c_int(0)
+    _check(_lib().depsync_gemm_chain_tuned(ctypes.byref(d), policy.handle, ctypes.byref(tile), ctypes.byref(flags)),
+           "depsync_gemm_chain_tuned")
+    return tile.value, flags.value
+
+
+def gemm_chain_set_tuned(X, W1t, H, W2t, Y, policy: SyncPolicy, tile: int, flags: int = 0, mid: int = MID_GELU, **attn):
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, TILE_AUTO, **attn)
+    _check(_lib().depsync_gemm_chain_set_tuned(ctypes.byref(d), policy.handle, tile, flags), "depsync_gemm_chain_set_tuned")
+
+
+def conv_chain_tuned(x, w1, mid, w2, out, policy: SyncPolicy):
+    d = _conv_desc(x, w1, mid, w2, out, TILE_AUTO)
+    tile, flags = ctypes.c_int(0), ctypes.c_int(0)
+    _check(_lib().depsync_conv_chain_tuned(ctypes.byref(d), policy.handle, ctypes.byref(tile), ctypes.byref(flags)),
+           "depsync_conv_chain_tuned")
+    return tile.value, flags.value
+
+
+def conv_chain_set_tuned(x, w1, mid, w2, out, policy: SyncPolicy, tile: int, flags: int = 0):
+    d = _conv_desc(x, w1, mid, w2, out, TILE_AUTO)
+    _check(_lib().depsync_conv_chain_set_tuned(ctypes.byref(d), policy.handle, tile, flags), "depsync_conv_chain_set_tuned")
 
 
 def _conv_desc(x, w1, mid, w2, out, tile) -> ConvChainDesc:

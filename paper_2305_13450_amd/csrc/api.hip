@@ -33,7 +33,7 @@ constexpr uint32_t WS_TRACE = WS_SEMS + WS_SEM_WORDS;     // TraceRec[WS_TRACE_C
 constexpr uint32_t WS_TRACE_CAP = 8192;
 constexpr uint32_t WS_ARRIVE = WS_TRACE + WS_TRACE_CAP * (sizeof(TraceRec) / 4);   // split-K arrival counters
 constexpr uint32_t WS_MAX_ARRIVE = 1u << 15;
-constexpr uint32_t WS_WORDS = WS_ARRIVE + WS_MAX_ARRIVE;
+constexpr uint32_t WS_WORDS = WS_ARRIVE + WS_MAX_ARRIVE * SYNC_WORD_STRIDE;   // one 128-byte line per counter
 
 int hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -52,11 +52,14 @@ struct sync_policy {
     depsync_policy_params params;
     int device;
     uint32_t* ws;
-    hipStream_t own_stream;
-    hipEvent_t ev_fork, ev_join;
+    hipStream_t own_stream;    // second stream when the caller gives none
+    hipStream_t third_stream;  // third stage of a three-stage chain in FINE mode
+    hipEvent_t ev_fork, ev_join, ev_join3;
     // epoch state: semaphores and the dispatch counter only ever grow between resets
     uint64_t geom_sig;
     uint32_t epoch;
+    uint32_t queue_epoch;  // chains that drew their tiles from the dispatch queues since the last reset
+    int force_order;       // autotuner only: -1 none, 0 dispatch queues, 1 hardware order
     uint32_t launches;
     float* scratch;        // split-K partial tiles, grown on demand
     size_t scratch_floats;
@@ -85,6 +88,7 @@ struct Plan {
     double flops, bytes;
     uint32_t amode;
     int dtype;
+    bool tuned_hw_order;             // the autotuner found one workgroup per tile in hardware order faster
 };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -254,8 +258,8 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     const int cus = device_cus(n_cu);
     if (cus <= 0) return DEPSYNC_EHIP;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    bool tuned_off = false;
-    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; }
+    bool tuned_off = false, tuned_hw = false;
+    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
     if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
     const TileShape* ts = tile_shape(tile);
     if (!ts) return DEPSYNC_EINVAL;
@@ -266,6 +270,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     p.n_stages = last + 1;
     p.amode = A_DENSE;
     p.dtype = d->dtype;
+    p.tuned_hw_order = tuned_hw;
     for (int s = 0; s < p.n_stages; ++s) p.tile[s] = tile;
     const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
     p.grid_y[0] = p.grid_y[last] = cdiv(d->M, ts->rows);
@@ -358,8 +363,8 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     if (cus <= 0) return DEPSYNC_EHIP;
     const uint32_t M = (uint32_t)Mpix;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    bool tuned_off = false;
-    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; }
+    bool tuned_off = false, tuned_hw = false;
+    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
     if (!tile) {
         // halo: a consumer row tile reads W+1 rows beyond each end
         tile = choose_tile(M, d->K1, 9 * d->C, d->K2, 9 * d->K1, false, cus, 1);
@@ -371,6 +376,7 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     p.n_stages = 2;
     p.amode = A_CONV3X3;
     p.dtype = d->dtype;
+    p.tuned_hw_order = tuned_hw;
     p.tile[0] = p.tile[1] = tile;
     p.grid_y[0] = p.grid_y[1] = cdiv(M, ts->rows);
     p.grid_x[0] = cdiv(d->K1, ts->cols);
@@ -447,6 +453,7 @@ int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t*
         if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, stream);
         if (e != hipSuccess) return hip_fail(e);
         pol->epoch = 0;
+        pol->queue_epoch = 0;
         pol->geom_sig = sig;
         pol->need_reset = false;
         pol->sems_dirty = 0;
@@ -480,6 +487,7 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
     }
     a.ticket = pol->ws + WS_TICKET;
     a.epoch = epoch;
+    a.queue_epoch = pol->queue_epoch;
     a.block_offset = 0;
     a.flags = pol->params.flags;
     // 0 selects a generous default bound (seconds), so that a dependency that can never be
@@ -498,7 +506,7 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
         st.queue_by_col = p.grid_x[s] >= 8 ? 1u : 0u;
         st.ksplit = p.ksplit[s];
         st.partials = pol->scratch ? pol->scratch + p.partial_off[s] : nullptr;
-        st.arrive = pol->ws + WS_ARRIVE + p.arrive_off[s];
+        st.arrive = pol->ws + WS_ARRIVE + p.arrive_off[s] * SYNC_WORD_STRIDE;
         st.zero_page = pol->ws + WS_ZERO_PAGE;
         st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
         if (s > 0) {
@@ -525,6 +533,11 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     hipStream_t sp = static_cast<hipStream_t>(sp_);
     hipStream_t sc = sc_ ? static_cast<hipStream_t>(sc_) : pol->own_stream;
     const bool sync = mode != DEPSYNC_MODE_PLAIN;
+    // Tiles in the hardware's order (Section IV-C, "T"): asked for by the caller, or found faster
+    // by the autotuner for this chain in one dispatch.  In-order dispatch of the block index on
+    // every XCD means no consumer workgroup is resident while a producer one is still unlaunched.
+    if (sync && mode == DEPSYNC_MODE_FUSED && (pol->force_order >= 0 ? pol->force_order == 1 : p.tuned_hw_order))
+        a.flags |= DEPSYNC_FLAG_HW_ORDER;
     uint32_t total = 0;
     for (int s = 0; s < p.n_stages; ++s) total += p.n_tiles[s];
     if (sync && (a.flags & DEPSYNC_FLAG_HW_ORDER) && mode == DEPSYNC_MODE_FINE && total > (uint32_t)p.slots)
@@ -546,11 +559,13 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
         if (mode == DEPSYNC_MODE_FINE) {
             HIP_TRY(hipEventRecord(pol->ev_fork, sp));
             HIP_TRY(hipStreamWaitEvent(sc, pol->ev_fork, 0));
+            if (p.n_stages > 2) HIP_TRY(hipStreamWaitEvent(pol->third_stream, pol->ev_fork, 0));
         }
         uint32_t off = 0;
         for (int s = 0; s < p.n_stages; ++s) {
             // producer on the caller's stream; later stages on the second stream in FINE mode
-            hipStream_t st = (mode == DEPSYNC_MODE_FINE && s > 0) ? sc : sp;
+            // (one stream per stage: launches on one stream would run one after the other)
+            hipStream_t st = mode != DEPSYNC_MODE_FINE || s == 0 ? sp : s == 1 ? sc : pol->third_stream;
             a.block_offset = off;
             // a launch works on its own stage and, when launches overlap (FINE), first helps
             // with whatever earlier stages have not been handed out yet
@@ -562,10 +577,15 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
         if (mode == DEPSYNC_MODE_FINE) {
             HIP_TRY(hipEventRecord(pol->ev_join, sc));
             HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join, 0));
+            if (p.n_stages > 2) {
+                HIP_TRY(hipEventRecord(pol->ev_join3, pol->third_stream));
+                HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join3, 0));
+            }
         }
     }
     if (sync) {
         pol->epoch += 1;
+        if (queues) pol->queue_epoch += 1;   // every queue counter has advanced by its length
     }
     pol->launches += 1;
     return DEPSYNC_OK;
@@ -593,10 +613,14 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
         e = hipMemcpy(p->ws + WS_STATUS, &sb, sizeof(sb), hipMemcpyHostToDevice);
     }
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->own_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->third_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join3, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming);
     if (e != hipSuccess) { (void)hipFree(p->ws); delete p; return hip_fail(e); }
     p->epoch = 0;
+    p->queue_epoch = 0;
+    p->force_order = -1;
     p->geom_sig = 0;
     p->launches = 0;
     p->sems_dirty = 0;
@@ -612,7 +636,9 @@ int sync_policy_destroy(sync_policy_t* pol) {
     (void)hipDeviceSynchronize();
     (void)hipEventDestroy(pol->ev_fork);
     (void)hipEventDestroy(pol->ev_join);
+    (void)hipEventDestroy(pol->ev_join3);
     (void)hipStreamDestroy(pol->own_stream);
+    (void)hipStreamDestroy(pol->third_stream);
     (void)hipFree(pol->ws);
     if (pol->scratch) (void)hipFree(pol->scratch);
     delete pol;
@@ -623,12 +649,13 @@ int dep_chain_reset(sync_policy_t* pol, void* stream) {
     if (!pol) return DEPSYNC_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, st));
-    HIP_TRY(launch_fill_u32(pol->ws + WS_ARRIVE, 0u, WS_MAX_ARRIVE, st));
+    HIP_TRY(launch_fill_u32(pol->ws + WS_ARRIVE, 0u, WS_MAX_ARRIVE * SYNC_WORD_STRIDE, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS + 1, 0xffffffffu, 1, st));   // first_timeout = -1
     HIP_TRY(launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, st));
     pol->sems_dirty = 0;
     pol->epoch = 0;
+    pol->queue_epoch = 0;
     pol->launches = 0;
     pol->need_reset = false;
     return DEPSYNC_OK;
@@ -766,7 +793,7 @@ int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync
 
 namespace {
 // Time every macro-tile shape the chain can run with, each with and without the library's split
-// along K (one-dispatch mode, HIP events on the caller's stream, two passes, blocks long enough
+// along K and with tiles drawn from the dispatch queues or named by the block index (one-dispatch mode, HIP events on the caller's stream, two passes, blocks long enough
 // to time), and remember the fastest combination.
 template <class Desc, class Run>
 int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* tile_out, Run run) {
@@ -792,8 +819,11 @@ int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* til
     };
     for (int pass = 0; pass < 2 && rc == DEPSYNC_OK; ++pass) {
         for (int t = 1; t < DEPSYNC_TILE__COUNT && rc == DEPSYNC_OK; ++t) {
-            for (int off = 0; off < (user_split == 0 ? 2 : 1) && rc == DEPSYNC_OK; ++off) {
+            for (int var = 0; var < (user_split == 0 ? 4 : 2) && rc == DEPSYNC_OK; ++var) {
+                const int off = var >> 1, hw = var & 1;
+                if (hw && (pol->params.flags & DEPSYNC_FLAG_HW_ORDER)) continue;   // already the caller's choice
                 pol->params.ksplit = off ? 1u : user_split;
+                pol->force_order = hw;
                 Desc dd = *d;
                 dd.tile_prod = dd.tile_cons = t;
                 int r = run(&dd);                   // warm-up; also tells whether this shape is usable
@@ -804,12 +834,13 @@ int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* til
                 if (r == DEPSYNC_OK && ms * reps < 1.0f)   // too short to compare: about 2 ms worth
                     r = time_block(&dd, (int)(2.0f / std::max(ms, 0.005f)) + 1, &ms);
                 if (r != DEPSYNC_OK) { rc = r; break; }
-                const int cand = t | (off ? 0x100 : 0);
+                const int cand = t | (off ? 0x100 : 0) | (hw ? 0x200 : 0);
                 if (best == 0 || ms < best_ms) { best = cand; best_ms = ms; }
             }
         }
     }
     pol->params.ksplit = user_split;
+    pol->force_order = -1;
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     if (rc != DEPSYNC_OK) return rc;
@@ -821,6 +852,24 @@ int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* til
     if (tile_out) *tile_out = best & 0xff;
     return DEPSYNC_OK;
 }
+// flags of a remembered choice: bit 0 no split along K, bit 1 tiles in hardware order
+template <class Desc>
+int get_tuned(const Desc* d, const sync_policy* pol, int* tile, int* flags) {
+    if (!d || !pol || !tile || !flags) return DEPSYNC_EINVAL;
+    const int v = tuned_tile(tune_key(d, pol));
+    *tile = v & 0xff;
+    *flags = (v >> 8) & 3;
+    return DEPSYNC_OK;
+}
+template <class Desc>
+int set_tuned(const Desc* d, const sync_policy* pol, int tile, int flags) {
+    if (!d || !pol || tile < 0 || tile >= DEPSYNC_TILE__COUNT || (flags & ~3)) return DEPSYNC_EINVAL;
+    std::lock_guard<std::mutex> g(g_tuned_mutex);
+    if (tile == 0) g_tuned.erase(tune_key(d, pol));
+    else g_tuned[tune_key(d, pol)] = tile | (flags << 8);
+    return DEPSYNC_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -837,6 +886,19 @@ int depsync_conv_chain_autotune(const depsync_conv_chain_desc* d, sync_policy_t*
     return autotune(d, pol, static_cast<hipStream_t>(stream), reps, tile_out, [&](const depsync_conv_chain_desc* dd) {
         return dep_conv_chain(dd, pol, DEPSYNC_MODE_FUSED, stream, nullptr);
     });
+}
+
+int depsync_gemm_chain_tuned(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int* tile, int* flags) {
+    return get_tuned(d, pol, tile, flags);
+}
+int depsync_conv_chain_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int* tile, int* flags) {
+    return get_tuned(d, pol, tile, flags);
+}
+int depsync_gemm_chain_set_tuned(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int tile, int flags) {
+    return set_tuned(d, pol, tile, flags);
+}
+int depsync_conv_chain_set_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int tile, int flags) {
+    return set_tuned(d, pol, tile, flags);
 }
 
 const char* depsync_strerror(int status) {

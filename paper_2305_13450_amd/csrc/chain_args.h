@@ -44,7 +44,7 @@ struct StageDesc {
     // partials in K order, applies the epilogue and posts.  The dispatch sees grid_y * ksplit rows.
     uint32_t ksplit;
     float* partials;           // [tile][ksplit][TM*TN] fp32, fragment order
-    uint32_t* arrive;          // one counter per tile, zero between chains
+    uint32_t* arrive;          // one counter per tile (SYNC_WORD_STRIDE words apart), zero between chains
     uint32_t op, amode, bmode, act;
     // conv geometry (A_CONV3X3): image height, width, input channels
     uint32_t H, W, Cin;
@@ -98,6 +98,7 @@ struct ChainArgs {
     uint32_t first_ticket[4];   // stage s owns tickets [first_ticket[s], first_ticket[s+1])
     uint32_t* ticket;           // dispatch counters: [stage][XCD queue], 3 x 8
     uint32_t epoch;             // chains run on this workspace since its last reset
+    uint32_t queue_epoch;       // those of them that drew their tiles from the dispatch queues
     uint32_t block_offset;      // HW order / PLAIN: ticket of this launch's block 0
     uint32_t stage_lo, stage_hi; // stages the workgroups of this launch may draw tiles of
     uint32_t flags;             // DEPSYNC_FLAG_*

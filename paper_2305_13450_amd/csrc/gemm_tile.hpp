@@ -447,7 +447,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         typedef float f32x4 __attribute__((ext_vector_type(4)));
         const uint32_t tile_lin = ty * s.grid_x + tx;
         float* const part = s.partials + (size_t)tile_lin * S * (TM * TN);
-        // fragment order: each lane stores 16 bytes next to its neighbours' (1 KB per instruction)
+        // fragment order: each lane stores 16 bytes next to its neighbours' (1 KB per instruction),
+        // written through to memory so that the count below can follow without a write-back
+        // of this XCD's whole L2
 #pragma unroll
         for (int i = 0; i < FM; ++i)
 #pragma unroll
@@ -455,37 +457,49 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     f32x4 v4 = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
-                    *(f32x4*)(part + (size_t)kz * (TM * TN) + ((((i * FN + j) * 4 + q) * 256 + tid) << 2)) = v4;
+                    float* dst = part + (size_t)kz * (TM * TN) + ((((i * FN + j) * 4 + q) * 256 + tid) << 2);
+                    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v4) : "memory");
                 }
-        // the partial must be in memory before the count moves: write this XCD's L2 back
+        // the partial is in memory before the count moves (every wave's stores, then the barrier)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         uint32_t* slot = reinterpret_cast<uint32_t*>(lds);
         if (tid == 0) {
-            asm volatile("buffer_wbl2 sc1\n\ts_waitcnt vmcnt(0)" ::: "memory");
-            const uint32_t old = __hip_atomic_fetch_add(s.arrive + tile_lin, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const uint32_t old = __hip_atomic_fetch_add(s.arrive + tile_lin * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             slot[0] = old;
         }
         __syncthreads();
         finish = __builtin_amdgcn_readfirstlane(slot[0]) == S - 1;
         __syncthreads();
         if (finish) {
-            // Every part's partial is in memory (each counted after its write-back) and none of
+            // Every part's partial is in memory (each counted after its stores had completed) and none of
             // these lines has been read on this XCD since the kernel started.  Sum in K order,
-            // whoever came last, so that the result does not depend on the arrival order.
-            if (tid == 0) __hip_atomic_store(s.arrive + tile_lin, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // whoever came last, so that the result does not depend on the arrival order.  All
+            // loads of one part and one row of blocks are issued before the first is added.
+            if (tid == 0) __hip_atomic_store(s.arrive + tile_lin * SYNC_WORD_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 #pragma unroll
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j)
 #pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        f32x4 sum = {0.f, 0.f, 0.f, 0.f};
-                        for (uint32_t z = 0; z < S; ++z)
-                            sum += *(const f32x4*)(part + (size_t)z * (TM * TN) + ((((i * FN + j) * 4 + q) * 256 + tid) << 2));
+                    for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            for (uint32_t z = 0; z < S; ++z) {
+                const float* src = part + (size_t)z * (TM * TN) + (tid << 2);
 #pragma unroll
-                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] = sum[e];
-                    }
+                for (int i = 0; i < FM; ++i) {
+                    f32x4 t4[FN][4];
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) t4[j][q] = *(const f32x4*)(src + ((((i * FN + j) * 4 + q) * 256) << 2));
+#pragma unroll
+                    for (int j = 0; j < FN; ++j)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += t4[j][q][e];
+                }
+            }
         }
     }
 

@@ -160,7 +160,7 @@ __device__ __forceinline__ uint32_t xcc_id() {
 // from the next non-empty one.  Hence no consumer tile is handed out while a producer tile is
 // undrawn anywhere: a workgroup can only be waiting when every tile of the stage it waits for
 // is already held by a resident workgroup, and by induction over the stages those finish.
-// A queue counter only grows: entry = counter - epoch * queue_length; a draw beyond the end
+// A queue counter only grows: entry = counter - queue_epoch * queue_length; a draw beyond the end
 // is undone, so after a chain every counter has advanced by exactly its queue length.
 __device__ __forceinline__ uint32_t queue_len(const StageDesc& st, uint32_t q) {
     const uint32_t rows = st.grid_y * st.ksplit;
@@ -240,7 +240,7 @@ struct Drawer {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             const uint32_t len = queue_len(st, j);
-            if (c[j] - a.epoch * len < len) avail |= 1u << j;
+            if (c[j] - a.queue_epoch * len < len) avail |= 1u << j;
         }
         if (avail == 0) return;                              // draw() will move on to the next stage
         const uint32_t rot = (avail >> home) | (avail << (8u - home));
@@ -261,7 +261,7 @@ struct Drawer {
             pending = false;
             const StageDesc& st = a.st[open];
             const uint32_t len = queue_len(st, pend_q);
-            uint32_t i = pend_val - a.epoch * len;
+            uint32_t i = pend_val - a.queue_epoch * len;
             if (i < len) {
                 if (open == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
                 stage = open; queue_entry(st, pend_q, i, tx, ty);
@@ -282,7 +282,7 @@ struct Drawer {
 #pragma unroll
                     for (int j = 0; j < 8; ++j) {
                         const uint32_t len = queue_len(st, j);
-                        if (c[j] - a.epoch * len < len) avail |= 1u << j;
+                        if (c[j] - a.queue_epoch * len < len) avail |= 1u << j;
                     }
                     if (avail == 0) break;                       // stage handed out: next stage
                     const uint32_t rot = (avail >> home) | (avail << (8u - home));
@@ -292,7 +292,7 @@ struct Drawer {
                 const uint32_t len = queue_len(st, q);
                 if (len == 0) continue;
                 uint32_t i = __hip_atomic_fetch_add(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
-                             a.epoch * len;
+                             a.queue_epoch * len;
                 if (i >= len) {   // emptied in the meantime: undo and look again
                     __hip_atomic_fetch_sub(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     continue;

@@ -253,6 +253,41 @@ def test_autotune_picks_a_tile_the_library_then_uses():
     pol.destroy()
 
 
+def test_remembered_hardware_order_alternates_with_the_dispatch_queues():
+    # A remembered choice with TUNED_HW_ORDER makes one-dispatch launches name tiles by the block
+    # index while two-stream and stream-sync launches of the same policy keep drawing from the
+    # queues: the queue counters then advance on some chains only.  More tiles than workgroup
+    # slots, several chains of each kind on one policy, same bits every time.
+    M, K1, N1, N2 = 2048, 256, 2048, 1024
+    t = inputs.mlp(M, K1, N1, N2, seed=61)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    X, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
+    H = torch.empty((M, N1), dtype=X.dtype, device="cuda")
+    Y = torch.empty((M, N2), dtype=X.dtype, device="cuda")
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    assert ds.gemm_chain_tuned(X, W1t, H, W2t, Y, pol) == (0, 0)
+    ds.gemm_chain_set_tuned(X, W1t, H, W2t, Y, pol, ds.TILE_64x64, ds.TUNED_HW_ORDER | ds.TUNED_NO_SPLIT)
+    assert ds.gemm_chain_tuned(X, W1t, H, W2t, Y, pol) == (ds.TILE_64x64, ds.TUNED_HW_ORDER | ds.TUNED_NO_SPLIT)
+    plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol)
+    assert plan.tile_prod == ds.TILE_64x64 and plan.n_prod + plan.n_cons > plan.slots
+    order = [ds.MODE_FUSED, ds.MODE_FINE, ds.MODE_FUSED, ds.MODE_STREAMSYNC, ds.MODE_FUSED, ds.MODE_FUSED,
+             ds.MODE_FINE, ds.MODE_FINE, ds.MODE_FUSED]
+    first = None
+    for i, mode in enumerate(order):
+        print(f"chain {i} mode={mode}", flush=True)
+        Hm, Ym = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode)
+        if first is None:
+            first = (Hm, Ym)
+            assert mid_err(Hm, Href) <= TOL_MID and rel_err(Ym, Yref) <= TOL_BF16
+        assert torch.equal(Hm, first[0]) and torch.equal(Ym, first[1]), (i, mode)
+    assert pol.status().timed_out == 0
+    ds.gemm_chain_set_tuned(X, W1t, H, W2t, Y, pol, 0)
+    assert ds.gemm_chain_tuned(X, W1t, H, W2t, Y, pol) == (0, 0)
+    with pytest.raises(ds.DepsyncError):
+        ds.gemm_chain_set_tuned(X, W1t, H, W2t, Y, pol, 99)
+    pol.destroy()
+
+
 def test_trace_records_cover_every_tile_in_order():
     # DEPSYNC_FLAG_TRACE: one record per tile with enter <= start <= ready <= end, producers
     # finishing before the consumers that wait for their whole row start computing
