@@ -477,13 +477,20 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
             // whoever came last, so that the result does not depend on the arrival order.  All
             // loads of one part and one row of blocks are issued before the first is added.
             if (tid == 0) __hip_atomic_store(s.arrive + tile_lin * SYNC_WORD_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // The sum is p0 + p1 + p2 + ... from the left.  A finisher that holds part 0 or
+            // part 1 starts from its registers (p1 + p0 and p0 + p1 are the same number) and
+            // skips reading its own partial back; any other starts from zero and reads them all.
+            const bool own = kz <= 1;
+            if (!own) {
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
+                for (int i = 0; i < FM; ++i)
 #pragma unroll
-                for (int j = 0; j < FN; ++j)
+                    for (int j = 0; j < FN; ++j)
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+                        for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+            }
             for (uint32_t z = 0; z < S; ++z) {
+                if (own && z == kz) continue;
                 const float* src = part + (size_t)z * (TM * TN) + (tid << 2);
 #pragma unroll
                 for (int i = 0; i < FM; ++i) {
