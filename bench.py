@@ -52,6 +52,10 @@ def parse():
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB three times, so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
+    ap.add_argument("--mfma-calibration", type=int, default=0, metavar="MS",
+                    help="also run the library's register-only bf16 MFMA loop for this many milliseconds with zero "
+                         "and with random operands (the practical MFMA ceiling under the chip's power cap) and "
+                         "report both in the JSON line")
     ap.add_argument("--sweep", default=None, metavar="FILE", help="run all configurations, write a markdown table")
     ap.add_argument("--ablation", default=None, metavar="FILE",
                     help="time the chosen workload with the optimisations of Section IV-C switched off one at a time")
@@ -391,6 +395,13 @@ def main():
         "device": {"cus": n_cu, "clock_mhz": clock_khz / 1e3},
         "roofline": roof,
     }
+
+    if args.mfma_calibration:
+        # after the chain, so that the chip is warm; random operands last
+        zero = ds.mfma_calibration(True, args.mfma_calibration)
+        rnd = ds.mfma_calibration(False, args.mfma_calibration)
+        out["mfma_calibration"] = {"zero_operands_tflops": zero, "random_operands_tflops": rnd,
+                                   "chain_vs_random_ceiling": tflops / rnd if rnd else None}
 
     if not args.no_cpu_baseline:
         import oracle

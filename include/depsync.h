@@ -326,6 +326,14 @@ const char* depsync_strerror(int status);
 int depsync_last_hip_error(void);
 /* Rows and columns of a depsync_tile id; DEPSYNC_EINVAL for AUTO or unknown ids.           */
 int depsync_tile_shape(int tile, int* rows, int* cols);
+/* Measurement aid, not part of the method: runs a loop of nothing but bf16 MFMAs
+ * (v_mfma_f32_32x32x16_bf16 on register operands, two workgroups of four waves per CU) on the
+ * current device's null stream for about `milliseconds` (1..2000) and reports what the last
+ * launch sustained, in TFLOP/s.  zero_operands != 0: all operand bits zero; else random bf16
+ * values with |x| in [1/8, 4).  The difference between the two is the chip's power cap at
+ * work: it is the practical ceiling of an MFMA-bound kernel on such data.  Allocates and frees
+ * 1 MiB + 4 bytes per thread of device memory; synchronises.  DEPSYNC_EINVAL / DEPSYNC_EHIP.     */
+int depsync_mfma_calibration(int zero_operands, int milliseconds, double* tflops);
 /* CU count and shader clock (kHz) of the current device.                                   */
 int depsync_device_info(int* n_cu, int* clock_khz);
 

@@ -32,6 +32,7 @@ EXPORTS = [
     "depsync_sync_count", "depsync_simulate_chain", "depsync_strerror", "depsync_last_hip_error",
     "depsync_tile_shape", "depsync_device_info", "depsync_gemm_chain_autotune", "depsync_conv_chain_autotune",
     "depsync_gemm_chain_tuned", "depsync_conv_chain_tuned", "depsync_gemm_chain_set_tuned", "depsync_conv_chain_set_tuned",
+    "depsync_mfma_calibration",
 ]
 
 
@@ -120,6 +121,7 @@ def _lib() -> ctypes.CDLL:
         L.depsync_conv_chain_plan.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
         L.depsync_gemm_chain_autotune.argtypes = [ctypes.POINTER(GemmChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
         L.depsync_conv_chain_autotune.argtypes = [ctypes.POINTER(ConvChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
+        L.depsync_mfma_calibration.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double)]
         L.depsync_gemm_chain_tuned.argtypes = [ctypes.POINTER(GemmChainDesc), vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.depsync_conv_chain_tuned.argtypes = [ctypes.POINTER(ConvChainDesc), vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.depsync_gemm_chain_set_tuned.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, i32]
@@ -393,6 +395,13 @@ def wave_model(n_tiles, occupancy, n_cu):
 def sync_count(kind, prod_grid, cons_grid, prod_rows_per_cons_row=1) -> int:
     return _lib().depsync_sync_count(kind, prod_grid[0], prod_grid[1], cons_grid[0], cons_grid[1],
                                      prod_rows_per_cons_row)
+
+
+def mfma_calibration(zero_operands: bool = False, milliseconds: int = 200) -> float:
+    """TFLOP/s a register-only bf16 MFMA loop sustains on this device (zero or random operands)."""
+    out = ctypes.c_double(0.0)
+    _check(_lib().depsync_mfma_calibration(int(zero_operands), milliseconds, ctypes.byref(out)), "depsync_mfma_calibration")
+    return out.value
 
 
 def simulate_chain(slots, prod_grid, d1, cons_grid, d2, halo=0, stream_sync=False) -> float:

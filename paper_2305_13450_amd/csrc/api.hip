@@ -923,6 +923,56 @@ int depsync_tile_shape(int tile, int* rows, int* cols) {
     return DEPSYNC_OK;
 }
 
+int depsync_mfma_calibration(int zero_operands, int milliseconds, double* tflops) {
+    if (!tflops || milliseconds <= 0 || milliseconds > 2000) return DEPSYNC_EINVAL;
+    int dev = 0, cus = 0;
+    HIP_TRY(hipGetDevice(&dev));
+    HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    const int n_blocks = 2 * cus;                      // two workgroups per CU: two waves per SIMD
+    constexpr size_t SRC_BYTES = 1u << 20;
+    std::vector<uint16_t> host(SRC_BYTES / 2, 0);
+    if (!zero_operands) {
+        // bf16 bit patterns with random sign and mantissa and exponents 124..128 (|x| in [1/8, 4))
+        uint64_t x = 0x9e3779b97f4a7c15ull;
+        for (auto& h : host) {
+            x = x * 6364136223846793005ull + 1442695040888963407ull;
+            const uint32_t r = (uint32_t)(x >> 33);
+            h = (uint16_t)(((r & 1u) << 15) | ((124u + (r >> 1) % 5u) << 7) | ((r >> 8) & 127u));
+        }
+    }
+    void* src = nullptr;
+    float* out = nullptr;
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    int rc = DEPSYNC_OK;
+    auto fail = [&](hipError_t e) { if (e != hipSuccess && rc == DEPSYNC_OK) rc = hip_fail(e); return e != hipSuccess; };
+    if (fail(hipMalloc(&src, SRC_BYTES)) || fail(hipMalloc(reinterpret_cast<void**>(&out), (size_t)n_blocks * 256 * sizeof(float))) ||
+        fail(hipMemcpy(src, host.data(), SRC_BYTES, hipMemcpyHostToDevice)) || fail(hipEventCreate(&e0)) ||
+        fail(hipEventCreate(&e1))) {
+        // fall through to the clean-up
+    } else {
+        // a short launch sizes the loop; then launches of about 10 ms each until the time is used
+        // up, so that the clock has settled under the power cap; the last launch is reported
+        const double flops_per_iter = (double)n_blocks * 4 * 8 * 2.0 * 32 * 32 * 16;
+        float ms = 0.f;
+        int iters = 2000;
+        double spent = 0.0;
+        while (rc == DEPSYNC_OK) {
+            if (fail(hipEventRecord(e0, nullptr)) || fail(launch_mfma_calibration(src, out, n_blocks, iters, nullptr)) ||
+                fail(hipEventRecord(e1, nullptr)) || fail(hipEventSynchronize(e1)) || fail(hipEventElapsedTime(&ms, e0, e1)))
+                break;
+            *tflops = flops_per_iter * iters / (ms * 1e-3) * 1e-12;
+            spent += ms;
+            if (spent >= milliseconds) break;
+            iters = (int)std::min(2.0e6, std::max(2000.0, iters * 10.0 / std::max(ms, 0.01f)));
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (src) (void)hipFree(src);
+    if (out) (void)hipFree(out);
+    return rc;
+}
+
 int depsync_device_info(int* n_cu, int* clock_khz) {
     if (!n_cu || !clock_khz) return DEPSYNC_EINVAL;
     int dev = 0;

@@ -380,6 +380,12 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     constexpr int NST = Cfg::NSTAGE;
     constexpr int NG = 4 * FM;            // MFMA groups per step
     constexpr int ND = NIA + NIB;         // DMA instructions per step
+    // groups the DMA instructions are spread over: with two stages the step's requests must
+    // have landed by the end of the same step, so they go out at its start (measured on the
+    // GPT-3 chain at M = 2048: 128x192 601 -> 581 us, 128x128 727 -> 669 us with all of them in
+    // the first group; the 256-row tiles, with twice the requests per wave, do best with a
+    // quarter of the groups: 256x192 714 -> 684 us)
+    constexpr int NGD = (NST > 2) ? NG : (FM <= 2 ? 1 : NG / 4);
     static_assert((NST - 2) * ND <= 48, "outstanding DMA instructions must fit the vmcnt counter");
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p) {
@@ -391,8 +397,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     }
 
     // The K loop.  Per step and wave: 4*FM groups of FN MFMAs.  The DMA instructions of the step
-    // NST-1 ahead are spread over those groups (a wave that issues them all at once sits at the
-    // memory pipeline's queue and starves its matrix unit), weights first; the fragments of the
+    // NST-1 ahead are spread over the first NGD of those groups (with three or more stages: all
+    // of them, since a wave that issues a burst sits at the memory pipeline's queue and starves
+    // its matrix unit, and the requests have a further step to land), weights first; the fragments of the
     // next 16-wide K slice are read from LDS while the current slice's MFMAs run.  The body is
     // free of branches: past the end the last slice is simply requested again into an idle stage.
     uint32_t cur = 0, req = NST - 1;      // stage being computed on / stage being filled
@@ -425,10 +432,12 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                     for (int j = (i * FN) / FM; j < ((i + 1) * FN) / FM; ++j)
                         bf[n][j] = *(const V8*)(lb + boff[kk + 1] + j * (32 * 128));
                 }
+                if (g < NGD) {
 #pragma unroll
-                for (int d = (g * ND) / NG; d < ((g + 1) * ND) / NG; ++d) {
-                    if (d < NIB) dma_B(req, d);
-                    else dma_A(req, d - NIB);
+                    for (int d = (g * ND) / NGD; d < ((g + 1) * ND) / NGD; ++d) {
+                        if (d < NIB) dma_B(req, d);
+                        else dma_A(req, d - NIB);
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < FN; ++j) acc[i][j] = M::mma(af[c][i], bf[c][j], acc[i][j]);

@@ -22,6 +22,10 @@ hipError_t launch_chain_kernel(int tile, int dtype, uint32_t amode, bool sync, u
 
 hipError_t launch_fill_u32(uint32_t* p, uint32_t value, uint32_t n, hipStream_t stream);
 
+// Register-only MFMA loop: n_blocks workgroups of 256 threads, 8 * iters MFMAs (32x32x16 bf16)
+// per wave; src holds 1 MiB of operand bits, out n_blocks * 256 floats (practically never written).
+hipError_t launch_mfma_calibration(const void* src, float* out, int n_blocks, int iters, hipStream_t stream);
+
 // One family per translation unit (kern_*.hip).
 hipError_t launch_bf16_gemm(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);
 hipError_t launch_f16_gemm(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);

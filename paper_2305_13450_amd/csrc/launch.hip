@@ -11,6 +11,52 @@ __global__ void fill_u32_kernel(uint32_t* p, uint32_t value, uint32_t n) {
     if (i < n) p[i] = value;
 }
 
+// Calibration: nothing but bf16 MFMAs on register operands (eight independent 32x32 accumulator
+// blocks per wave, no LDS, no memory traffic in the loop).  What this sustains is what the
+// matrix cores can do under the chip's power cap for the given operand values.
+typedef __bf16 cal_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float cal_f32x16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256, 2) void mfma_calibration_kernel(const uint4* src, float* out, int iters) {
+    const uint32_t t = blockIdx.x * 256 + threadIdx.x;
+    cal_bf16x8 a[4], b[2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const uint4 x = src[(t * 6 + i) & 0xffffu];
+        __builtin_memcpy(&a[i], &x, 16);
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const uint4 y = src[(t * 6 + 4 + j) & 0xffffu];
+        __builtin_memcpy(&b[j], &y, 16);
+    }
+    cal_f32x16 acc[4][2];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 2; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sum += acc[i][j][v];
+    if (sum == 123.456f) out[t] = sum;          // keeps the loop alive; practically never taken
+}
+
+hipError_t launch_mfma_calibration(const void* src, float* out, int n_blocks, int iters, hipStream_t stream) {
+    hipLaunchKernelGGL(mfma_calibration_kernel, dim3(n_blocks), dim3(256), 0, stream, static_cast<const uint4*>(src), out, iters);
+    return hipGetLastError();
+}
+
 hipError_t launch_chain_kernel(int tile, int dtype, uint32_t amode, bool sync, uint32_t n_blocks,
                                hipStream_t stream, const ChainArgs& a) {
     if (n_blocks == 0) return hipSuccess;

@@ -401,3 +401,13 @@ def test_k_blocked_weight_layout_gives_the_same_bits(mid):
             assert torch.equal(H, outs[0][0]) and torch.equal(Y, outs[0][1])
     with pytest.raises(ValueError):      # both operands must use one layout
         ds.dep_gemm_chain(X, W1b, H, W2t, Y, ds.SyncPolicy(ds.ROWSYNC), mid=mid)
+
+
+def test_mfma_calibration_reports_a_plausible_rate():
+    # register-only MFMA loop: faster on zero operands than on random ones (power cap), both
+    # below the 2516.6 TFLOP/s peak and far above anything a broken loop would report
+    zero = ds.mfma_calibration(True, 30)
+    rnd = ds.mfma_calibration(False, 30)
+    assert 500.0 < rnd <= zero * 1.05 and zero < 2600.0, (zero, rnd)
+    with pytest.raises(ds.DepsyncError):
+        ds.mfma_calibration(False, 0)
