@@ -181,23 +181,25 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
             const float m_new = fmaxf(m_run, mx);
             // a query beyond the sequence end or with no visible key yet keeps m = -inf: guard the exps
             const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;
-            const float alpha = exp2f(m_run - m_use);
+            const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);   // arguments are <= 0 or -inf: v_exp_f32 as is
             float psum = 0.0f;
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh)
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const float p = exp2f(st[kh][v] - m_use);
+                    const float p = __builtin_amdgcn_exp2f(st[kh][v] - m_use);
                     st[kh][v] = p;
                     psum += p;
                 }
             psum += __shfl_xor(psum, 32);
             l_run = l_run * alpha + psum;
             m_run = m_new;
+            if (__builtin_amdgcn_ballot_w64(alpha != 1.0f) != 0) {   // no query of the wave has a new maximum: O stays
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
+                for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+                    for (int v = 0; v < 16; ++v) o[i][v] *= alpha;
+            }
             // ---- O^T += V^T P^T : 4 steps of 16 keys ----
 #pragma unroll
             for (int step = 0; step < 4; ++step) {
