@@ -24,7 +24,7 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
 # HBM-side bytes of one chain from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by what the
 # same counter reads for a 1 GiB copy), per workload and launch mode; see profiles/*.md for the runs.
 MEASURED_TRAFFIC_BYTES = {
-    ("gpt3_mlp", 2048, "fused"): (1082264 + 86384) * 1024,
+    ("gpt3_mlp", 2048, "fused"): (1178589 + 80732) * 1024,
     ("gpt3_attn", 2048, "fused"): (1036536 + 104904) * 1024,
     ("vgg_conv", 2048, "fused"): (360834 + 55184) * 1024,     # 56x56x256, batch 16 (the default conv shape)
 }
