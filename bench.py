@@ -25,8 +25,8 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
 # same counter reads for a 1 GiB copy), per workload and launch mode; see profiles/*.md for the runs.
 MEASURED_TRAFFIC_BYTES = {
     ("gpt3_mlp", 2048, "fused"): (1178589 + 80732) * 1024,
-    ("gpt3_attn", 2048, "fused"): (1036536 + 104904) * 1024,
-    ("vgg_conv", 2048, "fused"): (360834 + 55184) * 1024,     # 56x56x256, batch 16 (the default conv shape)
+    ("gpt3_attn", 2048, "fused"): (1429047 + 102886) * 1024,
+    ("vgg_conv", 2048, "fused"): (348715 + 55168) * 1024,     # 56x56x256, batch 16 (the default conv shape)
 }
 
 
