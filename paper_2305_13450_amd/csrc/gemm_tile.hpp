@@ -93,7 +93,22 @@ __device__ __forceinline__ void store_out16(void* p, V8 v) {
         *(V8*)p = v;
     }
 }
-__device__ __forceinline__ float gelu_erf(float x) { return 0.5f * x * (1.0f + erff(x * 0.70710678118654752f)); }
+// GeLU x * Phi(x) with Phi written through erfc: Phi(x) = erfc(-x / sqrt 2) / 2, and for z >= 0
+// erfc(z) = t (a1 + t (a2 + t (a3 + t (a4 + t a5)))) exp(-z^2), t = 1 / (1 + p z), to 1.5e-7
+// absolute (Abramowitz and Stegun 7.1.26).  Working from erfc on the negative side keeps the
+// small values of the left tail free of the cancellation in 1 + erf; the whole thing is two
+// transcendental and a dozen plain instructions, less than half of a library erff, which
+// matters where the epilogue is not hidden (the workgroup that finishes a tile split along K).
+__device__ __forceinline__ float gelu_erf(float x) {
+    const float z = fabsf(x) * 0.70710678118654752f;
+    const float t = __builtin_amdgcn_rcpf(__builtin_fmaf(0.3275911f, z, 1.0f));
+    float h = __builtin_fmaf(t, 0.5f * 1.061405429f, 0.5f * -1.453152027f);   // coefficients of erfc / 2
+    h = __builtin_fmaf(t, h, 0.5f * 1.421413741f);
+    h = __builtin_fmaf(t, h, 0.5f * -0.284496736f);
+    h = __builtin_fmaf(t, h, 0.5f * 0.254829592f);
+    h = h * t * __builtin_amdgcn_exp2f(z * z * -1.4426950408889634f);          // erfc(z) / 2 = Phi(-|x|)
+    return x * (x >= 0.0f ? 1.0f - h : h);
+}
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
 // ---- dependency bookkeeping of a consumer tile -------------------------------------------
