@@ -56,6 +56,10 @@ def parse():
                     help="also run the library's register-only bf16 MFMA loop for this many milliseconds with zero "
                          "and with random operands (the practical MFMA ceiling under the chip's power cap) and "
                          "report both in the JSON line")
+    ap.add_argument("--sync-overhead", default=None, metavar="FILE",
+                    help="copy -> copy chain (consumer tile i waits for producer tile i; Section V, overhead of "
+                         "synchronisation): one full wave of tiles at several tile sizes, every launch mode; writes a "
+                         "markdown table and prints one JSON line for the 64 KiB tile")
     ap.add_argument("--sweep", default=None, metavar="FILE", help="run all configurations, write a markdown table")
     ap.add_argument("--ablation", default=None, metavar="FILE",
                     help="time the chosen workload with the optimisations of Section IV-C switched off one at a time")
@@ -330,6 +334,86 @@ def ablation(args, torch, ds, wl):
     print(json.dumps({"ablation": args.ablation, "rows": len(rows)}))
 
 
+def sync_overhead(args, torch, ds, n_cu):
+    """The copy -> copy chain: what post, wait and the dispatch queues cost when the tiles do nothing
+    but move bytes.  One full wave of tiles (CUs x 8 workgroups) and four waves, tile sizes 16 KiB to
+    1 MiB, TileSync and RowSync, every launch mode; interleaved blocks, median block."""
+    import oracle
+    sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    slots = n_cu * 8
+    modes = [("two streams", ds.MODE_FINE), ("one dispatch", ds.MODE_FUSED), ("stream sync", ds.MODE_STREAMSYNC),
+             ("plain", ds.MODE_PLAIN)]
+    rows, headline = [], None
+    for waves in (1, 4):
+        for tile_kib in (16, 64, 256, 1024):
+            tiles = slots * waves
+            n = tiles * tile_kib * 1024
+            if n > (2 << 30):
+                continue
+            src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 256)
+            mid, dst = torch.empty_like(src), torch.empty_like(src)
+            pols = {"tile": ds.SyncPolicy(ds.TILESYNC), "row": ds.SyncPolicy(ds.ROWSYNC)}
+            calls = {}
+            for pn, pol in pols.items():
+                for mn, mode in modes:
+                    if pn == "row" and mn in ("stream sync", "plain"):
+                        continue                      # the same launches whatever the policy
+                    def call(pol=pol, mode=mode):
+                        ds.dep_copy_chain(src, mid, dst, pol, mode=mode, tile_bytes=tile_kib * 1024,
+                                          stream_producer=sp, stream_consumer=sc)
+                    for _ in range(args.warmup):
+                        call()
+                    calls[(pn, mn)] = call
+            torch.cuda.synchronize()
+            assert torch.equal(dst, src)
+            blocks = {k: [] for k in calls}
+            for _ in range(args.rounds):
+                for k, c in calls.items():
+                    blocks[k].append(time_block(torch, c, sp, args.steps))
+            med = {k: sorted(b)[len(b) // 2] for k, b in blocks.items()}
+            plain, ss = med[("tile", "plain")], med[("tile", "stream sync")]
+            gbs = lambda us: 4.0 * n / us * 1e-3          # GB/s: each stage reads and writes the buffer once
+            rows.append(f"| {waves} | {tile_kib} KiB | {tiles} | {n >> 20} MiB | {med[('tile', 'one dispatch')]:.1f} | "
+                        f"{med[('tile', 'two streams')]:.1f} | {med[('row', 'one dispatch')]:.1f} | {med[('row', 'two streams')]:.1f} | "
+                        f"{ss:.1f} | {plain:.1f} | {100 * (med[('tile', 'one dispatch')] / plain - 1):+.1f} % | "
+                        f"{100 * (med[('tile', 'one dispatch')] / ss - 1):+.1f} % | {gbs(med[('tile', 'one dispatch')]):.0f} |")
+            if waves == 1 and tile_kib == 64:
+                headline = dict(n=n, tiles=tiles, med=med, plain=plain, ss=ss)
+                h = src[: 64 << 20].cpu().numpy()
+                t0 = time.perf_counter()
+                oracle.copy_chain(h)
+                cpu_s, cpu_bytes = time.perf_counter() - t0, h.size
+            for pol in pols.values():
+                pol.destroy()
+            del src, mid, dst
+    with open(args.sync_overhead, "w") as f:
+        f.write("| waves | tile | tiles per stage | buffer | TileSync, one dispatch (us) | TileSync, two streams | RowSync, one dispatch | "
+                "RowSync, two streams | stream sync | plain | one dispatch vs plain | vs stream sync | GB/s (TileSync, one dispatch) |\n"
+                "|---|---|---|---|---|---|---|---|---|---|---|---|---|\n" + "\n".join(rows) + "\n")
+    m = headline["med"]
+    best_key = min((k for k in m if k[1] in ("one dispatch", "two streams")), key=lambda k: m[k])
+    lat = m[best_key]
+    n = headline["n"]
+    out = {
+        "metric": "dependent-chain latency, fine-grained sync, best of {two-stream, one-dispatch} x sync policies (median block)",
+        "value": lat, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": lat / 1e3,
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"copy -> copy chain, {headline['tiles']} tiles of 64 KiB per stage (one full wave of {n_cu} CUs x 8 "
+                               f"workgroups), consumer tile i waits for producer tile i", "policy": best_key[0], "launch": best_key[1]},
+        "latency_us": {f"{k[0]}/{k[1]}": round(v, 2) for k, v in m.items()},
+        "overhead_vs_plain_pct": 100 * (lat / headline["plain"] - 1),
+        "speedup_vs_streamsync": headline["ss"] / lat,
+        "roofline": {"bound": "hbm", "achieved": 4.0 * n / lat * 1e-3, "peak": 8000.0, "unit": "GB/s",
+                     "frac": 4.0 * n / lat * 1e-3 / 8000.0, "traffic": None,
+                     "kernel": "copy_chain_kernel (both stages; one dispatch in fused mode)",
+                     "per_launch": {"bytes": 4.0 * n, "duration_us": lat}},
+        "cpu_baseline": {"value": cpu_s * 1e6 * n / cpu_bytes, "unit": "us", "cores": 1, "kind": "oracle",
+                         "sample": f"oracle copy chain timed on the first {cpu_bytes >> 20} MiB ({cpu_s:.3f} s), scaled to the buffer"},
+        "table": args.sync_overhead,
+    }
+    print(json.dumps(out))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -346,6 +430,8 @@ def main():
     n_cu, clock_khz = ds.device_info()
     if args.sweep:
         return sweep(args, torch, ds, inputs)
+    if args.sync_overhead:
+        return sync_overhead(args, torch, ds, n_cu)
 
     wl = Workload(torch, ds, inputs, args.workload, M=args.m, hw=args.hw, channels=args.channels, batch=args.batch,
                   w_layout=args.w_layout)

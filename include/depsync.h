@@ -297,6 +297,32 @@ int depsync_conv_chain_tuned(const depsync_conv_chain_desc* d, const sync_policy
 int depsync_gemm_chain_set_tuned(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int tile, int flags);
 int depsync_conv_chain_set_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int tile, int flags);
 
+
+/* ---- copy -> copy chain: what the synchronisation itself costs (Section V, overhead of
+ * synchronisation: tile i of the consumer depends on tile i of the producer and the kernels
+ * only move bytes) ------------------------------------------------------------------------ */
+typedef struct depsync_copy_chain_desc {
+    const void* src;      /* device, 16-byte aligned, `bytes` long; read only                 */
+    void* mid;            /* device, 128-byte aligned, `bytes` long; written by stage 0        */
+    void* dst;            /* device, 16-byte aligned, `bytes` long; written by stage 1         */
+    uint64_t bytes;       /* > 0, multiple of 16                                               */
+    uint32_t tile_bytes;  /* bytes one workgroup copies per tile: multiple of 4096; 0 = 65536  */
+} depsync_copy_chain_desc;
+
+/* dst = mid = src, as two dependent stages of ceil(bytes / tile_bytes) tiles each, with the
+ * same dispatch, post and wait as the GeMM and conv chains and the same launch modes.
+ * TILESYNC: consumer tile i waits for producer tile i (one semaphore per tile, at most 65536
+ * tiles, else DEPSYNC_ENOMEM); ROWSYNC: one semaphore that every producer tile posts to, so
+ * the consumer tiles start when the whole producer stage is done; STRIDEDSYNC:
+ * DEPSYNC_ENOTIMPL.  Buffers are the caller's and must not overlap; asynchronous like the
+ * other chains.  DEPSYNC_EINVAL for null or misaligned pointers and bad sizes.              */
+int dep_copy_chain(const depsync_copy_chain_desc* d, sync_policy_t* pol, depsync_mode mode,
+                   void* stream_producer, void* stream_consumer);
+/* Tiles per stage, workgroup slots (CUs x 8) and algorithmic bytes (4 x bytes: each stage
+ * reads and writes the buffer once) of the chain; n_cu 0 = the current device.              */
+int depsync_copy_chain_plan(const depsync_copy_chain_desc* d, const sync_policy_t* pol, int n_cu,
+                            depsync_plan_info* out);
+
 /* ---- host mirrors of the device index arithmetic (Fig. 4b; Section II-A) -------------- */
 
 /* Linear position of tile (x,y) in row-major order: y*grid_x + x.                         */

@@ -179,3 +179,16 @@ def conv_chain_pixels(x, w1, w2, pixels):
     lib().oracle_conv_chain_pixels(B, H, W, C, K1, K2, _p(x), _p(w1), _p(w2), n,
                                    pix.ctypes.data_as(ctypes.POINTER(ctypes.c_long)), _p(out))
     return out
+
+
+def copy_chain(src):
+    """The copy -> copy chain of the synchronisation-overhead experiment (Section V): both the
+    intermediate and the output are the input, byte for byte.  Returns (mid, dst) as new arrays."""
+    a = np.ascontiguousarray(np.asarray(src)).view(np.uint8).reshape(-1)
+    mid = np.empty_like(a)
+    for i in range(0, a.size, 1 << 20):          # plain element-wise definition, in slices
+        mid[i:i + (1 << 20)] = a[i:i + (1 << 20)]
+    dst = np.empty_like(mid)
+    for i in range(0, mid.size, 1 << 20):
+        dst[i:i + (1 << 20)] = mid[i:i + (1 << 20)]
+    return mid, dst

@@ -32,7 +32,7 @@ EXPORTS = [
     "depsync_sync_count", "depsync_simulate_chain", "depsync_strerror", "depsync_last_hip_error",
     "depsync_tile_shape", "depsync_device_info", "depsync_gemm_chain_autotune", "depsync_conv_chain_autotune",
     "depsync_gemm_chain_tuned", "depsync_conv_chain_tuned", "depsync_gemm_chain_set_tuned", "depsync_conv_chain_set_tuned",
-    "depsync_mfma_calibration",
+    "depsync_mfma_calibration", "dep_copy_chain", "depsync_copy_chain_plan",
 ]
 
 
@@ -98,6 +98,11 @@ class ConvChainDesc(ctypes.Structure):
                 ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32)]
 
 
+class CopyChainDesc(ctypes.Structure):
+    _fields_ = [("src", ctypes.c_void_p), ("mid", ctypes.c_void_p), ("dst", ctypes.c_void_p),
+                ("bytes", ctypes.c_uint64), ("tile_bytes", ctypes.c_uint32)]
+
+
 _LIB = None
 
 
@@ -121,6 +126,8 @@ def _lib() -> ctypes.CDLL:
         L.depsync_conv_chain_plan.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
         L.depsync_gemm_chain_autotune.argtypes = [ctypes.POINTER(GemmChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
         L.depsync_conv_chain_autotune.argtypes = [ctypes.POINTER(ConvChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
+        L.dep_copy_chain.argtypes = [ctypes.POINTER(CopyChainDesc), vp, i32, vp, vp]
+        L.depsync_copy_chain_plan.argtypes = [ctypes.POINTER(CopyChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
         L.depsync_mfma_calibration.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double)]
         L.depsync_gemm_chain_tuned.argtypes = [ctypes.POINTER(GemmChainDesc), vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.depsync_conv_chain_tuned.argtypes = [ctypes.POINTER(ConvChainDesc), vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
@@ -369,6 +376,35 @@ def conv_chain_plan(x, w1, mid, w2, out, policy: Optional[SyncPolicy], tile: int
     info = PlanInfo()
     _check(_lib().depsync_conv_chain_plan(ctypes.byref(d), policy.handle if policy else None, n_cu,
                                           ctypes.byref(info)), "depsync_conv_chain_plan")
+    return info
+
+
+def _copy_desc(src, mid, dst, tile_bytes: int) -> CopyChainDesc:
+    n = src.numel() * src.element_size()
+    for t, name in ((src, "src"), (mid, "mid"), (dst, "dst")):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"{name} must be a contiguous device tensor")
+        if t.numel() * t.element_size() != n:
+            raise ValueError("src, mid and dst must have the same size in bytes")
+    d = CopyChainDesc()
+    d.src, d.mid, d.dst = src.data_ptr(), mid.data_ptr(), dst.data_ptr()
+    d.bytes, d.tile_bytes = n, tile_bytes
+    return d
+
+
+def dep_copy_chain(src, mid, dst, policy: SyncPolicy, mode: int = MODE_FINE, tile_bytes: int = 0,
+                   stream_producer=None, stream_consumer=None) -> None:
+    """Enqueue mid = src then dst = mid as two dependent tiled stages (the synchronisation-overhead chain)."""
+    d = _copy_desc(src, mid, dst, tile_bytes)
+    _check(_lib().dep_copy_chain(ctypes.byref(d), policy.handle, mode, _stream_handle(stream_producer),
+                                 _stream_handle(stream_consumer)), "dep_copy_chain")
+
+
+def copy_chain_plan(src, mid, dst, policy: SyncPolicy, tile_bytes: int = 0, n_cu: int = 0) -> PlanInfo:
+    d = _copy_desc(src, mid, dst, tile_bytes)
+    info = PlanInfo()
+    _check(_lib().depsync_copy_chain_plan(ctypes.byref(d), policy.handle, n_cu, ctypes.byref(info)),
+           "depsync_copy_chain_plan")
     return info
 
 

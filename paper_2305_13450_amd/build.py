@@ -18,6 +18,7 @@ SOURCES = [
     "kern_f16_gemm.hip",
     "kern_bf16_conv.hip",
     "kern_f16_conv.hip",
+    "kern_copy.hip",
 ]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -411,6 +411,42 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     return DEPSYNC_OK;
 }
 
+// Copy chain: two stages of ceil(bytes / tile_bytes) tiles, one row of tiles each.
+int plan_copy(const depsync_copy_chain_desc* d, const sync_policy* pol, int n_cu, Plan& p) {
+    if (!d || !pol) return DEPSYNC_EINVAL;
+    if (!d->src || !d->mid || !d->dst || d->bytes == 0 || (d->bytes & 15u)) return DEPSYNC_EINVAL;
+    if (!aligned16(d->src) || !aligned16(d->dst) || (reinterpret_cast<uintptr_t>(d->mid) & 127u)) return DEPSYNC_EINVAL;
+    const uint32_t tb = d->tile_bytes ? d->tile_bytes : 65536u;
+    if (tb % 4096u) return DEPSYNC_EINVAL;
+    if (pol->kind == DEPSYNC_STRIDEDSYNC) return DEPSYNC_ENOTIMPL;
+    const uint64_t tiles64 = (d->bytes + tb - 1) / tb;
+    if (tiles64 > (1u << 20) || (d->bytes >> 4) > 0xffffffffull) return DEPSYNC_EINVAL;
+    const uint32_t tiles = (uint32_t)tiles64;
+    const int cus = device_cus(n_cu);
+    if (cus <= 0) return DEPSYNC_EHIP;
+    std::memset(&p, 0, sizeof(p));
+    p.n_stages = 2;
+    for (int s = 0; s < 2; ++s) {
+        p.tile[s] = 0;
+        p.grid_x[s] = tiles; p.grid_y[s] = 1; p.n_tiles[s] = tiles;
+        p.out_tm[s] = 1; p.out_tn[s] = 1; p.ksplit[s] = 1;
+    }
+    const bool row = pol->kind == DEPSYNC_ROWSYNC;
+    p.dep_kind[1] = row ? DEP_ROW : DEP_TILE;
+    p.sem_off[1] = 0;
+    p.sem_count[1] = row ? 1u : tiles;
+    p.sem_value[1] = row ? tiles : 1u;
+    p.n_sems = p.sem_count[1];
+    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
+    p.slots = cus * 8;                     // 256 threads, no LDS to speak of: eight workgroups per CU
+    p.flops = 0.0;
+    p.bytes = 4.0 * (double)d->bytes;      // each stage reads the buffer once and writes it once
+    p.amode = A_COPY;
+    p.dtype = 0;
+    p.tuned_hw_order = false;
+    return DEPSYNC_OK;
+}
+
 void fill_plan_info(const Plan& p, depsync_plan_info* o) {
     std::memset(o, 0, sizeof(*o));
     o->tile_prod = p.tile[0];
@@ -785,6 +821,45 @@ int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync
     s1.op = OP_GEMM; s1.amode = A_CONV3X3; s1.bmode = B_DENSE; s1.act = ACT_NONE;
     s1.H = d->H; s1.W = d->W; s1.Cin = d->K1;
     if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
+    fill_common(a, pol, p, epoch);
+    return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
+}
+
+int depsync_copy_chain_plan(const depsync_copy_chain_desc* d, const sync_policy_t* pol, int n_cu, depsync_plan_info* out) {
+    if (!out) return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_copy(d, pol, n_cu, p);
+    if (rc != DEPSYNC_OK) return rc;
+    fill_plan_info(p, out);
+    return DEPSYNC_OK;
+}
+
+int dep_copy_chain(const depsync_copy_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
+                   void* stream_consumer) {
+    if (!pol) return DEPSYNC_EINVAL;
+    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN &&
+        mode != DEPSYNC_MODE_FUSED)
+        return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_copy(d, pol, 0, p);
+    if (rc != DEPSYNC_OK) return rc;
+    uint32_t epoch = 0;
+    if (mode != DEPSYNC_MODE_PLAIN) {
+        rc = prepare_epoch(pol, p, static_cast<hipStream_t>(stream_producer), &epoch);
+        if (rc != DEPSYNC_OK) return rc;
+    }
+    ChainArgs a;
+    std::memset(&a, 0, sizeof(a));
+    const uint32_t tb = d->tile_bytes ? d->tile_bytes : 65536u;
+    StageDesc& s0 = a.st[0];
+    s0.A = d->src; s0.C = d->mid;
+    StageDesc& s1 = a.st[1];
+    s1.A = d->mid; s1.C = d->dst;
+    for (int s = 0; s < 2; ++s) {
+        a.st[s].N = (uint32_t)(d->bytes >> 4);   // 16-byte units in all
+        a.st[s].K = tb >> 4;                     // and per tile
+        a.st[s].amode = A_COPY;
+    }
     fill_common(a, pol, p, epoch);
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
 }

@@ -246,6 +246,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
             }
     }
 
+    dr.grab();   // the increment for the next tile travels while the stores drain
     if (SYNC) post_tile<true>(args, s, qblk * heads + head, head, qblk);
     if (tracing && tid == 0) {
         TraceRec r;

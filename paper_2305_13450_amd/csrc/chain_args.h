@@ -7,7 +7,7 @@
 namespace depsync {
 
 // How a stage addresses its A operand (rows of the implicit GeMM).
-enum AMode : uint32_t { A_DENSE = 0, A_CONV3X3 = 1 };
+enum AMode : uint32_t { A_DENSE = 0, A_CONV3X3 = 1, A_COPY = 2 };   // A_COPY: the stage moves bytes (copy chain)
 // How a stage maps rows of its B-operand tile to rows of the weight array.
 enum BMode : uint32_t { B_DENSE = 0, B_GATE_UP = 1 };
 // Epilogue applied to the fp32 accumulators before rounding to 16 bits.

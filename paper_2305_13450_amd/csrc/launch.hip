@@ -60,6 +60,7 @@ hipError_t launch_mfma_calibration(const void* src, float* out, int n_blocks, in
 hipError_t launch_chain_kernel(int tile, int dtype, uint32_t amode, bool sync, uint32_t n_blocks,
                                hipStream_t stream, const ChainArgs& a) {
     if (n_blocks == 0) return hipSuccess;
+    if (amode == A_COPY) return launch_copy(sync, n_blocks, stream, a);
     if (amode == A_CONV3X3)
         return dtype == 0 ? launch_bf16_conv(tile, sync, n_blocks, stream, a)
                           : launch_f16_conv(tile, sync, n_blocks, stream, a);

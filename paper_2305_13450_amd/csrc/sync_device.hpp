@@ -195,10 +195,17 @@ __device__ __forceinline__ TileId hw_order_tile(const ChainArgs& a) {
 // the tiles' durations are: workgroup i always runs on XCD i mod 8, so with one workgroup per
 // tile an XCD that happened to get the long tiles would still have to run its share of the
 // rest.  The draws are made by the first lane of wave 1 (wave 0's first lane does the post).
-// A draw first looks at the eight counters of the earliest stage not known to be handed out
-// and only then increments one that still has entries, so exhausted queues see loads, not
-// atomics; the look for the NEXT tile is started when the current tile's K loop ends (peek)
-// and is in flight during the epilogue.
+//
+// Traffic on the counters' lines is what a draw costs when thousands of workgroups draw (reads
+// and increments of one line are served one after the other: 2048 workgroups that each read
+// all eight counters per tile made a chain of 64 KiB copy tiles take 213 us instead of 89).
+// So in the steady state a draw is ONE increment of the queue the workgroup drew from last,
+// started during the current tile's stores (grab) and collected when the tile is done.  The
+// counters are only read where a blind increment would probably fail: near the end of the
+// queue peek reads that queue's counter when the tile's main loop ends; if it shows the queue
+// empty, grab starts reading all eight, so that draw can pick another queue (or move on to
+// the next stage) without a round trip for the look; and after a failed increment.  A failed
+// increment is undone.
 constexpr uint32_t DRAW_THREAD = 64;
 
 struct Drawer {
@@ -206,100 +213,120 @@ struct Drawer {
     uint32_t* slot;        // four words of LDS used to broadcast a tile to the workgroup
     uint32_t home;         // XCD this workgroup runs on
     uint32_t open;         // first stage not yet known to be handed out completely
-    uint32_t c[8];         // counters of stage `open` as read by peek()
-    bool peeked;
+    uint32_t cur_q;        // queue of stage `open` this workgroup drew from last
+    uint32_t last_i;       // entry it got there (0xffffffff: none yet in this stage)
+    uint32_t c0;           // counter of (open, cur_q) as read by peek()
+    uint32_t c[8];         // counters of stage `open` as read by grab() when c0 showed the queue empty
+    bool peeked;           // c0 is being read
+    bool looked;           // c[] is being read
     bool first;
     bool pending;          // grab() has an increment in flight
     uint32_t pend_q, pend_val;
 
     __device__ __forceinline__ Drawer(const ChainArgs& args, uint32_t* lds_slot)
-        : a(args), slot(lds_slot), home(xcc_id()), open(args.stage_lo), peeked(false), first(true), pending(false), pend_q(0), pend_val(0) {}
+        : a(args), slot(lds_slot), home(xcc_id()), open(args.stage_lo), cur_q(home), last_i(0xffffffffu),
+          peeked(false), looked(false), first(true), pending(false), pend_q(0), pend_val(0) {}
 
-    __device__ __forceinline__ void load_counters() {
-        const uint32_t* cnt = a.ticket + 8u * open * SYNC_WORD_STRIDE;
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            c[j] = __hip_atomic_load(cnt + j * SYNC_WORD_STRIDE, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __device__ __forceinline__ uint32_t* counter(uint32_t q) const { return a.ticket + (8u * open + q) * SYNC_WORD_STRIDE; }
+    __device__ __forceinline__ uint32_t base(uint32_t len) const { return a.queue_epoch * len; }
+
+    // Is the queue this workgroup draws from close enough to its end that a blind increment
+    // would probably fail?  (As many entries left as workgroups may be drawing from it.)
+    __device__ __forceinline__ bool near_end() const {
+        if (last_i == 0xffffffffu) return false;
+        const uint32_t len = queue_len(a.st[open], cur_q);
+        return last_i + (gridDim.x >> 3) + 2u >= len;
     }
 
-    // Start reading the counters for the next draw (the values are not looked at here, so the
-    // loads stay in flight behind whatever the wave does next).
-    __device__ __forceinline__ void peek() {
-        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi) return;
-        load_counters();
-        peeked = true;
-    }
-
-    // A while after peek(): if the counters it read show entries left, start the increment on
-    // the chosen queue so that its round trip, too, passes during the tile's stores.  Nothing is
-    // started on a queue that looked empty, so exhausted queues still see loads only.
-    __device__ __forceinline__ void grab() {
-        if (threadIdx.x != DRAW_THREAD || !peeked || open > a.stage_hi) return;
-        const StageDesc& st = a.st[open];
+    // Entries left in the queues of stage `open`, one bit per queue, by the counters in c[].
+    __device__ __forceinline__ uint32_t available() const {
         uint32_t avail = 0;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const uint32_t len = queue_len(st, j);
-            if (c[j] - a.queue_epoch * len < len) avail |= 1u << j;
+            const uint32_t len = queue_len(a.st[open], j);
+            if (c[j] - base(len) < len) avail |= 1u << j;
         }
-        if (avail == 0) return;                              // draw() will move on to the next stage
+        return avail;
+    }
+    __device__ __forceinline__ uint32_t first_from_home(uint32_t avail) const {
         const uint32_t rot = (avail >> home) | (avail << (8u - home));
-        pend_q = (home + (uint32_t)__builtin_ctz(rot & 0xffu)) & 7u;
-        pend_val = __hip_atomic_fetch_add(a.ticket + (8u * open + pend_q) * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED,
-                                          __HIP_MEMORY_SCOPE_AGENT);
+        return (home + (uint32_t)__builtin_ctz(rot & 0xffu)) & 7u;
+    }
+
+    __device__ __forceinline__ void look() {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) c[j] = __hip_atomic_load(counter(j), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        looked = true;
+    }
+
+    // When the tile's main loop ends: near the end of the queue, start reading its counter (the
+    // value is not looked at here, so the load stays in flight behind what the wave does next).
+    __device__ __forceinline__ void peek() {
+        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi || !near_end()) return;
+        c0 = __hip_atomic_load(counter(cur_q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        peeked = true;
+    }
+
+    // A while later (during the tile's stores): start the increment for the next tile on the
+    // queue drawn from last; near its end only if the counter read by peek() shows entries,
+    // else start reading all eight counters for draw().
+    __device__ __forceinline__ void grab() {
+        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi || pending) return;
+        const uint32_t len = queue_len(a.st[open], cur_q);
+        if (near_end()) {
+            if (!peeked) return;                              // draw() will look first
+            peeked = false;
+            if (c0 - base(len) >= len) { look(); return; }    // empty: draw() picks another queue or moves on
+        }
+        if (len == 0) return;
+        pend_q = cur_q;
+        pend_val = __hip_atomic_fetch_add(counter(cur_q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         pending = true;
-        peeked = false;
+    }
+
+    __device__ __forceinline__ bool take(uint32_t q, uint32_t val, uint32_t& stage, uint32_t& tx, uint32_t& ty) {
+        const StageDesc& st = a.st[open];
+        const uint32_t len = queue_len(st, q);
+        uint32_t i = val - base(len);
+        if (i >= len) {                                       // emptied before this increment: undo it
+            __hip_atomic_fetch_sub(counter(q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            return false;
+        }
+        cur_q = q; last_i = i;
+        if (open == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
+        stage = open; queue_entry(st, q, i, tx, ty);
+        return true;
     }
 
     // DRAW_THREAD: draw a tile (blocking).
     __device__ __forceinline__ bool draw(uint32_t& stage, uint32_t& tx, uint32_t& ty) {
         // a workgroup launched for the first stage it may work on goes straight for its XCD's
-        // queue the first time (one round trip)
+        // queue the first time (one round trip); so does every workgroup that moves on to a
+        // stage with at least a tile for each of them
         bool direct = first && a.block_offset + blockIdx.x < a.first_ticket[a.stage_lo + 1];
         first = false;
+        peeked = false;
         if (pending) {                                       // the increment grab() started
             pending = false;
-            const StageDesc& st = a.st[open];
-            const uint32_t len = queue_len(st, pend_q);
-            uint32_t i = pend_val - a.queue_epoch * len;
-            if (i < len) {
-                if (open == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
-                stage = open; queue_entry(st, pend_q, i, tx, ty);
-                return true;
-            }
-            __hip_atomic_fetch_sub(a.ticket + (8u * open + pend_q) * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED,
-                                   __HIP_MEMORY_SCOPE_AGENT);   // emptied since the look: undo, look again
+            if (take(pend_q, pend_val, stage, tx, ty)) return true;
         }
-        for (; open <= a.stage_hi; ++open, peeked = false) {
+        bool fresh = false;                                  // moved on to this stage just now
+        for (; open <= a.stage_hi; ++open, cur_q = home, last_i = 0xffffffffu, fresh = true) {
             const StageDesc& st = a.st[open];
-            uint32_t* cnt = a.ticket + 8u * open * SYNC_WORD_STRIDE;
+            // blind only where every workgroup of the launch can get a tile of the stage
+            if (fresh) direct = st.grid_x * st.grid_y * st.ksplit >= gridDim.x;
             for (uint32_t attempt = 0; attempt < 16; ++attempt) {
                 uint32_t q = home;
-                if (!direct) {
-                    if (!peeked) load_counters();
-                    peeked = false;
-                    uint32_t avail = 0;
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) {
-                        const uint32_t len = queue_len(st, j);
-                        if (c[j] - a.queue_epoch * len < len) avail |= 1u << j;
-                    }
+                if (!direct || queue_len(st, home) == 0) {
+                    if (!looked) look();
+                    looked = false;                              // one look serves one attempt
+                    const uint32_t avail = available();
                     if (avail == 0) break;                       // stage handed out: next stage
-                    const uint32_t rot = (avail >> home) | (avail << (8u - home));
-                    q = (home + (uint32_t)__builtin_ctz(rot & 0xffu)) & 7u;   // first non-empty from home
+                    q = first_from_home(avail);
                 }
                 direct = false;
-                const uint32_t len = queue_len(st, q);
-                if (len == 0) continue;
-                uint32_t i = __hip_atomic_fetch_add(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) -
-                             a.queue_epoch * len;
-                if (i >= len) {   // emptied in the meantime: undo and look again
-                    __hip_atomic_fetch_sub(cnt + q * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    continue;
-                }
-                if (open == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
-                stage = open; queue_entry(st, q, i, tx, ty);
-                return true;
+                const uint32_t val = __hip_atomic_fetch_add(counter(q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (take(q, val, stage, tx, ty)) return true;    // else emptied in the meantime: look again
             }
             // 16 lost races in a row: whatever is left of this stage is being taken by others
         }

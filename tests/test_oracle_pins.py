@@ -293,3 +293,18 @@ def test_fig1_example(golden):
     assert g["n_sm"] * g["waves_per_kernel_stream_sync"] - n == g["idle_sms_in_each_second_wave"]
     assert sm.sync_count("tile", grid, grid) == g["syncs_tilesync"]
     assert sm.sync_count("row", grid, grid) == g["syncs_rowsync"]
+
+
+def test_copy_chain_is_the_identity_on_bytes():
+    # hand-written bytes, a size that is not a multiple of the slice, and independence of the input
+    src = np.array([0, 1, 2, 254, 255, 128, 127, 7], dtype=np.uint8)
+    mid, dst = oracle.copy_chain(src)
+    assert mid.tolist() == [0, 1, 2, 254, 255, 128, 127, 7] and dst.tolist() == mid.tolist()
+    big = (np.arange((1 << 20) * 2 + 13, dtype=np.uint64) * 2654435761 >> 7).astype(np.uint8)
+    mid, dst = oracle.copy_chain(big)
+    assert mid.shape == big.shape and np.array_equal(dst, big) and np.array_equal(mid, big)
+    big[5] ^= 0xFF
+    assert dst[5] != big[5]                      # copies, not views
+    f = np.array([1.5, -2.25], dtype=np.float32)
+    mid, dst = oracle.copy_chain(f)
+    assert dst.view(np.float32).tolist() == [1.5, -2.25]
