@@ -337,12 +337,20 @@ def ablation(args, torch, ds, wl):
 def sync_overhead(args, torch, ds, n_cu):
     """The copy -> copy chain: what post, wait and the dispatch queues cost when the tiles do nothing
     but move bytes.  One full wave of tiles (CUs x 8 workgroups) and four waves, tile sizes 16 KiB to
-    1 MiB, TileSync and RowSync, every launch mode; interleaved blocks, median block."""
+    1 MiB, every launch mode, tiles named by the block index or drawn from the dispatch queues;
+    interleaved blocks, median block."""
     import oracle
     sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
     slots = n_cu * 8
-    modes = [("two streams", ds.MODE_FINE), ("one dispatch", ds.MODE_FUSED), ("stream sync", ds.MODE_STREAMSYNC),
-             ("plain", ds.MODE_PLAIN)]
+    variants = [   # label, policy kind, flags, mode, counts as fine-grained
+        ("TileSync, one dispatch, block-index order", ds.TILESYNC, ds.FLAG_HW_ORDER, ds.MODE_FUSED, True),
+        ("TileSync, one dispatch, queues", ds.TILESYNC, 0, ds.MODE_FUSED, True),
+        ("TileSync, two streams, queues", ds.TILESYNC, 0, ds.MODE_FINE, True),
+        ("RowSync, one dispatch, block-index order", ds.ROWSYNC, ds.FLAG_HW_ORDER, ds.MODE_FUSED, True),
+        ("stream sync, block-index order", ds.TILESYNC, ds.FLAG_HW_ORDER, ds.MODE_STREAMSYNC, False),
+        ("stream sync, queues", ds.TILESYNC, 0, ds.MODE_STREAMSYNC, False),
+        ("plain", ds.TILESYNC, 0, ds.MODE_PLAIN, False),
+    ]
     rows, headline = [], None
     for waves in (1, 4):
         for tile_kib in (16, 64, 256, 1024):
@@ -352,18 +360,16 @@ def sync_overhead(args, torch, ds, n_cu):
                 continue
             src = torch.empty(n, dtype=torch.uint8, device="cuda").random_(0, 256)
             mid, dst = torch.empty_like(src), torch.empty_like(src)
-            pols = {"tile": ds.SyncPolicy(ds.TILESYNC), "row": ds.SyncPolicy(ds.ROWSYNC)}
-            calls = {}
-            for pn, pol in pols.items():
-                for mn, mode in modes:
-                    if pn == "row" and mn in ("stream sync", "plain"):
-                        continue                      # the same launches whatever the policy
-                    def call(pol=pol, mode=mode):
-                        ds.dep_copy_chain(src, mid, dst, pol, mode=mode, tile_bytes=tile_kib * 1024,
-                                          stream_producer=sp, stream_consumer=sc)
-                    for _ in range(args.warmup):
-                        call()
-                    calls[(pn, mn)] = call
+            pols, calls = [], {}
+            for label, kind, flags, mode, _ in variants:
+                pol = ds.SyncPolicy(kind, flags=flags)
+                pols.append(pol)
+                def call(pol=pol, mode=mode):
+                    ds.dep_copy_chain(src, mid, dst, pol, mode=mode, tile_bytes=tile_kib * 1024,
+                                      stream_producer=sp, stream_consumer=sc)
+                for _ in range(args.warmup):
+                    call()
+                calls[label] = call
             torch.cuda.synchronize()
             assert torch.equal(dst, src)
             blocks = {k: [] for k in calls}
@@ -371,36 +377,35 @@ def sync_overhead(args, torch, ds, n_cu):
                 for k, c in calls.items():
                     blocks[k].append(time_block(torch, c, sp, args.steps))
             med = {k: sorted(b)[len(b) // 2] for k, b in blocks.items()}
-            plain, ss = med[("tile", "plain")], med[("tile", "stream sync")]
-            gbs = lambda us: 4.0 * n / us * 1e-3          # GB/s: each stage reads and writes the buffer once
-            rows.append(f"| {waves} | {tile_kib} KiB | {tiles} | {n >> 20} MiB | {med[('tile', 'one dispatch')]:.1f} | "
-                        f"{med[('tile', 'two streams')]:.1f} | {med[('row', 'one dispatch')]:.1f} | {med[('row', 'two streams')]:.1f} | "
-                        f"{ss:.1f} | {plain:.1f} | {100 * (med[('tile', 'one dispatch')] / plain - 1):+.1f} % | "
-                        f"{100 * (med[('tile', 'one dispatch')] / ss - 1):+.1f} % | {gbs(med[('tile', 'one dispatch')]):.0f} |")
+            fine = min(med[v[0]] for v in variants if v[4])
+            ss = min(med["stream sync, block-index order"], med["stream sync, queues"])
+            plain = med["plain"]
+            rows.append(f"| {waves} | {tile_kib} KiB | {tiles} | {n >> 20} MiB | " + " | ".join(f"{med[v[0]]:.1f}" for v in variants) +
+                        f" | {100 * (fine / plain - 1):+.1f} % | {100 * (fine / ss - 1):+.1f} % | {4.0 * n / fine * 1e-3:.0f} |")
             if waves == 1 and tile_kib == 64:
                 headline = dict(n=n, tiles=tiles, med=med, plain=plain, ss=ss)
                 h = src[: 64 << 20].cpu().numpy()
                 t0 = time.perf_counter()
                 oracle.copy_chain(h)
                 cpu_s, cpu_bytes = time.perf_counter() - t0, h.size
-            for pol in pols.values():
+            for pol in pols:
                 pol.destroy()
             del src, mid, dst
     with open(args.sync_overhead, "w") as f:
-        f.write("| waves | tile | tiles per stage | buffer | TileSync, one dispatch (us) | TileSync, two streams | RowSync, one dispatch | "
-                "RowSync, two streams | stream sync | plain | one dispatch vs plain | vs stream sync | GB/s (TileSync, one dispatch) |\n"
-                "|---|---|---|---|---|---|---|---|---|---|---|---|---|\n" + "\n".join(rows) + "\n")
+        f.write("| waves | tile | tiles per stage | buffer | " + " | ".join(v[0] + (" (us)" if i == 0 else "") for i, v in enumerate(variants)) +
+                " | best fine-grained vs plain | vs best stream sync | GB/s (best fine-grained) |\n" +
+                "|" + "---|" * (len(variants) + 7) + "\n" + "\n".join(rows) + "\n")
     m = headline["med"]
-    best_key = min((k for k in m if k[1] in ("one dispatch", "two streams")), key=lambda k: m[k])
-    lat = m[best_key]
+    best = min((v[0] for v in variants if v[4]), key=lambda k: m[k])
+    lat = m[best]
     n = headline["n"]
     out = {
         "metric": "dependent-chain latency, fine-grained sync, best of {two-stream, one-dispatch} x sync policies (median block)",
         "value": lat, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": lat / 1e3,
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"copy -> copy chain, {headline['tiles']} tiles of 64 KiB per stage (one full wave of {n_cu} CUs x 8 "
-                               f"workgroups), consumer tile i waits for producer tile i", "policy": best_key[0], "launch": best_key[1]},
-        "latency_us": {f"{k[0]}/{k[1]}": round(v, 2) for k, v in m.items()},
+                               f"workgroups), consumer tile i waits for producer tile i", "variant": best},
+        "latency_us": {k: round(v, 2) for k, v in m.items()},
         "overhead_vs_plain_pct": 100 * (lat / headline["plain"] - 1),
         "speedup_vs_streamsync": headline["ss"] / lat,
         "roofline": {"bound": "hbm", "achieved": 4.0 * n / lat * 1e-3, "peak": 8000.0, "unit": "GB/s",
