@@ -61,6 +61,8 @@ def parse():
                          "synchronisation): one full wave of tiles at several tile sizes, every launch mode; writes a "
                          "markdown table and prints one JSON line for the 64 KiB tile")
     ap.add_argument("--sweep", default=None, metavar="FILE", help="run all configurations, write a markdown table")
+    ap.add_argument("--sweep-set", default="paper", choices=["paper", "resnet"],
+                    help="rows of --sweep: the five configurations of the headline table, or ResNet-38's conv pairs")
     ap.add_argument("--ablation", default=None, metavar="FILE",
                     help="time the chosen workload with the optimisations of Section IV-C switched off one at a time")
     return ap.parse_args()
@@ -85,7 +87,7 @@ class Workload:
 
     def __init__(self, torch, ds, inputs, kind, M=2048, hw=56, channels=256, batch=16, w_layout="rows"):
         self.kind, self.M = kind, M
-        self.conv = kind == "vgg_conv"
+        self.conv = kind in ("vgg_conv", "resnet_conv")
         self.attn = None
         self.ds = ds
         if self.conv:
@@ -94,7 +96,8 @@ class Workload:
             self.x, self.w1, self.w2 = t["x"].cuda(), t["w1"].cuda(), t["w2"].cuda()
             self.mid_t = torch.empty((batch, hw, hw, channels), dtype=self.x.dtype, device="cuda")
             self.out = torch.empty_like(self.mid_t)
-            self.name = f"VGG conv pair {hw}x{hw}x{channels} -> ReLU -> {channels}, batch {batch}, 3x3 s1 p1, NHWC bf16"
+            net = "VGG" if kind == "vgg_conv" else "ResNet-38"
+            self.name = f"{net} conv pair {hw}x{hw}x{channels} -> ReLU -> {channels}, batch {batch}, 3x3 s1 p1, NHWC bf16"
             self.policies = ["strided", "row", "tile"]
             return
         if kind == "gpt3_mlp":
@@ -258,11 +261,16 @@ def roofline(plan, lat_us):
 def sweep(args, torch, ds, inputs):
     """All configurations -> markdown table."""
     sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
-    cases = [("cfg1", dict())]
-    cases += [("gpt3_mlp", dict(M=m)) for m in inputs.CFG2["Ms"]]
-    cases += [("llama_mlp", dict(M=m)) for m in inputs.CFG3["Ms"]]
-    cases += [("gpt3_attn", dict(M=m)) for m in inputs.CFG4["Ms"]]
-    cases += [("vgg_conv", dict(hw=hw, channels=ch, batch=b)) for hw, ch in inputs.CFG5["stages"] for b in (1, 16)]
+    if args.sweep_set == "resnet":
+        # the paper's second conv workload (Fig. 7): ResNet-38's pairs of 3x3 convolutions, 56x56x64 ... 7x7x512
+        cases = [("resnet_conv", dict(hw=hw, channels=ch, batch=b))
+                 for hw, ch in ((56, 64), (28, 128), (14, 256), (7, 512)) for b in (1, 8, 32)]
+    else:
+        cases = [("cfg1", dict())]
+        cases += [("gpt3_mlp", dict(M=m)) for m in inputs.CFG2["Ms"]]
+        cases += [("llama_mlp", dict(M=m)) for m in inputs.CFG3["Ms"]]
+        cases += [("gpt3_attn", dict(M=m)) for m in inputs.CFG4["Ms"]]
+        cases += [("vgg_conv", dict(hw=hw, channels=ch, batch=b)) for hw, ch in inputs.CFG5["stages"] for b in (1, 16)]
     lines = ["| workload | tile | P / (mid) / C tiles | slots | waves ss / fine | best fine-grained us (policy/launch) | "
              "stream-sync us | plain us | speedup vs ss | vs plain | TFLOP/s | roofline | slot util. | final wave |",
              "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]

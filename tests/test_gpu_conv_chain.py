@@ -166,3 +166,19 @@ def test_conv_chain_fp16():
         assert rel_err(out, oref) <= 4e-3
         assert torch.equal(mid, res[0][0]) and torch.equal(out, res[0][1])
     pol.destroy()
+
+
+@pytest.mark.parametrize("hw,ch,batch", [(7, 512, 3), (14, 256, 2), (28, 128, 1)])
+def test_conv_chain_resnet_pair_shapes(hw, ch, batch):
+    # the paper's second conv workload: ResNet-38's pairs of 3x3 convolutions (images of 7x7 pixels are
+    # smaller than a row tile, so one tile spans several images and its halo crosses image boundaries)
+    print(f"resnet pair {hw}x{hw}x{ch} batch {batch}", flush=True)
+    t = inputs.conv(batch, hw, hw, ch, ch, ch, seed=71)
+    mid_ref, out_ref = _oracle(t)
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    res = [run_conv_chain(t["x"], t["w1"], t["w2"], pol, mode) for mode in MODES]
+    for mid, out in res:
+        assert mid_err(mid, mid_ref) <= TOL_MID
+        assert rel_err(out, out_ref) <= TOL_BF16
+        assert torch.equal(mid, res[0][0]) and torch.equal(out, res[0][1])
+    pol.destroy()
