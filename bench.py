@@ -37,7 +37,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--rounds", type=int, default=3, help="interleaved timing blocks per variant (comparison table)")
     ap.add_argument("--m", type=int, default=2048, help="tokens (rows of X)")
-    ap.add_argument("--workload", default="gpt3_mlp", choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "cfg1", "vgg_conv"])
+    ap.add_argument("--workload", default="gpt3_mlp",
+                    choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "cfg1", "vgg_conv", "vgg_layer", "resnet_conv"])
     ap.add_argument("--hw", type=int, default=56, help="vgg_conv: image height = width")
     ap.add_argument("--channels", type=int, default=256, help="vgg_conv: channels of all three tensors")
     ap.add_argument("--batch", type=int, default=16, help="vgg_conv: images")
@@ -61,8 +62,9 @@ def parse():
                          "synchronisation): one full wave of tiles at several tile sizes, every launch mode; writes a "
                          "markdown table and prints one JSON line for the 64 KiB tile")
     ap.add_argument("--sweep", default=None, metavar="FILE", help="run all configurations, write a markdown table")
-    ap.add_argument("--sweep-set", default="paper", choices=["paper", "resnet"],
-                    help="rows of --sweep: the five configurations of the headline table, or ResNet-38's conv pairs")
+    ap.add_argument("--sweep-set", default="paper", choices=["paper", "resnet", "vgg_layers"],
+                    help="rows of --sweep: the five configurations of the headline table, ResNet-38's conv pairs, or "
+                         "VGG-19's layer groups of four convolutions")
     ap.add_argument("--ablation", default=None, metavar="FILE",
                     help="time the chosen workload with the optimisations of Section IV-C switched off one at a time")
     return ap.parse_args()
@@ -88,8 +90,19 @@ class Workload:
     def __init__(self, torch, ds, inputs, kind, M=2048, hw=56, channels=256, batch=16, w_layout="rows"):
         self.kind, self.M = kind, M
         self.conv = kind in ("vgg_conv", "resnet_conv")
+        self.convn = kind == "vgg_layer"
         self.attn = None
         self.ds = ds
+        if self.convn:
+            # one VGG-19 layer group: four 3x3 convolutions of equal width, ReLU between them (Section V)
+            layers = [inputs.conv(batch, hw, hw, channels, channels, 64, seed=i) for i in range(4)]
+            self.t = layers
+            self.x = layers[0]["x"].cuda()
+            self.ws = [l["w1"].cuda() for l in layers]
+            self.outs = [torch.empty((batch, hw, hw, channels), dtype=self.x.dtype, device="cuda") for _ in range(4)]
+            self.name = f"VGG layer of four convs {hw}x{hw}x{channels}, ReLU between, batch {batch}, 3x3 s1 p1, NHWC bf16"
+            self.policies = ["strided", "row", "tile"]
+            return
         if self.conv:
             t = inputs.conv(batch, hw, hw, channels, channels, channels)
             self.t = t
@@ -135,12 +148,16 @@ class Workload:
 
     def plan(self, pol, tile=0):
         ds = self.ds
+        if self.convn:
+            return ds.conv_chain_n_plan(self.x, self.ws, self.outs, pol, tile=tile)
         if self.conv:
             return ds.conv_chain_plan(self.x, self.w1, self.mid_t, self.w2, self.out, pol, tile=tile)
         return ds.gemm_chain_plan(self.X, self.W1t, self.H, self.W2t, self.Y, pol, mid=self.mid, tile=tile, **self.extra)
 
     def autotune(self, pol, sp):
         ds = self.ds
+        if self.convn:
+            return ds.conv_chain_n_autotune(self.x, self.ws, self.outs, pol, stream=sp, reps=3)
         if self.conv:
             return ds.conv_chain_autotune(self.x, self.w1, self.mid_t, self.w2, self.out, pol, stream=sp, reps=3)
         return ds.gemm_chain_autotune(self.X, self.W1t, self.H, self.W2t, self.Y, pol, mid=self.mid, stream=sp,
@@ -148,7 +165,11 @@ class Workload:
 
     def caller(self, pol, mode, tile, sp, sc):
         ds = self.ds
-        if self.conv:
+        if self.convn:
+            def call():
+                ds.dep_conv_chain_n(self.x, self.ws, self.outs, pol, mode=mode, tile=tile,
+                                    stream_producer=sp, stream_consumer=sc)
+        elif self.conv:
             def call():
                 ds.dep_conv_chain(self.x, self.w1, self.mid_t, self.w2, self.out, pol, mode=mode, tile=tile,
                                   stream_producer=sp, stream_consumer=sc)
@@ -163,6 +184,13 @@ class Workload:
         import inputs
         import oracle
         t = self.t
+        if self.convn:
+            B = t[0]["x"].shape[0]
+            xs = inputs.to_f64(t[0]["x"][:1])
+            wf = [inputs.to_f64(l["w1"]) for l in t]
+            t0 = time.perf_counter()
+            oracle.conv_chain_n(xs, wf)
+            return time.perf_counter() - t0, 1.0 / B, f"fp64 oracle timed on the first of {B} images (images are independent)"
         if self.conv:
             B = t["x"].shape[0]
             xs = inputs.to_f64(t["x"][:1])
@@ -265,6 +293,9 @@ def sweep(args, torch, ds, inputs):
         # the paper's second conv workload (Fig. 7): ResNet-38's pairs of 3x3 convolutions, 56x56x64 ... 7x7x512
         cases = [("resnet_conv", dict(hw=hw, channels=ch, batch=b))
                  for hw, ch in ((56, 64), (28, 128), (14, 256), (7, 512)) for b in (1, 8, 32)]
+    elif args.sweep_set == "vgg_layers":
+        # chains of four convolutions: VGG-19's layer groups at 256 and 512 channels (Section V)
+        cases = [("vgg_layer", dict(hw=hw, channels=ch, batch=b)) for hw, ch in ((56, 256), (28, 512), (14, 512)) for b in (1, 16)]
     else:
         cases = [("cfg1", dict())]
         cases += [("gpt3_mlp", dict(M=m)) for m in inputs.CFG2["Ms"]]

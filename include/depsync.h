@@ -229,6 +229,26 @@ typedef struct {
     int32_t tile_prod, tile_cons;
 } depsync_conv_chain_desc;
 
+/*
+ * Chain of n = 2..4 such convolutions with ReLU between them and none after the last, as in the
+ * layers of VGG (Section V, the chains of more than two convolutions): conv i reads the output
+ * of conv i-1 (conv 0 reads `in`) and each later stage waits on the one before it as the
+ * policy says.  K[i] = output channels of conv i; C and K[i] for i < n-1 multiples of 64, K[n-1]
+ * a multiple of 8.  w[i]: [K[i],3,3,Cin_i]; out[i]: [B,H,W,K[i]], out[n-1] the result, the
+ * others intermediates (caller's buffers, 128-byte aligned, written then read).  Entries of K, w
+ * and out beyond n are ignored.  n = 2 is the same computation as depsync_conv_chain_desc.
+ */
+typedef struct {
+    int32_t B, H, W, C;
+    int32_t n;
+    int32_t K[4];
+    int32_t dtype;
+    const void* in;
+    const void* w[4];
+    void* out[4];
+    int32_t tile_prod, tile_cons;   /* one macro-tile for every stage: equal, or 0 = library's choice */
+} depsync_conv_chain_n_desc;
+
 /* ---- policy objects (CuStage + policy of Fig. 4; init of Section III-D) ------------- */
 
 /* Create a policy and its workspace on the current device.  params may be NULL.          */
@@ -256,6 +276,10 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
 /* Enqueue the Conv2D chain.  Section IV-B.                                                */
 int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync_mode mode,
                    void* stream_producer, void* stream_consumer);
+/* Enqueue a chain of 2..4 convolutions (same conventions; two-stream mode uses one stream per
+ * stage, the library's own for the third and fourth).  DEPSYNC_EINVAL for n outside 2..4.    */
+int dep_conv_chain_n(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, depsync_mode mode,
+                     void* stream_producer, void* stream_consumer);
 /* Dry run: validate the descriptor and report tiles, grids, wave counts, flops and bytes
  * without touching the device workspace.  n_cu <= 0 reads the CU count from the current
  * device (which then must exist).                                                          */
@@ -263,6 +287,10 @@ int depsync_gemm_chain_plan(const depsync_gemm_chain_desc* d, const sync_policy_
                             int n_cu, depsync_plan_info* out);
 int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_t* pol,
                             int n_cu, depsync_plan_info* out);
+/* For chains of more than three stages n_mid counts the tiles of all middle stages and the
+ * middle grid is that of the second stage.                                                  */
+int depsync_conv_chain_n_plan(const depsync_conv_chain_n_desc* d, const sync_policy_t* pol,
+                              int n_cu, depsync_plan_info* out);
 
 /* Tile selection by measurement (the role of the paper's policy/order search of Section IV-A,
  * narrowed to the macro-tile shape and the split along K): runs the chain in one-dispatch mode
@@ -277,6 +305,8 @@ int depsync_gemm_chain_autotune(const depsync_gemm_chain_desc* d, sync_policy_t*
                                 int reps, int* tile_out);
 int depsync_conv_chain_autotune(const depsync_conv_chain_desc* d, sync_policy_t* pol, void* stream,
                                 int reps, int* tile_out);
+int depsync_conv_chain_n_autotune(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, void* stream,
+                                  int reps, int* tile_out);
 
 /* The remembered choice for this chain shape, element type and policy kind, read or set without
  * measuring (to carry a tuning result from one process to the next).  `tile` is a DEPSYNC_TILE_*

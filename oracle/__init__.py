@@ -192,3 +192,15 @@ def copy_chain(src):
     for i in range(0, mid.size, 1 << 20):
         dst[i:i + (1 << 20)] = mid[i:i + (1 << 20)]
     return mid, dst
+
+
+def conv_chain_n(x, ws):
+    """Chain of len(ws) 3x3 convolutions (stride 1, zero padding 1), ReLU after every one but the
+    last (the layers of VGG, Section V).  Returns the list of every convolution's output, the
+    intermediates after their ReLU."""
+    outs = []
+    cur = _f64(x)
+    for i, w in enumerate(ws):
+        cur = conv2d_nhwc(cur, w, ACT_NONE if i == len(ws) - 1 else ACT_RELU)
+        outs.append(cur)
+    return outs

@@ -33,6 +33,7 @@ EXPORTS = [
     "depsync_tile_shape", "depsync_device_info", "depsync_gemm_chain_autotune", "depsync_conv_chain_autotune",
     "depsync_gemm_chain_tuned", "depsync_conv_chain_tuned", "depsync_gemm_chain_set_tuned", "depsync_conv_chain_set_tuned",
     "depsync_mfma_calibration", "dep_copy_chain", "depsync_copy_chain_plan",
+    "dep_conv_chain_n", "depsync_conv_chain_n_plan", "depsync_conv_chain_n_autotune",
 ]
 
 
@@ -98,6 +99,13 @@ class ConvChainDesc(ctypes.Structure):
                 ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32)]
 
 
+class ConvChainNDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32), ("C", ctypes.c_int32),
+                ("n", ctypes.c_int32), ("K", ctypes.c_int32 * 4), ("dtype", ctypes.c_int32),
+                ("inp", ctypes.c_void_p), ("w", ctypes.c_void_p * 4), ("out", ctypes.c_void_p * 4),
+                ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32)]
+
+
 class CopyChainDesc(ctypes.Structure):
     _fields_ = [("src", ctypes.c_void_p), ("mid", ctypes.c_void_p), ("dst", ctypes.c_void_p),
                 ("bytes", ctypes.c_uint64), ("tile_bytes", ctypes.c_uint32)]
@@ -126,6 +134,9 @@ def _lib() -> ctypes.CDLL:
         L.depsync_conv_chain_plan.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
         L.depsync_gemm_chain_autotune.argtypes = [ctypes.POINTER(GemmChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
         L.depsync_conv_chain_autotune.argtypes = [ctypes.POINTER(ConvChainDesc), vp, vp, i32, ctypes.POINTER(i32)]
+        L.dep_conv_chain_n.argtypes = [ctypes.POINTER(ConvChainNDesc), vp, i32, vp, vp]
+        L.depsync_conv_chain_n_plan.argtypes = [ctypes.POINTER(ConvChainNDesc), vp, i32, ctypes.POINTER(PlanInfo)]
+        L.depsync_conv_chain_n_autotune.argtypes = [ctypes.POINTER(ConvChainNDesc), vp, vp, i32, ctypes.POINTER(i32)]
         L.dep_copy_chain.argtypes = [ctypes.POINTER(CopyChainDesc), vp, i32, vp, vp]
         L.depsync_copy_chain_plan.argtypes = [ctypes.POINTER(CopyChainDesc), vp, i32, ctypes.POINTER(PlanInfo)]
         L.depsync_mfma_calibration.argtypes = [i32, i32, ctypes.POINTER(ctypes.c_double)]
@@ -377,6 +388,52 @@ def conv_chain_plan(x, w1, mid, w2, out, policy: Optional[SyncPolicy], tile: int
     _check(_lib().depsync_conv_chain_plan(ctypes.byref(d), policy.handle if policy else None, n_cu,
                                           ctypes.byref(info)), "depsync_conv_chain_plan")
     return info
+
+
+def _conv_n_desc(x, ws, outs, tile) -> ConvChainNDesc:
+    n = len(ws)
+    if n != len(outs) or not 2 <= n <= 4:
+        raise ValueError("a conv chain has 2 to 4 convolutions, one output buffer each")
+    for t in [x, *ws, *outs]:
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+    d = ConvChainNDesc()
+    d.B, d.H, d.W, d.C = x.shape
+    d.n = n
+    d.dtype = _dtype_code(x)
+    d.inp = x.data_ptr()
+    cin = d.C
+    for i, (w, o) in enumerate(zip(ws, outs)):
+        if tuple(w.shape[1:]) != (3, 3, cin) or tuple(o.shape) != (d.B, d.H, d.W, w.shape[0]) or w.dtype != x.dtype or o.dtype != x.dtype:
+            raise ValueError(f"conv {i}: weights [K,3,3,{cin}] and output [B,H,W,K] of the input's type expected")
+        d.K[i], d.w[i], d.out[i] = w.shape[0], w.data_ptr(), o.data_ptr()
+        cin = w.shape[0]
+    d.tile_prod = d.tile_cons = tile
+    return d
+
+
+def dep_conv_chain_n(x, ws, outs, policy: SyncPolicy, mode: int = MODE_FINE, tile: int = TILE_AUTO,
+                     stream_producer=None, stream_consumer=None) -> None:
+    """Enqueue 2..4 chained 3x3 convolutions, ReLU between them: outs[i] = conv(relu-ed outs[i-1], ws[i])."""
+    d = _conv_n_desc(x, ws, outs, tile)
+    _check(_lib().dep_conv_chain_n(ctypes.byref(d), policy.handle, mode, _stream_handle(stream_producer),
+                                   _stream_handle(stream_consumer)), "dep_conv_chain_n")
+
+
+def conv_chain_n_plan(x, ws, outs, policy: Optional[SyncPolicy], tile: int = TILE_AUTO, n_cu: int = 0) -> PlanInfo:
+    d = _conv_n_desc(x, ws, outs, tile)
+    info = PlanInfo()
+    _check(_lib().depsync_conv_chain_n_plan(ctypes.byref(d), policy.handle if policy else None, n_cu,
+                                            ctypes.byref(info)), "depsync_conv_chain_n_plan")
+    return info
+
+
+def conv_chain_n_autotune(x, ws, outs, policy: SyncPolicy, stream=None, reps: int = 3) -> int:
+    d = _conv_n_desc(x, ws, outs, TILE_AUTO)
+    tile = ctypes.c_int(0)
+    _check(_lib().depsync_conv_chain_n_autotune(ctypes.byref(d), policy.handle, _stream_handle(stream), reps,
+                                                ctypes.byref(tile)), "depsync_conv_chain_n_autotune")
+    return tile.value
 
 
 def _copy_desc(src, mid, dst, tile_bytes: int) -> CopyChainDesc:

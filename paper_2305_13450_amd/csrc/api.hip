@@ -22,11 +22,12 @@ namespace {
 thread_local int g_last_hip_error = 0;
 
 // Workspace layout in 32-bit words.
-constexpr uint32_t WS_TICKET = 0;        // 3 stages x 8 dispatch counters, one per 128-byte line
-constexpr uint32_t WS_TICKET_WORDS = 24 * SYNC_WORD_STRIDE;
+constexpr uint32_t WS_TICKET = 0;        // 4 stages x 8 dispatch counters, one per 128-byte line
+constexpr uint32_t WS_TICKET_WORDS = 32 * SYNC_WORD_STRIDE;
 constexpr uint32_t WS_STATUS = WS_TICKET_WORDS;          // StatusBlock, 8 words
 constexpr uint32_t WS_ZERO_PAGE = WS_STATUS + 64;        // 64 words = 256 zero bytes (never written after init)
-constexpr uint32_t WS_SEMS = 1024;                       // one semaphore per 128-byte line
+constexpr uint32_t WS_SEMS = 2048;                       // one semaphore per 128-byte line
+static_assert(WS_ZERO_PAGE + 64 <= WS_SEMS && WS_SEMS % SYNC_WORD_STRIDE == 0, "counters, status and zero page end before the semaphores");
 constexpr uint32_t WS_MAX_SEMS = 1u << 16;
 constexpr uint32_t WS_SEM_WORDS = WS_MAX_SEMS * SYNC_WORD_STRIDE;
 constexpr uint32_t WS_TRACE = WS_SEMS + WS_SEM_WORDS;     // TraceRec[WS_TRACE_CAP], 12 words each
@@ -53,8 +54,9 @@ struct sync_policy {
     int device;
     uint32_t* ws;
     hipStream_t own_stream;    // second stream when the caller gives none
-    hipStream_t third_stream;  // third stage of a three-stage chain in FINE mode
-    hipEvent_t ev_fork, ev_join, ev_join3;
+    hipStream_t third_stream;  // third stage of a chain in FINE mode
+    hipStream_t fourth_stream; // fourth stage
+    hipEvent_t ev_fork, ev_join, ev_join3, ev_join4;
     // epoch state: semaphores and the dispatch counter only ever grow between resets
     uint64_t geom_sig;
     uint32_t epoch;
@@ -70,18 +72,18 @@ struct sync_policy {
 namespace {
 
 struct Plan {
-    int tile[3];
+    int tile[4];
     int n_stages;
-    uint32_t grid_x[3], grid_y[3], n_tiles[3];
-    uint32_t dep_kind[3];      // dependency of stage s on stage s-1
-    uint32_t sem_off[3];       // offset of that dependency's semaphores inside the sem area
-    uint32_t sem_count[3];
-    uint32_t sem_value[3];
-    uint32_t stride[3];
-    uint32_t out_tm[3], out_tn[3];   // rows / columns of its own output one tile of stage s covers
-    uint32_t ksplit[3];              // workgroups per output tile (split along K)
-    uint32_t arrive_off[3];          // first arrival counter of the stage
-    size_t partial_off[3];           // first float of the stage's partial tiles
+    uint32_t grid_x[4], grid_y[4], n_tiles[4];
+    uint32_t dep_kind[4];      // dependency of stage s on stage s-1
+    uint32_t sem_off[4];       // offset of that dependency's semaphores inside the sem area
+    uint32_t sem_count[4];
+    uint32_t sem_value[4];
+    uint32_t stride[4];
+    uint32_t out_tm[4], out_tn[4];   // rows / columns of its own output one tile of stage s covers
+    uint32_t ksplit[4];              // workgroups per output tile (split along K)
+    uint32_t arrive_off[4];          // first arrival counter of the stage
+    size_t partial_off[4];           // first float of the stage's partial tiles
     size_t partial_floats;           // scratch the chain needs
     uint32_t n_sems;
     int slots;
@@ -124,17 +126,21 @@ double tile_cost_factor(int tile) {
 // changes what overlaps).  Looked up before the model below when the caller leaves the tile
 // to the library.
 struct TuneKey {
-    int64_t v[10];
-    bool operator<(const TuneKey& o) const { return std::lexicographical_compare(v, v + 10, o.v, o.v + 10); }
+    int64_t v[12];
+    bool operator<(const TuneKey& o) const { return std::lexicographical_compare(v, v + 12, o.v, o.v + 12); }
 };
 std::map<TuneKey, int> g_tuned;
 std::mutex g_tuned_mutex;
 
 TuneKey tune_key(const depsync_gemm_chain_desc* d, const sync_policy* pol) {
-    return TuneKey{{d->w_layout ? 2 : 0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq}};
+    return TuneKey{{d->w_layout ? 2 : 0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq, 0, 0}};
 }
 TuneKey tune_key(const depsync_conv_chain_desc* d, const sync_policy* pol) {
-    return TuneKey{{1, d->B, d->H, d->W, d->C, d->K1, d->K2, d->dtype, pol ? pol->kind : -1, 0}};
+    return TuneKey{{1, d->B, d->H, d->W, d->C, d->K1, d->K2, d->dtype, pol ? pol->kind : -1, 0, 0, 0}};
+}
+TuneKey tune_key(const depsync_conv_chain_n_desc* d, const sync_policy* pol) {
+    if (d->n == 2) return TuneKey{{1, d->B, d->H, d->W, d->C, d->K[0], d->K[1], d->dtype, pol ? pol->kind : -1, 0, 0, 0}};
+    return TuneKey{{3, d->B, d->H, d->W, d->C, d->K[0], d->K[1], d->dtype, pol ? pol->kind : -1, d->n, d->K[2], d->n > 3 ? d->K[3] : 0}};
 }
 int tuned_tile(const TuneKey& k) {
     std::lock_guard<std::mutex> g(g_tuned_mutex);
@@ -340,21 +346,40 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     return DEPSYNC_OK;
 }
 
-int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu, Plan& p) {
+// The two-convolution descriptor as a chain of n = 2.
+depsync_conv_chain_n_desc as_chain_n(const depsync_conv_chain_desc& d) {
+    depsync_conv_chain_n_desc c;
+    std::memset(&c, 0, sizeof(c));
+    c.B = d.B; c.H = d.H; c.W = d.W; c.C = d.C; c.n = 2;
+    c.K[0] = d.K1; c.K[1] = d.K2;
+    c.dtype = d.dtype;
+    c.in = d.in; c.w[0] = d.w1; c.w[1] = d.w2; c.out[0] = d.mid; c.out[1] = d.out;
+    c.tile_prod = d.tile_prod; c.tile_cons = d.tile_cons;
+    return c;
+}
+
+// Chain of n = 2..4 3x3 convolutions: stage i is conv i, each later stage depends on the one
+// before it in the way the policy says (per halo row tile, per filter row, or per filter row
+// and channel tile).
+int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int n_cu, Plan& p) {
     if (!d) return DEPSYNC_EINVAL;
-    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0 || d->K1 <= 0 || d->K2 <= 0) return DEPSYNC_EINVAL;
+    if (d->n < 2 || d->n > 4) return DEPSYNC_EINVAL;
+    if (d->B <= 0 || d->H <= 0 || d->W <= 0 || d->C <= 0) return DEPSYNC_EINVAL;
     if (d->dtype != DEPSYNC_BF16 && d->dtype != DEPSYNC_FP16) return DEPSYNC_EINVAL;
-    if (!d->in || !d->w1 || !d->mid || !d->w2 || !d->out) return DEPSYNC_EINVAL;
-    if (!aligned16(d->in) || !aligned16(d->w1) || !aligned16(d->mid) || !aligned16(d->w2) || !aligned16(d->out))
-        return DEPSYNC_EINVAL;
-    if (reinterpret_cast<uintptr_t>(d->mid) & 127u) return DEPSYNC_EINVAL;   // whole cache lines per pixel
-    if (d->C % 64 || d->K1 % 64 || d->K2 % 8) return DEPSYNC_EINVAL;
+    if (!d->in || !aligned16(d->in) || d->C % 64) return DEPSYNC_EINVAL;
     if (d->H >= 32768 || d->W >= 32768) return DEPSYNC_EINVAL;
     const uint64_t Mpix = (uint64_t)d->B * d->H * d->W;
     const uint64_t lim = 1ull << 32;
-    const uint64_t cmax = (uint64_t)std::max(std::max(d->C, d->K1), d->K2);
-    if (Mpix * cmax * 2 >= lim || 9ull * d->C * d->K1 * 2 >= lim || 9ull * d->K1 * d->K2 * 2 >= lim)
-        return DEPSYNC_EINVAL;
+    const int n = d->n;
+    int cin[4];                                            // input channels of conv i
+    for (int i = 0; i < n; ++i) {
+        cin[i] = i == 0 ? d->C : d->K[i - 1];
+        if (d->K[i] <= 0 || !d->w[i] || !d->out[i] || !aligned16(d->w[i]) || !aligned16(d->out[i])) return DEPSYNC_EINVAL;
+        const bool last = i == n - 1;
+        if (last ? d->K[i] % 8 : d->K[i] % 64) return DEPSYNC_EINVAL;
+        if (!last && (reinterpret_cast<uintptr_t>(d->out[i]) & 127u)) return DEPSYNC_EINVAL;   // whole cache lines per pixel
+        if (Mpix * (uint64_t)std::max(cin[i], d->K[i]) * 2 >= lim || 9ull * cin[i] * d->K[i] * 2 >= lim) return DEPSYNC_EINVAL;
+    }
     if (d->tile_prod < 0 || d->tile_prod >= DEPSYNC_TILE__COUNT || d->tile_cons < 0 ||
         d->tile_cons >= DEPSYNC_TILE__COUNT)
         return DEPSYNC_EINVAL;
@@ -366,49 +391,64 @@ int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu
     bool tuned_off = false, tuned_hw = false;
     if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
     if (!tile) {
-        // halo: a consumer row tile reads W+1 rows beyond each end
-        tile = choose_tile(M, d->K1, 9 * d->C, d->K2, 9 * d->K1, false, cus, 1);
+        // halo: a consumer row tile reads W+1 rows beyond each end (modelled on the first two stages)
+        tile = choose_tile(M, d->K[0], 9 * d->C, d->K[1], 9 * d->K[0], false, cus, 1);
     }
     const TileShape* ts = tile_shape(tile);
     if (!ts) return DEPSYNC_EINVAL;
 
     std::memset(&p, 0, sizeof(p));
-    p.n_stages = 2;
+    p.n_stages = n;
     p.amode = A_CONV3X3;
     p.dtype = d->dtype;
     p.tuned_hw_order = tuned_hw;
-    p.tile[0] = p.tile[1] = tile;
-    p.grid_y[0] = p.grid_y[1] = cdiv(M, ts->rows);
-    p.grid_x[0] = cdiv(d->K1, ts->cols);
-    p.grid_x[1] = cdiv(d->K2, ts->cols);
-    p.out_tm[0] = ts->rows; p.out_tn[0] = ts->cols;
-    for (int s = 0; s < 2; ++s) { p.n_tiles[s] = p.grid_x[s] * p.grid_y[s]; p.ksplit[s] = 1; }
     const int kind = pol ? pol->kind : DEPSYNC_STRIDEDSYNC;
-    p.dep_kind[1] = policy_dep_kind_conv(kind);
-    if (p.dep_kind[1] == DEP_CONV_TILE) {
-        if (ts->cols % 64) return DEPSYNC_EINVAL;
-        p.sem_count[1] = p.n_tiles[0];
-        p.sem_value[1] = 1;
-    } else {
-        p.sem_count[1] = p.grid_y[0];
-        p.sem_value[1] = p.grid_x[0];
-    }
-    p.n_sems = p.sem_count[1];
-    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
+    for (int s = 0; s < n; ++s) {
+        p.tile[s] = tile;
+        p.grid_y[s] = cdiv(M, ts->rows);
+        p.grid_x[s] = cdiv(d->K[s], ts->cols);
+        p.out_tm[s] = ts->rows; p.out_tn[s] = ts->cols;
+        p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
+        p.ksplit[s] = 1;
+    }
+    for (int s = 1; s < n; ++s) {
+        p.dep_kind[s] = policy_dep_kind_conv(kind);
+        p.sem_off[s] = p.n_sems;
+        if (p.dep_kind[s] == DEP_CONV_TILE) {
+            if (ts->cols % 64) return DEPSYNC_EINVAL;
+            p.sem_count[s] = p.n_tiles[s - 1];
+            p.sem_value[s] = 1;
+        } else {
+            p.sem_count[s] = p.grid_y[s - 1];
+            p.sem_value[s] = p.grid_x[s - 1];
+        }
+        p.n_sems += p.sem_count[s];
+    }
+    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.slots, 9u * d->C / 64, 1);
-    {
+    for (int s = 1; s < n; ++s) {
         uint32_t seg = 1;                                   // CONV_ROW: the whole halo is waited for by every part
         // per filter row or per (filter row, channel tile): the wait at a filter row's first tap
         // also covers its other two taps, so parts must be whole filter rows
-        if (p.dep_kind[1] != DEP_CONV_ROW) seg = 3u * d->K1 / 64;
-        p.ksplit[1] = choose_split(pol, tuned_off, p.n_tiles[1], p.slots, 9u * d->K1 / 64, seg);
+        if (p.dep_kind[s] != DEP_CONV_ROW) seg = 3u * cin[s] / 64;
+        p.ksplit[s] = choose_split(pol, tuned_off, p.n_tiles[s], p.slots, 9u * cin[s] / 64, seg);
     }
     if (int rc = finish_split(p); rc != DEPSYNC_OK) return rc;
     const double Md = (double)M;
-    p.flops = 2.0 * Md * d->K1 * 9.0 * d->C + 2.0 * Md * d->K2 * 9.0 * d->K1;
-    p.bytes = 2.0 * (Md * d->C + 9.0 * d->C * d->K1 + 2.0 * Md * d->K1 + 9.0 * d->K1 * d->K2 + Md * d->K2);
+    p.flops = 0.0;
+    p.bytes = 2.0 * Md * d->C;                              // the input once
+    for (int i = 0; i < n; ++i) {
+        p.flops += 2.0 * Md * d->K[i] * 9.0 * cin[i];
+        p.bytes += 2.0 * (9.0 * cin[i] * d->K[i] + (i == n - 1 ? 1.0 : 2.0) * Md * d->K[i]);   // weights; output written (and read)
+    }
     return DEPSYNC_OK;
+}
+
+int plan_conv(const depsync_conv_chain_desc* d, const sync_policy* pol, int n_cu, Plan& p) {
+    if (!d) return DEPSYNC_EINVAL;
+    const depsync_conv_chain_n_desc c = as_chain_n(*d);
+    return plan_conv_n(&c, pol, n_cu, p);
 }
 
 // Copy chain: two stages of ceil(bytes / tile_bytes) tiles, one row of tiles each.
@@ -451,12 +491,15 @@ void fill_plan_info(const Plan& p, depsync_plan_info* o) {
     std::memset(o, 0, sizeof(*o));
     o->tile_prod = p.tile[0];
     o->tile_cons = p.tile[p.n_stages - 1];
-    o->tile_mid = p.n_stages == 3 ? p.tile[1] : 0;
+    o->tile_mid = p.n_stages >= 3 ? p.tile[1] : 0;
     o->prod_grid_x = p.grid_x[0]; o->prod_grid_y = p.grid_y[0];
     o->cons_grid_x = p.grid_x[p.n_stages - 1]; o->cons_grid_y = p.grid_y[p.n_stages - 1];
     o->n_prod = p.n_tiles[0];
     o->n_cons = p.n_tiles[p.n_stages - 1];
-    if (p.n_stages == 3) { o->mid_grid_x = p.grid_x[1]; o->mid_grid_y = p.grid_y[1]; o->n_mid = p.n_tiles[1]; }
+    if (p.n_stages >= 3) {   // four stages: the grid of the second, the tiles of both middle stages
+        o->mid_grid_x = p.grid_x[1]; o->mid_grid_y = p.grid_y[1];
+        for (int s = 1; s + 1 < p.n_stages; ++s) o->n_mid += p.n_tiles[s];
+    }
     o->n_sems = p.n_sems;
     o->slots = p.slots;
     uint32_t total = 0;
@@ -517,7 +560,7 @@ int ensure_scratch(sync_policy* pol, const Plan& p) {
 void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) {
     a.n_stages = p.n_stages;
     uint32_t t = 0;
-    for (int s = 0; s < 4; ++s) {
+    for (int s = 0; s < 5; ++s) {
         a.first_ticket[s] = t;
         if (s < p.n_stages) t += p.n_tiles[s];
     }
@@ -596,12 +639,13 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
             HIP_TRY(hipEventRecord(pol->ev_fork, sp));
             HIP_TRY(hipStreamWaitEvent(sc, pol->ev_fork, 0));
             if (p.n_stages > 2) HIP_TRY(hipStreamWaitEvent(pol->third_stream, pol->ev_fork, 0));
+            if (p.n_stages > 3) HIP_TRY(hipStreamWaitEvent(pol->fourth_stream, pol->ev_fork, 0));
         }
         uint32_t off = 0;
         for (int s = 0; s < p.n_stages; ++s) {
             // producer on the caller's stream; later stages on the second stream in FINE mode
             // (one stream per stage: launches on one stream would run one after the other)
-            hipStream_t st = mode != DEPSYNC_MODE_FINE || s == 0 ? sp : s == 1 ? sc : pol->third_stream;
+            hipStream_t st = mode != DEPSYNC_MODE_FINE || s == 0 ? sp : s == 1 ? sc : s == 2 ? pol->third_stream : pol->fourth_stream;
             a.block_offset = off;
             // a launch works on its own stage and, when launches overlap (FINE), first helps
             // with whatever earlier stages have not been handed out yet
@@ -616,6 +660,10 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
             if (p.n_stages > 2) {
                 HIP_TRY(hipEventRecord(pol->ev_join3, pol->third_stream));
                 HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join3, 0));
+            }
+            if (p.n_stages > 3) {
+                HIP_TRY(hipEventRecord(pol->ev_join4, pol->fourth_stream));
+                HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join4, 0));
             }
         }
     }
@@ -651,6 +699,8 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->own_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->third_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join3, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->fourth_stream, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join4, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming);
     if (e != hipSuccess) { (void)hipFree(p->ws); delete p; return hip_fail(e); }
@@ -673,6 +723,8 @@ int sync_policy_destroy(sync_policy_t* pol) {
     (void)hipEventDestroy(pol->ev_fork);
     (void)hipEventDestroy(pol->ev_join);
     (void)hipEventDestroy(pol->ev_join3);
+    (void)hipEventDestroy(pol->ev_join4);
+    (void)hipStreamDestroy(pol->fourth_stream);
     (void)hipStreamDestroy(pol->own_stream);
     (void)hipStreamDestroy(pol->third_stream);
     (void)hipFree(pol->ws);
@@ -789,14 +841,14 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
 }
 
-int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
-                   void* stream_consumer) {
+int dep_conv_chain_n(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
+                     void* stream_consumer) {
     if (!pol) return DEPSYNC_EINVAL;
     if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN &&
         mode != DEPSYNC_MODE_FUSED)
         return DEPSYNC_EINVAL;
     Plan p;
-    int rc = plan_conv(d, pol, 0, p);
+    int rc = plan_conv_n(d, pol, 0, p);
     if (rc != DEPSYNC_OK) return rc;
     uint32_t epoch = 0;
     if (mode != DEPSYNC_MODE_PLAIN) {
@@ -806,23 +858,36 @@ int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync
     ChainArgs a;
     std::memset(&a, 0, sizeof(a));
     const uint32_t M = (uint32_t)d->B * d->H * d->W;
-    StageDesc& s0 = a.st[0];
-    s0.A = d->in; s0.B = d->w1; s0.C = d->mid;
-    s0.M = M; s0.N = d->K1; s0.K = 9u * d->C;
-    s0.lda = d->C; s0.ldb = 9u * d->C; s0.ldc = d->K1;
-    s0.b_row_bytes = 18u * d->C; s0.b_kstep_bytes = 128u;
-    s0.op = OP_GEMM; s0.amode = A_CONV3X3; s0.bmode = B_DENSE; s0.act = ACT_RELU;
-    s0.H = d->H; s0.W = d->W; s0.Cin = d->C;
-    StageDesc& s1 = a.st[1];
-    s1.A = d->mid; s1.B = d->w2; s1.C = d->out;
-    s1.M = M; s1.N = d->K2; s1.K = 9u * d->K1;
-    s1.lda = d->K1; s1.ldb = 9u * d->K1; s1.ldc = d->K2;
-    s1.b_row_bytes = 18u * d->K1; s1.b_kstep_bytes = 128u;
-    s1.op = OP_GEMM; s1.amode = A_CONV3X3; s1.bmode = B_DENSE; s1.act = ACT_NONE;
-    s1.H = d->H; s1.W = d->W; s1.Cin = d->K1;
+    for (int i = 0; i < d->n; ++i) {
+        const uint32_t cin = i == 0 ? (uint32_t)d->C : (uint32_t)d->K[i - 1];
+        StageDesc& st = a.st[i];
+        st.A = i == 0 ? d->in : d->out[i - 1]; st.B = d->w[i]; st.C = d->out[i];
+        st.M = M; st.N = d->K[i]; st.K = 9u * cin;
+        st.lda = cin; st.ldb = 9u * cin; st.ldc = d->K[i];
+        st.b_row_bytes = 18u * cin; st.b_kstep_bytes = 128u;
+        st.op = OP_GEMM; st.amode = A_CONV3X3; st.bmode = B_DENSE;
+        st.act = i == d->n - 1 ? ACT_NONE : ACT_RELU;
+        st.H = d->H; st.W = d->W; st.Cin = cin;
+    }
     if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
     fill_common(a, pol, p, epoch);
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
+}
+
+int dep_conv_chain(const depsync_conv_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
+                   void* stream_consumer) {
+    if (!d) return DEPSYNC_EINVAL;
+    const depsync_conv_chain_n_desc c = as_chain_n(*d);
+    return dep_conv_chain_n(&c, pol, mode, stream_producer, stream_consumer);
+}
+
+int depsync_conv_chain_n_plan(const depsync_conv_chain_n_desc* d, const sync_policy_t* pol, int n_cu, depsync_plan_info* out) {
+    if (!out) return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_conv_n(d, pol, n_cu, p);
+    if (rc != DEPSYNC_OK) return rc;
+    fill_plan_info(p, out);
+    return DEPSYNC_OK;
 }
 
 int depsync_copy_chain_plan(const depsync_copy_chain_desc* d, const sync_policy_t* pol, int n_cu, depsync_plan_info* out) {
@@ -953,6 +1018,13 @@ int depsync_gemm_chain_autotune(const depsync_gemm_chain_desc* d, sync_policy_t*
                                 int* tile_out) {
     return autotune(d, pol, static_cast<hipStream_t>(stream), reps, tile_out, [&](const depsync_gemm_chain_desc* dd) {
         return dep_gemm_chain(dd, pol, DEPSYNC_MODE_FUSED, stream, nullptr);
+    });
+}
+
+int depsync_conv_chain_n_autotune(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, void* stream, int reps,
+                                  int* tile_out) {
+    return autotune(d, pol, static_cast<hipStream_t>(stream), reps, tile_out, [&](const depsync_conv_chain_n_desc* dd) {
+        return dep_conv_chain_n(dd, pol, DEPSYNC_MODE_FUSED, stream, nullptr);
     });
 }
 

@@ -1,5 +1,5 @@
 // Plain-data kernel arguments shared by the host launcher and the device code of the chain
-// kernels.  A chain has up to three stages (producer, optional middle stage, consumer); each
+// kernels.  A chain has up to four stages (producer, optional middle stages, consumer); each
 // stage after the first has one dependency on the stage before it (Section III-A).
 #pragma once
 #include <stdint.h>
@@ -93,10 +93,10 @@ struct TraceRec {
 constexpr uint32_t SYNC_WORD_STRIDE = 32;   // in 32-bit words
 
 struct ChainArgs {
-    StageDesc st[3];
+    StageDesc st[4];
     uint32_t n_stages;
-    uint32_t first_ticket[4];   // stage s owns tickets [first_ticket[s], first_ticket[s+1])
-    uint32_t* ticket;           // dispatch counters: [stage][XCD queue], 3 x 8
+    uint32_t first_ticket[5];   // stage s owns tickets [first_ticket[s], first_ticket[s+1])
+    uint32_t* ticket;           // dispatch counters: [stage][XCD queue], 4 x 8
     uint32_t epoch;             // chains run on this workspace since its last reset
     uint32_t queue_epoch;       // those of them that drew their tiles from the dispatch queues
     uint32_t block_offset;      // HW order / PLAIN: ticket of this launch's block 0

@@ -184,6 +184,7 @@ __device__ __forceinline__ TileId hw_order_tile(const ChainArgs& a) {
     uint32_t stage = 0;
     if (a.n_stages > 1 && rel >= a.first_ticket[1]) stage = 1;
     if (a.n_stages > 2 && rel >= a.first_ticket[2]) stage = 2;
+    if (a.n_stages > 3 && rel >= a.first_ticket[3]) stage = 3;
     const uint32_t lin = rel - a.first_ticket[stage], gx = a.st[stage].grid_x;
     t.stage = stage; t.tx = lin % gx; t.ty = lin / gx; t.rel = rel;
     return t;

@@ -182,3 +182,81 @@ def test_conv_chain_resnet_pair_shapes(hw, ch, batch):
         assert rel_err(out, out_ref) <= TOL_BF16
         assert torch.equal(mid, res[0][0]) and torch.equal(out, res[0][1])
     pol.destroy()
+
+
+def _run_conv_n(x, ws, pol, mode, tile=ds.TILE_AUTO):
+    xd = x.cuda()
+    wd = [w.cuda() for w in ws]
+    B, H, W, _ = x.shape
+    outs = [torch.full((B, H, W, w.shape[0]), float("nan"), dtype=x.dtype, device="cuda") for w in ws]
+    torch.cuda.synchronize()
+    ds.dep_conv_chain_n(xd, wd, outs, pol, mode=mode, tile=tile)
+    torch.cuda.synchronize()
+    return outs
+
+
+def _conv_n_inputs(B, H, W, chans, seed):
+    # He-normal weights as in inputs.conv, one more layer at a time from the same recipe
+    ws = []
+    x = None
+    for i in range(len(chans) - 1):
+        t = inputs.conv(B, H, W, chans[i], chans[i + 1], 64, seed=seed + i)
+        if x is None:
+            x = t["x"]
+        ws.append(t["w1"])
+    return x, ws
+
+
+@pytest.mark.parametrize("kind", KINDS)
+@pytest.mark.parametrize("chans,tile", [((64, 128, 64, 128), ds.TILE_64x64), ((64, 64, 128, 64, 64), ds.TILE_128x128),
+                                        ((128, 64, 64, 192), ds.TILE_AUTO)])
+def test_conv_chain_of_three_and_four_convolutions(kind, chans, tile):
+    # VGG-style layers: every stage is checked against the oracle applied to the stage's OWN input as
+    # the GPU produced it (one convolution's error: the 2e-2 bar), the whole chain against the
+    # oracle end to end (n - 1 roundings of intermediates compound: 2e-2 * sqrt(n - 1)), and the
+    # launch modes against each other bit for bit
+    print(f"conv chain n={len(chans) - 1} kind={kind} tile={tile}", flush=True)
+    x, ws = _conv_n_inputs(3, 13, 11, chans, seed=80)
+    n = len(ws)
+    ref = oracle.conv_chain_n(inputs.to_f64(x), [inputs.to_f64(w) for w in ws])
+    pol = ds.SyncPolicy(kind)
+    res = [_run_conv_n(x, ws, pol, mode, tile) for mode in MODES]
+    outs = res[0]
+    for other in res[1:]:
+        for a, b in zip(outs, other):
+            assert torch.equal(a, b)
+    for i in range(n):
+        prev = inputs.to_f64(x) if i == 0 else outs[i - 1].cpu().double().numpy()
+        stage_ref = oracle.conv2d_nhwc(prev, inputs.to_f64(ws[i]), oracle.ACT_NONE if i == n - 1 else oracle.ACT_RELU)
+        if i == n - 1:
+            assert rel_err(outs[i], stage_ref) <= TOL_BF16, i
+        else:
+            assert mid_err(outs[i], stage_ref) <= TOL_MID, i
+    assert rel_err(outs[-1], ref[-1]) <= TOL_BF16 * (n - 1) ** 0.5
+    assert pol.status().timed_out == 0
+    pol.destroy()
+
+
+def test_conv_chain_n_delayed_middle_stage_and_bad_arguments():
+    x, ws = _conv_n_inputs(1, 28, 28, (64, 64, 64, 64, 64), seed=90)
+    base = ds.SyncPolicy(ds.STRIDEDSYNC)
+    ref = _run_conv_n(x, ws, base, ds.MODE_STREAMSYNC, ds.TILE_64x64)
+    base.destroy()
+    for delay_tile in (1, 7, 13):
+        pol = ds.SyncPolicy(ds.STRIDEDSYNC, delay_tile=delay_tile, delay_iters=200)
+        for mode in (ds.MODE_FINE, ds.MODE_FUSED):
+            outs = _run_conv_n(x, ws, pol, mode, ds.TILE_64x64)
+            assert all(torch.equal(a, b) for a, b in zip(outs, ref)), (delay_tile, mode)
+        pol.destroy()
+    pol = ds.SyncPolicy(ds.STRIDEDSYNC)
+    xd, wd = x.cuda(), [w.cuda() for w in ws]
+    outs = [torch.empty((1, 28, 28, 64), dtype=x.dtype, device="cuda") for _ in ws]
+    with pytest.raises(ValueError):
+        ds.dep_conv_chain_n(xd, wd + wd[:1], outs + outs[:1], pol)        # five convolutions
+    d = ds._conv_n_desc(xd, wd, outs, ds.TILE_AUTO)
+    d.n = 5
+    assert ds._lib().dep_conv_chain_n(d, pol.handle, ds.MODE_FINE, None, None) == ds.EINVAL
+    d.n = 4
+    d.K[1] = 72                                                          # an intermediate that is not a multiple of 64
+    assert ds._lib().dep_conv_chain_n(d, pol.handle, ds.MODE_FINE, None, None) == ds.EINVAL
+    pol.destroy()

@@ -308,3 +308,25 @@ def test_copy_chain_is_the_identity_on_bytes():
     f = np.array([1.5, -2.25], dtype=np.float32)
     mid, dst = oracle.copy_chain(f)
     assert dst.view(np.float32).tolist() == [1.5, -2.25]
+
+
+def test_conv_chain_n_composes_the_pinned_convolution():
+    # two convolutions: the same as the (separately pinned) conv_chain; three: hand-checkable
+    # identity filters (centre tap 1 on the diagonal) pass a non-negative image through unchanged,
+    # and a negating filter in the middle is clipped to zero by the ReLU that follows it
+    rng = np.random.default_rng(5)
+    x = rng.standard_normal((2, 5, 4, 3))
+    w1, w2 = rng.standard_normal((4, 3, 3, 3)), rng.standard_normal((2, 3, 3, 4))
+    mid, out = oracle.conv_chain(x, w1, w2)
+    o = oracle.conv_chain_n(x, [w1, w2])
+    assert np.array_equal(o[0], mid) and np.array_equal(o[1], out)
+    ident = np.zeros((3, 3, 3, 3))
+    for c in range(3):
+        ident[c, 1, 1, c] = 1.0
+    xp = np.abs(x)
+    o = oracle.conv_chain_n(xp, [ident, ident, ident])
+    assert all(np.array_equal(t, xp) for t in o)
+    o = oracle.conv_chain_n(xp, [ident, -ident, ident])
+    assert np.array_equal(o[0], xp) and not o[1].any() and not o[2].any()      # relu(-x) = 0 for x >= 0
+    o = oracle.conv_chain_n(xp, [ident, ident, -ident])
+    assert np.array_equal(o[2], -xp)                                            # no ReLU after the last
