@@ -26,7 +26,7 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
 MEASURED_TRAFFIC_BYTES = {
     ("gpt3_mlp", 2048, "fused"): (1178589 + 80732) * 1024,
     ("gpt3_attn", 2048, "fused"): (1429047 + 102886) * 1024,
-    ("vgg_conv", 2048, "fused"): (348715 + 55168) * 1024,     # 56x56x256, batch 16 (the default conv shape)
+    ("vgg_conv", 50176, "fused"): (348715 + 55168) * 1024,    # 56x56x256, batch 16 (the default conv shape)
 }
 
 
@@ -38,7 +38,8 @@ def parse():
     ap.add_argument("--rounds", type=int, default=3, help="interleaved timing blocks per variant (comparison table)")
     ap.add_argument("--m", type=int, default=2048, help="tokens (rows of X)")
     ap.add_argument("--workload", default="gpt3_mlp",
-                    choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "cfg1", "vgg_conv", "vgg_layer", "resnet_conv"])
+                    choices=["gpt3_mlp", "llama_mlp", "gpt3_attn", "gpt3_attn_gen", "cfg1", "vgg_conv", "vgg_layer", "resnet_conv"])
+    ap.add_argument("--cached", type=int, default=2048, help="gpt3_attn_gen: cached tokens per sequence")
     ap.add_argument("--hw", type=int, default=56, help="vgg_conv: image height = width")
     ap.add_argument("--channels", type=int, default=256, help="vgg_conv: channels of all three tensors")
     ap.add_argument("--batch", type=int, default=16, help="vgg_conv: images")
@@ -62,7 +63,7 @@ def parse():
                          "synchronisation): one full wave of tiles at several tile sizes, every launch mode; writes a "
                          "markdown table and prints one JSON line for the 64 KiB tile")
     ap.add_argument("--sweep", default=None, metavar="FILE", help="run all configurations, write a markdown table")
-    ap.add_argument("--sweep-set", default="paper", choices=["paper", "resnet", "vgg_layers"],
+    ap.add_argument("--sweep-set", default="paper", choices=["paper", "resnet", "vgg_layers", "generation"],
                     help="rows of --sweep: the five configurations of the headline table, ResNet-38's conv pairs, or "
                          "VGG-19's layer groups of four convolutions")
     ap.add_argument("--ablation", default=None, metavar="FILE",
@@ -87,10 +88,12 @@ def time_block(torch, call, sp, steps):
 class Workload:
     """Device buffers of one chain plus closures to plan, tune and launch it."""
 
-    def __init__(self, torch, ds, inputs, kind, M=2048, hw=56, channels=256, batch=16, w_layout="rows"):
+    def __init__(self, torch, ds, inputs, kind, M=2048, hw=56, channels=256, batch=16, w_layout="rows", cached=2048):
         self.kind, self.M = kind, M
         self.conv = kind in ("vgg_conv", "resnet_conv")
         self.convn = kind == "vgg_layer"
+        if self.conv or self.convn:
+            self.M = batch * hw * hw          # rows of the implicit GeMM
         self.attn = None
         self.ds = ds
         if self.convn:
@@ -119,6 +122,18 @@ class Workload:
         elif kind == "llama_mlp":
             t = inputs.swiglu(M=M, K1=8192, Nh=2752, N2=8192); self.mid = ds.MID_SWIGLU; W1 = t["Wgu"]
             self.name = f"LLaMA-65B MLP shard X[{M}x8192] [Wg|Wu][8192x5504] SwiGLU W2[2752x8192] bf16"
+        elif kind == "gpt3_attn_gen":
+            # token generation (Fig. 2b): one new token per sequence over `cached` earlier ones
+            c = inputs.CFG4; self.mid = ds.MID_CAUSAL_ATTN
+            nb = batch if batch <= 8 else 4
+            self.M = M = nb
+            t = inputs.attention(M, c["K1"], c["heads"], c["d"], c["N2"])
+            W1 = t["Wqkv"]; t["W2"] = t["Wo"]
+            self.kv = inputs.kv_cache(nb, cached, c["heads"], c["d"])
+            self.attn = dict(batch=nb, seq=1, heads=c["heads"], head_dim=c["d"])
+            self.cache = dict(k_cache=self.kv["Kc"].cuda(), v_cache=self.kv["Vc"].cuda())
+            self.name = (f"GPT-3 attention shard, token generation: X[{M}x12288] Wqkv[12288x4608] attention 12 heads x 128 "
+                         f"over {cached} cached tokens (batch {nb}, 1 new token each) Wo[1536x12288] bf16")
         elif kind == "gpt3_attn":
             c = inputs.CFG4; self.mid = ds.MID_CAUSAL_ATTN
             t = inputs.attention(M, c["K1"], c["heads"], c["d"], c["N2"])
@@ -144,6 +159,7 @@ class Workload:
         if self.attn:
             self.extra = dict(self.attn, T=torch.empty((M, self.attn["heads"] * self.attn["head_dim"]),
                                                        dtype=self.X.dtype, device="cuda"))
+            self.extra.update(getattr(self, "cache", {}))
         self.policies = ["row", "tile", "strided"] if self.attn else ["row", "tile"]
 
     def plan(self, pol, tile=0):
@@ -202,7 +218,11 @@ class Workload:
         Xs = inputs.to_f64(t["X"][:rows])
         W1f, W2f = inputs.to_f64(self.W1), inputs.to_f64(t["W2"])
         t0 = time.perf_counter()
-        if self.attn:
+        if self.attn and hasattr(self, "kv"):
+            rows = self.M
+            oracle.attn_chain_cached(inputs.to_f64(t["X"]), W1f, W2f, inputs.to_f64(self.kv["Kc"]), inputs.to_f64(self.kv["Vc"]),
+                                     self.attn["batch"], 1, self.attn["heads"], self.attn["head_dim"])
+        elif self.attn:
             # causal: the first `rows` tokens of the sequence need nothing from later tokens
             oracle.attn_chain(Xs, W1f, W2f, 1, rows, self.attn["heads"], self.attn["head_dim"])
         elif self.mid == self.ds.MID_SWIGLU:
@@ -293,6 +313,9 @@ def sweep(args, torch, ds, inputs):
         # the paper's second conv workload (Fig. 7): ResNet-38's pairs of 3x3 convolutions, 56x56x64 ... 7x7x512
         cases = [("resnet_conv", dict(hw=hw, channels=ch, batch=b))
                  for hw, ch in ((56, 64), (28, 128), (14, 256), (7, 512)) for b in (1, 8, 32)]
+    elif args.sweep_set == "generation":
+        # token generation with cached keys and values: S = 1, S' in {512, 2048}, B in {1, 4} (Section V)
+        cases = [("gpt3_attn_gen", dict(batch=b, cached=c)) for b in (1, 4) for c in (512, 2048)]
     elif args.sweep_set == "vgg_layers":
         # chains of four convolutions: VGG-19's layer groups at 256 and 512 channels (Section V)
         cases = [("vgg_layer", dict(hw=hw, channels=ch, batch=b)) for hw, ch in ((56, 256), (28, 512), (14, 512)) for b in (1, 16)]
@@ -478,7 +501,7 @@ def main():
         return sync_overhead(args, torch, ds, n_cu)
 
     wl = Workload(torch, ds, inputs, args.workload, M=args.m, hw=args.hw, channels=args.channels, batch=args.batch,
-                  w_layout=args.w_layout)
+                  w_layout=args.w_layout, cached=args.cached)
     M = wl.M
 
     if args.copy_calibration:

@@ -207,9 +207,18 @@ typedef struct {
     const void* W2t; int64_t ldw2;  /* [N2 x K2]                                             */
     void* Y;         int64_t ldy;   /* [M x N2]                                              */
     void* T;         int64_t ldt;   /* CAUSAL_ATTN only: [M x heads*head_dim]                */
-    int32_t batch, seq, heads, head_dim; /* CAUSAL_ATTN only                                 */
+    int32_t batch, seq, heads, head_dim; /* CAUSAL_ATTN only; batch > 1 needs seq % 128 == 0 or seq < 128 */
     int32_t tile_prod, tile_cons;   /* depsync_tile; 0 = chosen by the library               */
     int32_t w_layout;               /* depsync_w_layout of W1t and W2t                       */
+    /* CAUSAL_ATTN, token generation (Fig. 2b, cached keys and values): `cached` earlier tokens
+     * per sequence whose keys and values are read from k_cache / v_cache, [batch][cached] rows of
+     * ld_cache elements (>= heads*head_dim, multiple of 8), head h in columns h*head_dim..;
+     * device, 16-byte aligned, read only.  New token i of a sequence attends to all cached
+     * tokens and to new tokens 0..i.  cached = 0: prompt phase, the pointers are ignored.      */
+    const void* k_cache;
+    const void* v_cache;
+    int64_t ld_cache;
+    int32_t cached;
 } depsync_gemm_chain_desc;
 
 /*

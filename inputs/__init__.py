@@ -66,6 +66,14 @@ def attention(M: int, K1: int, heads: int, d: int, N2: int, seed: int = 0, dtype
     }
 
 
+def kv_cache(batch: int, cached: int, heads: int, d: int, seed: int = 0, dtype=torch.bfloat16) -> Dict[str, torch.Tensor]:
+    """Keys and values of `cached` earlier tokens per sequence, [batch, cached, heads*d], N(0,1) like the
+    K and V columns the QKV GeMM produces from N(0,1) activations and N(0,1/K) weights."""
+    g = _gen(seed + 1000)
+    E = heads * d
+    return {"Kc": _normal(g, (batch, cached, E), 1.0, dtype), "Vc": _normal(g, (batch, cached, E), 1.0, dtype)}
+
+
 def conv(B: int, H: int, W: int, C: int, K1: int, K2: int, seed: int = 0, dtype=torch.bfloat16) -> Dict[str, torch.Tensor]:
     """x[B,H,W,C] (NHWC), w1[K1,3,3,C], w2[K2,3,3,K1]."""
     g = _gen(seed)

@@ -204,3 +204,36 @@ def conv_chain_n(x, ws):
         cur = conv2d_nhwc(cur, w, ACT_NONE if i == len(ws) - 1 else ACT_RELU)
         outs.append(cur)
     return outs
+
+
+def cached_attention(QKV, Kc, Vc, batch: int, seq: int, heads: int, d: int):
+    """Attention of `seq` new tokens per sequence over `cached` earlier tokens and themselves (Fig. 2b,
+    token generation with cached keys and values): new token i of a sequence sees every cached token and
+    new tokens 0..i.  QKV[batch*seq x 3*heads*d] (Q | K | V), Kc / Vc[batch x cached x heads*d].
+    Written out from the definition, one (sequence, head, query) at a time."""
+    QKV, Kc, Vc = _f64(QKV), _f64(Kc), _f64(Vc)
+    E = heads * d
+    cached = Kc.shape[1]
+    assert QKV.shape == (batch * seq, 3 * E) and Kc.shape == (batch, cached, E) and Vc.shape == Kc.shape
+    T = np.zeros((batch * seq, E))
+    for b in range(batch):
+        rows = slice(b * seq, (b + 1) * seq)
+        for h in range(heads):
+            cols = slice(h * d, (h + 1) * d)
+            q = QKV[rows, h * d:(h + 1) * d]
+            k = np.concatenate([Kc[b][:, cols], QKV[rows, E + h * d:E + (h + 1) * d]], axis=0)
+            v = np.concatenate([Vc[b][:, cols], QKV[rows, 2 * E + h * d:2 * E + (h + 1) * d]], axis=0)
+            for i in range(seq):
+                n = cached + i + 1                       # keys this query sees
+                sc = (k[:n] @ q[i]) / np.sqrt(float(d))
+                sc = sc - sc.max()
+                w = np.exp(sc)
+                T[b * seq + i, cols] = (w / w.sum()) @ v[:n]
+    return T
+
+
+def attn_chain_cached(X, Wqkv, Wo, Kc, Vc, batch: int, seq: int, heads: int, d: int):
+    """(QKV, T, Y) of the attention block with cached keys and values: QKV = X Wqkv, T as above, Y = T Wo."""
+    QKV = gemm(X, Wqkv)
+    T = cached_attention(QKV, Kc, Vc, batch, seq, heads, d)
+    return QKV, T, gemm(T, Wo)

@@ -88,7 +88,9 @@ class GemmChainDesc(ctypes.Structure):
                 ("T", ctypes.c_void_p), ("ldt", ctypes.c_int64),
                 ("batch", ctypes.c_int32), ("seq", ctypes.c_int32), ("heads", ctypes.c_int32),
                 ("head_dim", ctypes.c_int32),
-                ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32), ("w_layout", ctypes.c_int32)]
+                ("tile_prod", ctypes.c_int32), ("tile_cons", ctypes.c_int32), ("w_layout", ctypes.c_int32),
+                ("k_cache", ctypes.c_void_p), ("v_cache", ctypes.c_void_p), ("ld_cache", ctypes.c_int64),
+                ("cached", ctypes.c_int32)]
 
 
 class ConvChainDesc(ctypes.Structure):
@@ -261,7 +263,8 @@ def _dev_w(t, name: str):
     return ptr, ld, t.shape[0], t.shape[1], False
 
 
-def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, head_dim=0) -> GemmChainDesc:
+def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, head_dim=0,
+               k_cache=None, v_cache=None) -> GemmChainDesc:
     d = GemmChainDesc()
     d.X, d.ldx = _dev2d(X, "X")
     d.W1t, d.ldw1, w1n, w1k, b1 = _dev_w(W1t, "W1t")
@@ -282,6 +285,17 @@ def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, he
     if T is not None:
         d.T, d.ldt = _dev2d(T, "T")
     d.batch, d.seq, d.heads, d.head_dim = batch, seq, heads, head_dim
+    if k_cache is not None or v_cache is not None:
+        # [batch, cached, heads*head_dim] device tensors of earlier tokens' keys and values
+        for t, name in ((k_cache, "k_cache"), (v_cache, "v_cache")):
+            if t is None or not t.is_cuda or t.dim() != 3 or t.stride(2) != 1 or t.dtype != X.dtype:
+                raise ValueError(f"{name} must be a 3-D device tensor of the chain's element type")
+            if t.shape[0] != batch or t.stride(0) != t.shape[1] * t.stride(1):
+                raise ValueError(f"{name}: one block of rows per sequence, equally spaced")
+        if k_cache.shape != v_cache.shape or k_cache.stride() != v_cache.stride():
+            raise ValueError("k_cache and v_cache must have the same shape and strides")
+        d.k_cache, d.v_cache = k_cache.data_ptr(), v_cache.data_ptr()
+        d.ld_cache, d.cached = k_cache.stride(1), k_cache.shape[1]
     d.tile_prod = d.tile_cons = tile
     rows1 = 2 * d.N1 if mid == MID_SWIGLU else d.N1
     k2 = heads * head_dim if mid == MID_CAUSAL_ATTN else d.N1
@@ -292,9 +306,10 @@ def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, he
 
 def dep_gemm_chain(X, W1t, H, W2t, Y, policy: SyncPolicy, mode: int = MODE_FINE, mid: int = MID_GELU,
                    tile: int = TILE_AUTO, stream_producer=None, stream_consumer=None, T=None,
-                   batch: int = 0, seq: int = 0, heads: int = 0, head_dim: int = 0) -> None:
+                   batch: int = 0, seq: int = 0, heads: int = 0, head_dim: int = 0,
+                   k_cache=None, v_cache=None) -> None:
     """Enqueue Y = mid(X W1) W2 with W1t = W1^T [N1 x K1] and W2t = W2^T [N2 x K2] (row-major)."""
-    d = _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T, batch, seq, heads, head_dim)
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T, batch, seq, heads, head_dim, k_cache, v_cache)
     _check(_lib().dep_gemm_chain(ctypes.byref(d), policy.handle, mode, _stream_handle(stream_producer),
                                  _stream_handle(stream_consumer)), "dep_gemm_chain")
 

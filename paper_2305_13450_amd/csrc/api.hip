@@ -133,7 +133,7 @@ std::map<TuneKey, int> g_tuned;
 std::mutex g_tuned_mutex;
 
 TuneKey tune_key(const depsync_gemm_chain_desc* d, const sync_policy* pol) {
-    return TuneKey{{d->w_layout ? 2 : 0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq, 0, 0}};
+    return TuneKey{{d->w_layout ? 2 : 0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq, d->cached, 0}};
 }
 TuneKey tune_key(const depsync_conv_chain_desc* d, const sync_policy* pol) {
     return TuneKey{{1, d->B, d->H, d->W, d->C, d->K1, d->K2, d->dtype, pol ? pol->kind : -1, 0, 0, 0}};
@@ -239,7 +239,14 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
         if (d->batch <= 0 || d->seq <= 0 || d->heads <= 0) return DEPSYNC_EINVAL;
         if ((int64_t)d->batch * d->seq != d->M || (int64_t)d->N1 != 3ll * E) return DEPSYNC_EINVAL;
         if (!d->T || (reinterpret_cast<uintptr_t>(d->T) & 127u) || d->ldt < (int64_t)E || d->ldt % 64) return DEPSYNC_EINVAL;
-        if (d->batch > 1 && d->seq % 128) return DEPSYNC_ENOTIMPL;   // query blocks must not straddle sequences
+        // query blocks must not straddle sequences: whole blocks of 128, or one short block each
+        if (d->batch > 1 && d->seq % 128 && d->seq > 128) return DEPSYNC_ENOTIMPL;
+        if (d->cached < 0) return DEPSYNC_EINVAL;
+        if (d->cached > 0) {
+            if (!d->k_cache || !d->v_cache || !aligned16(d->k_cache) || !aligned16(d->v_cache)) return DEPSYNC_EINVAL;
+            if (d->ld_cache < (int64_t)E || d->ld_cache % 8) return DEPSYNC_EINVAL;
+            if ((uint64_t)d->batch * (uint64_t)d->cached * (uint64_t)d->ld_cache * 2 >= (1ull << 32)) return DEPSYNC_EINVAL;
+        }
     }
     const uint32_t K2 = attn ? E : (uint32_t)d->N1;
     if (d->K1 % 64 || K2 % 64) return DEPSYNC_EINVAL;
@@ -286,7 +293,8 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     if (attn) {   // middle stage: one tile per (head, block of 128 query rows)
         p.grid_x[1] = d->heads;
         p.grid_y[1] = (uint32_t)d->batch * cdiv(d->seq, 128);
-        p.out_tm[1] = 128; p.out_tn[1] = 128;
+        p.out_tm[1] = (d->batch > 1 && d->seq < 128) ? (uint32_t)d->seq : 128u;   // rows one attention tile covers
+        p.out_tn[1] = 128;
     }
     for (int s = 0; s < p.n_stages; ++s) { p.n_tiles[s] = p.grid_x[s] * p.grid_y[s]; p.ksplit[s] = 1; }
 
@@ -340,8 +348,10 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     p.flops = 2.0 * M * w1c * d->K1 + 2.0 * M * d->N2 * K2;
     p.bytes = 2.0 * (M * d->K1 + w1c * d->K1 + 2.0 * M * d->N1 + (double)d->N2 * K2 + M * d->N2);
     if (attn) {   // causal: each of Q K^T and P V does seq*(seq+1)/2 * d multiply-adds per head and sequence
-        p.flops += 2.0 * 2.0 * d->batch * d->heads * 128.0 * 0.5 * (double)d->seq * ((double)d->seq + 1.0);
+        p.flops += 2.0 * 2.0 * d->batch * d->heads * 128.0 *
+                   (0.5 * (double)d->seq * ((double)d->seq + 1.0) + (double)d->seq * (double)d->cached);
         p.bytes += 2.0 * 2.0 * M * E;   // T written and read once
+        p.bytes += 2.0 * 2.0 * (double)d->batch * (double)d->cached * E;   // cached keys and values read once
     }
     return DEPSYNC_OK;
 }
@@ -828,6 +838,8 @@ int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync
         sa.lda = (uint32_t)d->ldh; sa.ldc = (uint32_t)d->ldt;
         sa.op = OP_ATTN; sa.amode = A_DENSE; sa.bmode = B_DENSE; sa.act = ACT_NONE;
         sa.batch = d->batch; sa.seq = d->seq; sa.heads = d->heads; sa.head_dim = 128;
+        sa.kcache = d->cached > 0 ? d->k_cache : nullptr; sa.vcache = d->cached > 0 ? d->v_cache : nullptr;
+        sa.cached = (uint32_t)d->cached; sa.ld_cache = (uint32_t)d->ld_cache;
     }
     StageDesc& s1 = a.st[attn ? 2 : 1];
     s1.A = attn ? d->T : d->H; s1.B = d->W2t; s1.C = d->Y;

@@ -83,6 +83,10 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     const uint32_t q_last = min(q0 + ATT_BQ, seq) - 1;
     const T* QKV = (const T*)uni_ptr(s.A);
     T* Tout = (T*)uni_ptr(s.C);
+    // cached keys and values of this sequence come first in key order (token generation)
+    const uint32_t cached = uni(s.cached), ldkv = uni(s.ld_cache);
+    const T* Kc = (const T*)uni_ptr(s.kcache);
+    const T* Vc = (const T*)uni_ptr(s.vcache);
 
     WaitCtx wctx{&args, rel_ticket, true};
     const bool tracing = SYNC && (args.flags & DS_FLAG_TRACE) && args.trace != nullptr && rel_ticket < args.trace_cap;
@@ -113,7 +117,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     // While block kb is used, the K and V rows of block kb+1 are DMA'd into LDS (no registers
     // held); V is transposed LDS to LDS at the top of the next iteration.
     const uint32_t wave_q_last = min(q0 + wave * 32 + 31, seq - 1);
-    const uint32_t nblk = q_last / ATT_BK + 1;                    // key blocks the tile touches
+    const uint32_t nblk = (cached + q_last) / ATT_BK + 1;         // key blocks the tile touches
     char* const ldsVraw = lds + 2 * ATT_BLK_BYTES;
     char* const ldsV = lds + 3 * ATT_BLK_BYTES;
     auto fetch = [&](uint32_t kb) __attribute__((always_inline)) {
@@ -122,10 +126,18 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
 #pragma unroll
         for (int i = 0; i < 4; ++i) {                             // 4 x 16 bytes per lane for K, and for V
             const uint32_t idx = i * 256 + tid, row = idx >> 4, slot = idx & 15u, chunk = slot ^ (row & 15u);
-            const uint32_t krow = seq_row0 + min(k0 + row, seq - 1);
-            const char* g = (const char*)(QKV + (size_t)krow * ld + E + head * ATT_D);
-            dma16(g + chunk * 16, ldsKn + (i * 256 + wave * 64) * 16);
-            dma16(g + E * 2 + chunk * 16, ldsVraw + (i * 256 + wave * 64) * 16);   // V rows, same swizzle
+            const uint32_t key = k0 + row;                        // position in key order: cache first
+            const char *gk, *gv;
+            if (key < cached) {
+                const size_t r = ((size_t)b * cached + key) * ldkv + head * ATT_D;
+                gk = (const char*)(Kc + r); gv = (const char*)(Vc + r);
+            } else {
+                const uint32_t krow = seq_row0 + min(key - cached, seq - 1);
+                gk = (const char*)(QKV + (size_t)krow * ld + E + head * ATT_D);
+                gv = gk + E * 2;
+            }
+            dma16(gk + chunk * 16, ldsKn + (i * 256 + wave * 64) * 16);
+            dma16(gv + chunk * 16, ldsVraw + (i * 256 + wave * 64) * 16);   // V rows, same swizzle
         }
     };
     fetch(0);
@@ -150,7 +162,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
         __syncthreads();   // V^T complete; the raw V rows and the other K buffer are free again
         if (kb + 1 < nblk) fetch(kb + 1);
 
-        if (k0 <= wave_q_last) {        // blocks entirely above this wave's diagonal contribute nothing
+        if (k0 <= cached + wave_q_last) {   // blocks entirely above this wave's diagonal contribute nothing
             // ---- S^T for the two 32-key halves of the block ----
             f32x16 st[2];
 #pragma unroll
@@ -173,7 +185,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
                 for (int v = 0; v < 16; ++v) {
                     const uint32_t key = k0 + kh * 32 + 8 * (v / 4) + 4 * h2 + (v % 4);
                     float x = st[kh][v] * sc;
-                    if (key > qi || key >= seq) x = -INFINITY;
+                    if (key > cached + qi || key >= cached + seq) x = -INFINITY;
                     st[kh][v] = x;
                     mx = fmaxf(mx, x);
                 }

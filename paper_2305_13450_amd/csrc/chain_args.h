@@ -51,6 +51,11 @@ struct StageDesc {
     const void* zero_page;     // >= 256 zero bytes, source for padded taps
     // attention (OP_ATTN): A = QKV, C = T
     uint32_t batch, seq, heads, head_dim;
+    // keys and values of earlier tokens (token generation, Fig. 2b): [batch][cached] rows of ld_cache
+    // elements, head h in columns h*head_dim..; attended to before the new tokens' own keys
+    const void* kcache;
+    const void* vcache;
+    uint32_t cached, ld_cache;
     // dependency on the previous stage
     uint32_t dep_kind;
     uint32_t* sems;            // semaphores this stage WAITS on (posted by the previous stage)

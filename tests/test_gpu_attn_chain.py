@@ -7,7 +7,7 @@ import torch
 import inputs
 import oracle
 import paper_2305_13450_amd as ds
-from gpu_util import TOL_BF16, TOL_MID, mid_err, rel_err, row_err, run_attn_chain
+from gpu_util import TOL_BF16, TOL_MID, mid_err, rel_err, row_err, run_attn_chain, same
 
 pytestmark = pytest.mark.gpu
 
@@ -169,5 +169,76 @@ def test_invalid_attention_arguments(two_sequences):
         ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, T=T, batch=2, seq=256, heads=4, head_dim=64, **kw)
     with pytest.raises(ds.DepsyncError):      # T missing
         ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, batch=2, seq=256, heads=2, head_dim=128, **kw)
+    torch.cuda.synchronize()
+    pol.destroy()
+
+
+# ---- token generation: cached keys and values (Fig. 2b, S' cached tokens) -------------------------
+
+def _run_cached(t, kv, batch, seq, heads, pol, mode, tile=ds.TILE_AUTO):
+    Xd = t["X"].cuda()
+    Wqkv_t = t["Wqkv"].t().contiguous().cuda()
+    Wo_t = t["Wo"].t().contiguous().cuda()
+    M, E = Xd.shape[0], heads * 128
+    QKV = torch.full((M, 3 * E), float("nan"), dtype=Xd.dtype, device="cuda")
+    T = torch.full((M, E), float("nan"), dtype=Xd.dtype, device="cuda")
+    Y = torch.full((M, t["Wo"].shape[1]), float("nan"), dtype=Xd.dtype, device="cuda")
+    torch.cuda.synchronize()
+    ds.dep_gemm_chain(Xd, Wqkv_t, QKV, Wo_t, Y, pol, mode=mode, mid=ds.MID_CAUSAL_ATTN, tile=tile, T=T,
+                      batch=batch, seq=seq, heads=heads, head_dim=128, k_cache=kv["Kc"].cuda(), v_cache=kv["Vc"].cuda())
+    torch.cuda.synchronize()
+    return QKV, T, Y
+
+
+@pytest.mark.parametrize("kind", [ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC])
+@pytest.mark.parametrize("batch,seq,cached", [
+    (4, 1, 512),      # token generation: one new token per sequence
+    (1, 1, 100),      # a cache that ends inside a key block
+    (3, 1, 1),        # one cached token
+    (1, 200, 77),     # a block of new tokens over a cache (chunked prompt): ragged on both sides
+    (2, 128, 64),     # two sequences, whole query blocks
+    (2, 16, 300),     # two sequences of fewer than 128 new tokens each
+])
+def test_attention_with_cached_keys_and_values(kind, batch, seq, cached):
+    print(f"cached attention kind={kind} batch={batch} seq={seq} cached={cached}", flush=True)
+    heads, K1, N2 = 2, 256, 192
+    t = inputs.attention(batch * seq, K1, heads, 128, N2, seed=21 + cached)
+    kv = inputs.kv_cache(batch, cached, heads, 128, seed=cached)
+    Kc, Vc = inputs.to_f64(kv["Kc"]), inputs.to_f64(kv["Vc"])
+    QKVr, Tr, Yr = oracle.attn_chain_cached(inputs.to_f64(t["X"]), inputs.to_f64(t["Wqkv"]), inputs.to_f64(t["Wo"]),
+                                            Kc, Vc, batch, seq, heads, 128)
+    pol = ds.SyncPolicy(kind)
+    res = [_run_cached(t, kv, batch, seq, heads, pol, mode) for mode in (ds.MODE_FINE, ds.MODE_FUSED, ds.MODE_STREAMSYNC, ds.MODE_PLAIN)]
+    QKV, T, Y = res[0]
+    for other in res[1:]:
+        assert all(same(a, b) for a, b in zip(res[0], other))
+    # stage by stage against the oracle on the stage's own input (2e-2 per row), end to end at 6e-2
+    assert mid_err(QKV, QKVr) <= TOL_MID
+    assert row_err(T, oracle.cached_attention(_f64(QKV), Kc, Vc, batch, seq, heads, 128)) <= TOL_BF16
+    assert row_err(Y, oracle.gemm(_f64(T), inputs.to_f64(t["Wo"]))) <= TOL_BF16
+    assert row_err(T, Tr) <= TOL_BF16_CHAIN3 and row_err(Y, Yr) <= TOL_BF16_CHAIN3
+    assert pol.status().timed_out == 0
+    pol.destroy()
+
+
+def test_cached_attention_rejects_bad_caches():
+    t = inputs.attention(2, 256, 2, 128, 192, seed=5)
+    kv = inputs.kv_cache(2, 64, 2, 128, seed=5)
+    X, Wq, Wo = t["X"].cuda(), t["Wqkv"].t().contiguous().cuda(), t["Wo"].t().contiguous().cuda()
+    QKV = torch.empty((2, 768), dtype=X.dtype, device="cuda")
+    T = torch.empty((2, 256), dtype=X.dtype, device="cuda")
+    Y = torch.empty((2, 192), dtype=X.dtype, device="cuda")
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    kw = dict(mode=ds.MODE_FINE, mid=ds.MID_CAUSAL_ATTN, T=T, batch=2, seq=1, heads=2, head_dim=128)
+    with pytest.raises(ValueError):           # values missing
+        ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, k_cache=kv["Kc"].cuda(), **kw)
+    with pytest.raises(ValueError):           # one cache block per sequence
+        ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, k_cache=kv["Kc"][:1].cuda(), v_cache=kv["Vc"][:1].cuda(), **kw)
+    d = ds._gemm_desc(X, Wq, QKV, Wo, Y, ds.MID_CAUSAL_ATTN, ds.TILE_AUTO, T, 2, 1, 2, 128, kv["Kc"].cuda(), kv["Vc"].cuda())
+    d.ld_cache = 128                          # narrower than heads * head_dim
+    assert ds._lib().dep_gemm_chain(d, pol.handle, ds.MODE_FINE, None, None) == ds.EINVAL
+    d.ld_cache = 256
+    d.v_cache = None
+    assert ds._lib().dep_gemm_chain(d, pol.handle, ds.MODE_FINE, None, None) == ds.EINVAL
     torch.cuda.synchronize()
     pol.destroy()

@@ -330,3 +330,30 @@ def test_conv_chain_n_composes_the_pinned_convolution():
     assert np.array_equal(o[0], xp) and not o[1].any() and not o[2].any()      # relu(-x) = 0 for x >= 0
     o = oracle.conv_chain_n(xp, [ident, ident, -ident])
     assert np.array_equal(o[2], -xp)                                            # no ReLU after the last
+
+
+def test_cached_attention_agrees_with_the_prompt_phase():
+    # (1) no cache: the separately pinned prompt-phase attention; (2) the last token of a prompt of
+    # n+1 tokens is the same as one new token over a cache holding the first n tokens' keys and values
+    # (and the same for a block of new tokens); (3) one cached token and one new one, by hand
+    rng = np.random.default_rng(11)
+    batch, heads, d, n, m = 2, 3, 4, 5, 3
+    E = heads * d
+    full = rng.standard_normal((batch * (n + m), 3 * E))
+    T_full = oracle.causal_attention(full, batch, n + m, heads, d)
+    none = np.zeros((batch, 0, E))
+    assert np.allclose(oracle.cached_attention(full, none, none, batch, n + m, heads, d), T_full, rtol=0, atol=1e-12)
+    seqs = full.reshape(batch, n + m, 3 * E)
+    Kc, Vc = seqs[:, :n, E:2 * E].copy(), seqs[:, :n, 2 * E:].copy()
+    new = seqs[:, n:, :].reshape(batch * m, 3 * E)
+    T_new = oracle.cached_attention(new, Kc, Vc, batch, m, heads, d)
+    want = T_full.reshape(batch, n + m, E)[:, n:, :].reshape(batch * m, E)
+    assert np.allclose(T_new, want, rtol=0, atol=1e-12)
+    # by hand: d = 1, one head; scores q*k = 0 for both keys -> weights 1/2, 1/2 -> mean of the values
+    qkv = np.array([[0.0, 7.0, 4.0]])
+    T = oracle.cached_attention(qkv, np.array([[[3.0]]]), np.array([[[10.0]]]), 1, 1, 1, 1)
+    assert abs(T[0, 0] - 7.0) < 1e-12
+    # and with q = ln 3: scores ln3 * (1, 0) -> weights 3/4, 1/4 (d = 1, no scaling beyond 1/sqrt(1))
+    qkv = np.array([[np.log(3.0), 0.0, 4.0]])
+    T = oracle.cached_attention(qkv, np.array([[[1.0]]]), np.array([[[8.0]]]), 1, 1, 1, 1)
+    assert abs(T[0, 0] - (0.75 * 8.0 + 0.25 * 4.0)) < 1e-12
