@@ -336,8 +336,15 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     p.n_sems = off;
     if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
-    // split along K where a stage is much smaller than the chip (not the attention stage)
+    // split along K where a stage is much smaller than the chip (not the prompt-phase attention stage)
     p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.slots, d->K1 / 64, 1);
+    if (attn && d->seq == 1) {
+        // token generation: the keys of a (head, sequence) pair over up to 8 workgroups, at least 256
+        // keys each, as far as one wave of slots allows
+        uint32_t ks = std::min<uint32_t>(8u, ((uint32_t)d->cached + 1u) / 256u);
+        while (ks > 1 && p.n_tiles[1] * ks > (uint32_t)p.slots) --ks;
+        p.ksplit[1] = std::max<uint32_t>(ks, 1u);
+    }
     {
         const uint32_t dk = p.dep_kind[last];
         const uint32_t seg = (dk == DEP_ROW) ? 1u : p.out_tn[last - 1] / 64;

@@ -9,6 +9,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "chain_args.h"
+#include "attn_decode.hpp"
 #include "attn_tile.hpp"
 #include "gemm_tile.hpp"
 #include "sync_device.hpp"
@@ -20,7 +21,8 @@ __device__ __forceinline__ void run_tile(const ChainArgs& args, const TileId t, 
     const StageDesc& s = args.st[t.stage];
     if constexpr (AMODE == A_DENSE) {
         if (s.op == OP_ATTN) {   // middle stage of the attention chain
-            attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+            if (s.seq == 1) attn_decode_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);   // token generation
+            else attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
             return;
         }
     }
