@@ -90,3 +90,48 @@ def test_vgg_conv_pair(hw, ch, batch):
     ref = oracle.conv_chain_pixels(inputs.to_f64(t["x"]), inputs.to_f64(t["w1"]), inputs.to_f64(t["w2"]), pix)
     got = torch.stack([fine[1][b, y, x] for (b, y, x) in pix])
     assert rel_err(got, ref) <= TOL_BF16
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("batch,cached", [(4, 2048), (1, 512)])
+def test_gpt3_attention_token_generation_full_size(batch, cached, dtype):
+    # the generation phase at the shard's real widths, in the launch configuration bench.py times
+    # (autotuned tile, keys of a (head, sequence) pair split over several workgroups): the oracle
+    # computes the whole chain (a handful of rows), every stage is also checked on its own input
+    from gpu_util import row_err
+    print(f"generation batch={batch} cached={cached} {dtype}", flush=True)
+    c = inputs.CFG4
+    heads, d = c["heads"], c["d"]
+    t = inputs.attention(batch, c["K1"], heads, d, c["N2"], seed=3, dtype=dtype)
+    kv = inputs.kv_cache(batch, cached, heads, d, seed=3, dtype=dtype)
+    Kc, Vc = inputs.to_f64(kv["Kc"]), inputs.to_f64(kv["Vc"])
+    QKVr, Tr, Yr = oracle.attn_chain_cached(inputs.to_f64(t["X"]), inputs.to_f64(t["Wqkv"]), inputs.to_f64(t["Wo"]),
+                                            Kc, Vc, batch, 1, heads, d)
+    X, Wq, Wo = t["X"].cuda(), t["Wqkv"].t().contiguous().cuda(), t["Wo"].t().contiguous().cuda()
+    kc, vc = kv["Kc"].cuda(), kv["Vc"].cuda()
+    E = heads * d
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    kw = dict(mid=ds.MID_CAUSAL_ATTN, batch=batch, seq=1, heads=heads, head_dim=d, k_cache=kc, v_cache=vc)
+    bufs = lambda: (torch.full((batch, 3 * E), float("nan"), dtype=dtype, device="cuda"),
+                    torch.full((batch, E), float("nan"), dtype=dtype, device="cuda"),
+                    torch.full((batch, c["N2"]), float("nan"), dtype=dtype, device="cuda"))
+    QKV, T, Y = bufs()
+    ds.gemm_chain_autotune(X, Wq, QKV, Wo, Y, pol, T=T, reps=2, **kw)
+    res = []
+    for mode in (ds.MODE_FUSED, ds.MODE_FINE, ds.MODE_STREAMSYNC):
+        QKV, T, Y = bufs()
+        torch.cuda.synchronize()
+        ds.dep_gemm_chain(X, Wq, QKV, Wo, Y, pol, mode=mode, T=T, **kw)
+        torch.cuda.synchronize()
+        res.append((QKV, T, Y))
+    for other in res[1:]:
+        assert all(same(a, b) for a, b in zip(res[0], other))
+    QKV, T, Y = res[0]
+    f64 = lambda x: x.cpu().double().numpy()
+    tol, ulp = (TOL_BF16, 2.0 ** -8) if dtype == torch.bfloat16 else (4e-3, 2.0 ** -11)
+    assert mid_err(QKV, QKVr, ulp=ulp) <= TOL_MID
+    assert row_err(T, oracle.cached_attention(f64(QKV), Kc, Vc, batch, 1, heads, d)) <= tol
+    assert row_err(Y, oracle.gemm(f64(T), inputs.to_f64(t["Wo"]))) <= tol
+    assert row_err(T, Tr) <= 3 * tol and row_err(Y, Yr) <= 3 * tol
+    assert pol.status().timed_out == 0
+    pol.destroy()
