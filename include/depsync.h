@@ -100,7 +100,9 @@ typedef enum {
     DEPSYNC_TILE_256x64 = 9,   /* narrow outputs (64 channels)                           */
     DEPSYNC_TILE_64x64_DEEP = 10, /* 64x64 with an 8-stage operand pipeline, one workgroup per
                                   CU: for chains of few tiles that stream weights from HBM */
-    DEPSYNC_TILE__COUNT = 11
+    DEPSYNC_TILE_64x192 = 11,  /* 64 rows, 192 columns, 4-stage pipeline, one workgroup per CU: skinny M on
+                                  widths of the form 3 * 2^k, where it splits into 256 equal parts     */
+    DEPSYNC_TILE__COUNT = 12
 } depsync_tile;
 
 /* Policy flags. */

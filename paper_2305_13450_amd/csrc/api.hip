@@ -118,6 +118,7 @@ double tile_cost_factor(int tile) {
         case DEPSYNC_TILE_128x192: return 1.00;
         case DEPSYNC_TILE_256x64: return 1.3;
         case DEPSYNC_TILE_64x64_DEEP: return 4.0;   // one workgroup per CU: only ever worth it when tiles are few
+        case DEPSYNC_TILE_64x192: return 3.0;       // likewise
         default: return 2.4;
     }
 }

@@ -72,6 +72,7 @@ using Cfg256x192 = TileCfg<256, 192, 2, 2, 1, 2>;   // 112 KB
 using Cfg128x192 = TileCfg<128, 192, 2, 2, 2, 2>;   // 2 x 80 KB
 using Cfg256x64 = TileCfg<256, 64, 4, 1, 2, 2>;     // 2 x 80 KB
 using Cfg64x64Deep = TileCfg<64, 64, 2, 2, 1, 8>;   // 128 KB: seven K steps in flight
+using Cfg64x192 = TileCfg<64, 192, 2, 2, 1, 4>;     // 128 KB: three K steps in flight
 
 template <class Cfg, typename T, uint32_t AMODE>
 static hipError_t launch_cfg(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
@@ -95,6 +96,7 @@ static hipError_t launch_family(int tile, bool sync, uint32_t n_blocks, hipStrea
         case 8: return launch_cfg<Cfg128x192, T, AMODE>(sync, n_blocks, stream, a);
         case 9: return launch_cfg<Cfg256x64, T, AMODE>(sync, n_blocks, stream, a);
         case 10: return launch_cfg<Cfg64x64Deep, T, AMODE>(sync, n_blocks, stream, a);
+        case 11: return launch_cfg<Cfg64x192, T, AMODE>(sync, n_blocks, stream, a);
         default: return hipErrorInvalidValue;
     }
 }

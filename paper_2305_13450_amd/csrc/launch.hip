@@ -87,8 +87,9 @@ const TileShape* tile_shape(int tile) {
         {128, 192, 2, 96},
         {256, 64, 2, 64},
         {64, 64, 1, 32},
+        {64, 192, 1, 96},
     };
-    if (tile < 1 || tile > 10) return nullptr;
+    if (tile < 1 || tile > 11) return nullptr;
     return &shapes[tile];
 }
 
