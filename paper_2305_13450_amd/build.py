@@ -19,6 +19,8 @@ SOURCES = [
     "kern_bf16_conv.hip",
     "kern_f16_conv.hip",
     "kern_copy.hip",
+    "kern_bf16_gen.hip",
+    "kern_f16_gen.hip",
 ]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -2,10 +2,11 @@
 // sequence): one workgroup per (head, sequence).  There is a single query row, so the work is
 // streaming the sequence's cached K and V rows once; the matrix cores have nothing to do here.
 //
-// The four waves split the keys: in every step a wave takes 32 consecutive keys, two lanes
-// per key (each lane owns 64 of the 128 head dimensions, so the pair reads one 256-byte row
-// of K and one of V as two contiguous halves).  Every lane keeps an online softmax of its own
-// keys: running maximum m, sum l and 64 un-normalised output values.  At the end the lanes of
+// The four waves split the keys: in every step a wave takes 16 consecutive keys, four lanes
+// per key (each lane owns 32 of the 128 head dimensions, so the four read one 256-byte row of
+// K and one of V as contiguous quarters; 32 + 32 values of state per lane keep the tile's
+// registers well below those of the GeMM tile it shares a kernel with).  Every lane keeps an
+// online softmax of its own keys: running maximum m, sum l and 32 un-normalised output values.  At the end the lanes of
 // a wave are brought to the wave's maximum and summed through LDS, then the four waves are
 // combined the same way, the result is normalised, rounded and stored.  Key order: the cached
 // tokens, then the new token's own key (which the QKV GeMM has just produced, like the query).
@@ -33,7 +34,7 @@ __device__ __forceinline__ void attn_decode_tile(const ChainArgs& args, const St
     typedef T T8 __attribute__((ext_vector_type(8)));
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = uni(tid >> 6);
-    const uint32_t half = lane & 1u, slot = lane >> 1;           // half of the head dimensions, key slot in the step
+    const uint32_t quarter = lane & 3u, slot = lane >> 2;        // quarter of the head dimensions, key slot in the step
     const uint32_t heads = uni(s.heads), E = heads * ATT_D;
     const uint32_t ld = uni(s.lda), ldt = uni(s.ldc);
     const uint32_t cached = uni(s.cached), ldkv = uni(s.ld_cache);
@@ -52,49 +53,50 @@ __device__ __forceinline__ void attn_decode_tile(const ChainArgs& args, const St
     attn_wait_qkv<SYNC>(wctx, s, head, row, row);
     if (tracing) t_ready = now_ticks();
 
-    // this lane's half of the query, scaled to the base-2 softmax: 64 values
+    // this lane's quarter of the query, scaled to the base-2 softmax: 32 values
     const float sc = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
-    float q[64];
+    float q[32];
     {
-        const T* qp = QKV + (size_t)row * ld + head * ATT_D + half * 64;
+        const T* qp = QKV + (size_t)row * ld + head * ATT_D + quarter * 32;
 #pragma unroll
-        for (int c = 0; c < 8; ++c) {
+        for (int c = 0; c < 4; ++c) {
             const T8 v = *(const T8*)(qp + c * 8);
 #pragma unroll
             for (int e = 0; e < 8; ++e) q[c * 8 + e] = (float)v[e] * sc;
         }
     }
-    float o[64];
+    float o[32];
 #pragma unroll
-    for (int j = 0; j < 64; ++j) o[j] = 0.0f;
+    for (int j = 0; j < 32; ++j) o[j] = 0.0f;
     float m_run = -INFINITY, l_run = 0.0f;
 
     const uint32_t n = cached + 1;                               // keys: the cache, then the new token
-    const uint32_t chunk = ((n + KS - 1) / KS + 127u) & ~127u;   // keys per part, whole steps of 128
+    const uint32_t chunk = ((n + KS - 1) / KS + 63u) & ~63u;     // keys per part, whole steps of 64
     const uint32_t k_begin = ks * chunk, k_end = min(n, k_begin + chunk);
-    for (uint32_t k0 = k_begin + wave * 32; k0 < k_end; k0 += 128) {
+    for (uint32_t k0 = k_begin + wave * 16; k0 < k_end; k0 += 64) {
         const uint32_t key = k0 + slot;
         const bool live = key < k_end;
         const uint32_t kk = live ? key : n - 1;
         const T *kp, *vp;
         if (kk < cached) {
-            const size_t r = ((size_t)b * cached + kk) * ldkv + head * ATT_D + half * 64;
+            const size_t r = ((size_t)b * cached + kk) * ldkv + head * ATT_D + quarter * 32;
             kp = Kc + r; vp = Vc + r;
         } else {
-            kp = QKV + (size_t)row * ld + E + head * ATT_D + half * 64;
+            kp = QKV + (size_t)row * ld + E + head * ATT_D + quarter * 32;
             vp = kp + E;
         }
-        T8 kv[8], vv[8];
+        T8 kv[4], vv[4];
 #pragma unroll
-        for (int c = 0; c < 8; ++c) kv[c] = *(const T8*)(kp + c * 8);
+        for (int c = 0; c < 4; ++c) kv[c] = *(const T8*)(kp + c * 8);
 #pragma unroll
-        for (int c = 0; c < 8; ++c) vv[c] = *(const T8*)(vp + c * 8);
+        for (int c = 0; c < 4; ++c) vv[c] = *(const T8*)(vp + c * 8);
         float dot = 0.0f;
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
+        for (int c = 0; c < 4; ++c)
 #pragma unroll
             for (int e = 0; e < 8; ++e) dot = __builtin_fmaf(q[c * 8 + e], (float)kv[c][e], dot);
-        dot += __shfl_xor(dot, 1);                               // the pair's halves: the whole score, in both lanes
+        dot += __shfl_xor(dot, 1);                               // the four quarters: the whole score, in all four lanes
+        dot += __shfl_xor(dot, 2);
         const float x = live ? dot : -INFINITY;
         const float m_new = fmaxf(m_run, x);
         const float m_use = (m_new == -INFINITY) ? 0.0f : m_new;  // no live key yet: keep the exponentials finite
@@ -103,7 +105,7 @@ __device__ __forceinline__ void attn_decode_tile(const ChainArgs& args, const St
         l_run = l_run * alpha + p;
         m_run = m_new;
 #pragma unroll
-        for (int c = 0; c < 8; ++c)
+        for (int c = 0; c < 4; ++c)
 #pragma unroll
             for (int e = 0; e < 8; ++e) o[c * 8 + e] = __builtin_fmaf(p, (float)vv[c][e], o[c * 8 + e] * alpha);
     }
@@ -111,30 +113,28 @@ __device__ __forceinline__ void attn_decode_tile(const ChainArgs& args, const St
     // ---- the wave's lanes to the wave's maximum, summed through LDS ----
     float m_w = m_run;
 #pragma unroll
-    for (int d = 2; d < 64; d <<= 1) m_w = fmaxf(m_w, __shfl_xor(m_w, d));
-    m_w = fmaxf(m_w, __shfl_xor(m_w, 1));
+    for (int d = 1; d < 64; d <<= 1) m_w = fmaxf(m_w, __shfl_xor(m_w, d));
     const float m_wu = (m_w == -INFINITY) ? 0.0f : m_w;
     const float f = __builtin_amdgcn_exp2f(m_run - m_wu);         // 0 for lanes that saw no live key
-    float l_w = (half == 0) ? l_run * f : 0.0f;                   // both lanes of a pair hold the same l
+    float l_w = (quarter == 0) ? l_run * f : 0.0f;                // the four lanes of a key hold the same l
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) l_w += __shfl_xor(l_w, d);
     float* const tr = reinterpret_cast<float*>(lds) + wave * (64 * 33);
     float* const part = reinterpret_cast<float*>(lds) + 4 * (64 * 33) + wave * 130;   // [128 values, m, l]
     __syncthreads();                                              // (uniform) the LDS is free: the last tile is done with it
 #pragma unroll
-    for (int pass = 0; pass < 2; ++pass) {
+    for (int j = 0; j < 32; ++j) tr[lane * 33 + j] = o[j] * f;
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");            // this wave's writes are in LDS
+    __builtin_amdgcn_wave_barrier();
+    // each lane sums two of the 128 dimensions over the 16 key slots: dimension q * 32 + j lives in
+    // the lanes 4 * slot + q, at position j
 #pragma unroll
-        for (int j = 0; j < 32; ++j) tr[lane * 33 + j] = o[pass * 32 + j] * f;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");          // this wave's writes are in LDS
-        __builtin_amdgcn_wave_barrier();
-        // lane c of the pass sums dimension (c / 32) * 64 + pass * 32 + c % 32 over the 32 key slots
-        const uint32_t hh = lane >> 5, jj = lane & 31u;
+    for (int e = 0; e < 2; ++e) {
+        const uint32_t dim = 2 * lane + e, qd = dim >> 5, jj = dim & 31u;
         float acc = 0.0f;
 #pragma unroll
-        for (int sl = 0; sl < 32; ++sl) acc += tr[(2 * sl + hh) * 33 + jj];
-        part[hh * 64 + pass * 32 + jj] = acc;
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        __builtin_amdgcn_wave_barrier();
+        for (int sl = 0; sl < 16; ++sl) acc += tr[(4 * sl + qd) * 33 + jj];
+        part[dim] = acc;
     }
     if (lane == 0) { part[128] = m_w; part[129] = l_w; }
     dr.peek();

@@ -64,6 +64,11 @@ hipError_t launch_chain_kernel(int tile, int dtype, uint32_t amode, bool sync, u
     if (amode == A_CONV3X3)
         return dtype == 0 ? launch_bf16_conv(tile, sync, n_blocks, stream, a)
                           : launch_f16_conv(tile, sync, n_blocks, stream, a);
+    // a chain whose middle stage is attention for one new token per sequence runs the kernels that
+    // hold the token-generation tile
+    if (a.n_stages == 3 && a.st[1].op == OP_ATTN && a.st[1].seq == 1)
+        return dtype == 0 ? launch_bf16_gemm_gen(tile, sync, n_blocks, stream, a)
+                          : launch_f16_gemm_gen(tile, sync, n_blocks, stream, a);
     return dtype == 0 ? launch_bf16_gemm(tile, sync, n_blocks, stream, a)
                       : launch_f16_gemm(tile, sync, n_blocks, stream, a);
 }
