@@ -21,6 +21,8 @@ SOURCES = [
     "kern_copy.hip",
     "kern_bf16_gen.hip",
     "kern_f16_gen.hip",
+    "kern_bf16_attn.hip",
+    "kern_f16_attn.hip",
 ]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

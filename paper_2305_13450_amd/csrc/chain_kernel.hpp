@@ -4,9 +4,9 @@
 // tile it runs from the chain's dispatch queues (see sync_device.hpp for why producer
 // and consumer share one body).  It is instantiated per macro-tile shape, element type, A
 // addressing mode, and with the synchronisation hooks compiled in (FINE, STREAMSYNC) or out
-// (PLAIN).  The token-generation attention tile lives in instantiations of its own (GEN), used
-// only by chains that have such a stage, so that its registers do not weigh on the allocation
-// of the kernels every other chain runs.  Each translation unit kern_*.hip instantiates one
+// (PLAIN).  The attention tiles live in instantiations of their own (MIDK: 0 no attention stage,
+// 1 prompt-phase attention, 2 token generation), used only by chains that have such a stage, so
+// that their registers do not weigh on the allocation of the kernels every other chain runs.  Each translation unit kern_*.hip instantiates one
 // (type, mode) family so that the families compile in parallel.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -18,12 +18,12 @@
 
 namespace depsync {
 
-template <class Cfg, typename T, bool SYNC, uint32_t AMODE, bool GEN, class DR>
+template <class Cfg, typename T, bool SYNC, uint32_t AMODE, int MIDK, class DR>
 __device__ __forceinline__ void run_tile(const ChainArgs& args, const TileId t, char* lds, uint64_t t_enter, DR& dr) {
     const StageDesc& s = args.st[t.stage];
-    if constexpr (AMODE == A_DENSE) {
+    if constexpr (AMODE == A_DENSE && MIDK != 0) {
         if (s.op == OP_ATTN) {   // middle stage of the attention chain
-            if constexpr (GEN) attn_decode_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);   // token generation (seq = 1)
+            if constexpr (MIDK == 2) attn_decode_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);   // token generation (seq = 1)
             else attn_tile<T, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
             return;
         }
@@ -37,7 +37,7 @@ __device__ __forceinline__ void run_tile(const ChainArgs& args, const TileId t, 
     gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
 }
 
-template <class Cfg, typename T, bool SYNC, uint32_t AMODE, bool GEN>
+template <class Cfg, typename T, bool SYNC, uint32_t AMODE, int MIDK>
 __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs args) {
     // One LDS object only: with a second one the compiler can no longer tell the DMA writes
     // into the idle stage from the fragment reads of the current stage and serialises them.
@@ -47,7 +47,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs a
     if constexpr (!SYNC) {
         // hooks compiled out: one tile per workgroup, named by the hardware's block index
         NoDrawer nd;
-        run_tile<Cfg, T, false, AMODE, GEN>(args, hw_order_tile(args), lds, 0, nd);
+        run_tile<Cfg, T, false, AMODE, MIDK>(args, hw_order_tile(args), lds, 0, nd);
     } else {
         Drawer dr(args, reinterpret_cast<uint32_t*>(lds));
         const bool hw_order = (args.flags & DS_FLAG_HW_ORDER) != 0;   // one tile, from the block index
@@ -57,7 +57,7 @@ __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs a
             if (args.flags & DS_FLAG_TRACE) t_enter = now_ticks();
             const TileId t = hw_order ? hw_order_tile(args) : dr.next();
             if (t.rel == 0xffffffffu) return;
-            run_tile<Cfg, T, true, AMODE, GEN>(args, t, lds, t_enter, dr);
+            run_tile<Cfg, T, true, AMODE, MIDK>(args, t, lds, t_enter, dr);
             if (hw_order) return;
         }
     }
@@ -76,29 +76,29 @@ using Cfg256x64 = TileCfg<256, 64, 4, 1, 2, 2>;     // 2 x 80 KB
 using Cfg64x64Deep = TileCfg<64, 64, 2, 2, 1, 8>;   // 128 KB: seven K steps in flight
 using Cfg64x192 = TileCfg<64, 192, 2, 2, 1, 4>;     // 128 KB: three K steps in flight
 
-template <class Cfg, typename T, uint32_t AMODE, bool GEN>
+template <class Cfg, typename T, uint32_t AMODE, int MIDK>
 static hipError_t launch_cfg(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
     if (sync)
-        hipLaunchKernelGGL((chain_kernel<Cfg, T, true, AMODE, GEN>), dim3(n_blocks), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((chain_kernel<Cfg, T, true, AMODE, MIDK>), dim3(n_blocks), dim3(256), 0, stream, a);
     else
-        hipLaunchKernelGGL((chain_kernel<Cfg, T, false, AMODE, GEN>), dim3(n_blocks), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL((chain_kernel<Cfg, T, false, AMODE, MIDK>), dim3(n_blocks), dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 
-template <typename T, uint32_t AMODE, bool GEN = false>
+template <typename T, uint32_t AMODE, int MIDK = 0>
 static hipError_t launch_family(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
     switch (tile) {
-        case 1: return launch_cfg<Cfg256x256, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 2: return launch_cfg<Cfg256x128, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 3: return launch_cfg<Cfg128x256, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 4: return launch_cfg<Cfg128x128, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 5: return launch_cfg<Cfg64x128, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 6: return launch_cfg<Cfg64x64, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 7: return launch_cfg<Cfg256x192, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 8: return launch_cfg<Cfg128x192, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 9: return launch_cfg<Cfg256x64, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 10: return launch_cfg<Cfg64x64Deep, T, AMODE, GEN>(sync, n_blocks, stream, a);
-        case 11: return launch_cfg<Cfg64x192, T, AMODE, GEN>(sync, n_blocks, stream, a);
+        case 1: return launch_cfg<Cfg256x256, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 2: return launch_cfg<Cfg256x128, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 3: return launch_cfg<Cfg128x256, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 4: return launch_cfg<Cfg128x128, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 5: return launch_cfg<Cfg64x128, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 6: return launch_cfg<Cfg64x64, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 7: return launch_cfg<Cfg256x192, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 8: return launch_cfg<Cfg128x192, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 9: return launch_cfg<Cfg256x64, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 10: return launch_cfg<Cfg64x64Deep, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 11: return launch_cfg<Cfg64x192, T, AMODE, MIDK>(sync, n_blocks, stream, a);
         default: return hipErrorInvalidValue;
     }
 }

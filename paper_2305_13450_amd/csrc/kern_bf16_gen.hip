@@ -5,6 +5,6 @@
 
 namespace depsync {
 hipError_t launch_bf16_gemm_gen(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
-    return launch_family<__bf16, A_DENSE, true>(tile, sync, n_blocks, stream, a);
+    return launch_family<__bf16, A_DENSE, 2>(tile, sync, n_blocks, stream, a);
 }
 }  // namespace depsync

@@ -33,6 +33,8 @@ hipError_t launch_bf16_conv(int tile, bool sync, uint32_t n_blocks, hipStream_t 
 hipError_t launch_f16_conv(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);
 hipError_t launch_bf16_gemm_gen(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);
 hipError_t launch_f16_gemm_gen(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);
+hipError_t launch_bf16_gemm_attn(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);
+hipError_t launch_f16_gemm_attn(int tile, bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);
 hipError_t launch_copy(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a);   // kern_copy.hip
 
 }  // namespace depsync

@@ -69,6 +69,9 @@ hipError_t launch_chain_kernel(int tile, int dtype, uint32_t amode, bool sync, u
     if (a.n_stages == 3 && a.st[1].op == OP_ATTN && a.st[1].seq == 1)
         return dtype == 0 ? launch_bf16_gemm_gen(tile, sync, n_blocks, stream, a)
                           : launch_f16_gemm_gen(tile, sync, n_blocks, stream, a);
+    if (a.n_stages == 3 && a.st[1].op == OP_ATTN)
+        return dtype == 0 ? launch_bf16_gemm_attn(tile, sync, n_blocks, stream, a)
+                          : launch_f16_gemm_attn(tile, sync, n_blocks, stream, a);
     return dtype == 0 ? launch_bf16_gemm(tile, sync, n_blocks, stream, a)
                       : launch_f16_gemm(tile, sync, n_blocks, stream, a);
 }
