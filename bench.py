@@ -553,7 +553,10 @@ def main():
         # after the chain, so that the chip is warm; random operands last
         zero = ds.mfma_calibration(True, args.mfma_calibration)
         rnd = ds.mfma_calibration(False, args.mfma_calibration)
+        # a loop that issues an MFMA every cycle it can: TFLOP/s / (CUs x 4096 flop/clk) is the clock it ran at
+        per_clk = n_cu * 4096.0
         out["mfma_calibration"] = {"zero_operands_tflops": zero, "random_operands_tflops": rnd,
+                                   "implied_clock_mhz_zero": zero * 1e6 / per_clk, "implied_clock_mhz_random": rnd * 1e6 / per_clk,
                                    "chain_vs_random_ceiling": tflops / rnd if rnd else None}
 
     if not args.no_cpu_baseline:
