@@ -49,7 +49,7 @@ def parse():
                     help="GeMM chains: weights row-major [N x K] or packed [K/64][N][64]")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-autotune", action="store_true", help="use the library's model-based tile choice")
-    ap.add_argument("--cpu-rows", type=int, default=384, help="rows of X the CPU oracle is timed on")
+    ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of X the CPU oracle is timed on")
     ap.add_argument("--modes", default="fine,fused,streamsync,plain")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB three times, so that "
