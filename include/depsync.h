@@ -102,7 +102,9 @@ typedef enum {
                                   CU: for chains of few tiles that stream weights from HBM */
     DEPSYNC_TILE_64x192 = 11,  /* 64 rows, 192 columns, 4-stage pipeline, one workgroup per CU: skinny M on
                                   widths of the form 3 * 2^k, where it splits into 256 equal parts     */
-    DEPSYNC_TILE__COUNT = 12
+    DEPSYNC_TILE_128x192_DEEP = 12, /* 128x192 and 128x128 with a 4-stage operand pipeline, one workgroup */
+    DEPSYNC_TILE_128x128_DEEP = 13, /* per CU: mid-size M, where a tile's weights come from HBM, not L2  */
+    DEPSYNC_TILE__COUNT = 14
 } depsync_tile;
 
 /* Policy flags. */

@@ -119,6 +119,8 @@ double tile_cost_factor(int tile) {
         case DEPSYNC_TILE_256x64: return 1.3;
         case DEPSYNC_TILE_64x64_DEEP: return 4.0;   // one workgroup per CU: only ever worth it when tiles are few
         case DEPSYNC_TILE_64x192: return 3.0;       // likewise
+        case DEPSYNC_TILE_128x192_DEEP: return 1.25;   // found by the autotuner at mid-size M; the model has no
+        case DEPSYNC_TILE_128x128_DEEP: return 1.45;   // notion of where the weights come from
         default: return 2.4;
     }
 }

@@ -75,6 +75,8 @@ using Cfg128x192 = TileCfg<128, 192, 2, 2, 2, 2>;   // 2 x 80 KB
 using Cfg256x64 = TileCfg<256, 64, 4, 1, 2, 2>;     // 2 x 80 KB
 using Cfg64x64Deep = TileCfg<64, 64, 2, 2, 1, 8>;   // 128 KB: seven K steps in flight
 using Cfg64x192 = TileCfg<64, 192, 2, 2, 1, 4>;     // 128 KB: three K steps in flight
+using Cfg128x192Deep = TileCfg<128, 192, 2, 2, 1, 4>;   // 160 KB: three K steps in flight
+using Cfg128x128Deep = TileCfg<128, 128, 2, 2, 1, 4>;   // 128 KB: three K steps in flight
 
 template <class Cfg, typename T, uint32_t AMODE, int MIDK>
 static hipError_t launch_cfg(bool sync, uint32_t n_blocks, hipStream_t stream, const ChainArgs& a) {
@@ -99,6 +101,8 @@ static hipError_t launch_family(int tile, bool sync, uint32_t n_blocks, hipStrea
         case 9: return launch_cfg<Cfg256x64, T, AMODE, MIDK>(sync, n_blocks, stream, a);
         case 10: return launch_cfg<Cfg64x64Deep, T, AMODE, MIDK>(sync, n_blocks, stream, a);
         case 11: return launch_cfg<Cfg64x192, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 12: return launch_cfg<Cfg128x192Deep, T, AMODE, MIDK>(sync, n_blocks, stream, a);
+        case 13: return launch_cfg<Cfg128x128Deep, T, AMODE, MIDK>(sync, n_blocks, stream, a);
         default: return hipErrorInvalidValue;
     }
 }

@@ -401,6 +401,13 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // the first group; the 256-row tiles, with twice the requests per wave, do best with a
     // quarter of the groups: 256x192 714 -> 684 us)
     constexpr int NGD = (NST > 2) ? NG : (FM <= 2 ? 1 : NG / 4);
+    // Tiles that have a CU to themselves (one wave per SIMD) read all fragments of the next
+    // 16-wide K slice together, a whole slice of MFMAs before their first use, with the order
+    // pinned: left to itself the compiler issues each read right before the wait for it (while
+    // LDS DMA is in flight it only ever waits for lgkmcnt(0)), and with no second workgroup on
+    // the CU nothing fills that round trip.  Measured on the GPT-3 chain at M = 2048: 256x128
+    // 609 -> 585 us, 256x192 621 -> 612 us; with two workgroups per CU it gains nothing.
+    constexpr bool S2 = (Cfg::MINB == 1);
     static_assert((NST - 2) * ND <= 48, "outstanding DMA instructions must fit the vmcnt counter");
 #pragma unroll
     for (int p = 0; p < NST - 1; ++p) {
@@ -438,10 +445,27 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
             const int c = kk & 1, n = c ^ 1;
+            if constexpr (S2) {
+                // an empty asm that reads the current slice's fragments: the compiler's wait for
+                // them lands here, before the next slice's reads are issued
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+                for (int i = 0; i < FM; ++i) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, af[c][i])));
+#pragma unroll
+                for (int j = 0; j < FN; ++j) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, bf[c][j])));
+                __builtin_amdgcn_sched_barrier(0);
+                if (kk < 3) {
+#pragma unroll
+                    for (int i = 0; i < FM; ++i) af[n][i] = *(const V8*)(la + aoff[kk + 1] + i * (32 * 128));
+#pragma unroll
+                    for (int j = 0; j < FN; ++j) bf[n][j] = *(const V8*)(lb + boff[kk + 1] + j * (32 * 128));
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
 #pragma unroll
             for (int i = 0; i < FM; ++i) {
                 const int g = kk * FM + i;
-                if (kk < 3) {
+                if (!S2 && kk < 3) {
                     af[n][i] = *(const V8*)(la + aoff[kk + 1] + i * (32 * 128));
 #pragma unroll
                     for (int j = (i * FN) / FM; j < ((i + 1) * FN) / FM; ++j)
@@ -456,6 +480,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                 }
 #pragma unroll
                 for (int j = 0; j < FN; ++j) acc[i][j] = M::mma(af[c][i], bf[c][j], acc[i][j]);
+                if constexpr (S2) __builtin_amdgcn_sched_barrier(0);
             }
         }
         cur = (cur + 1 == NST) ? 0 : cur + 1;

@@ -11,7 +11,7 @@ struct TileShape {
     int wave_cols;        // columns of one wave's sub-tile (gate/up fusion needs a multiple of 64)
 };
 
-// nullptr for ids outside [1, 11].
+// nullptr for ids outside [1, 13].
 const TileShape* tile_shape(int tile);
 
 // Launch n_blocks workgroups of the chain kernel for macro-tile `tile`, element type `dtype`

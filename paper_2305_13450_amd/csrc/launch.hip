@@ -96,8 +96,10 @@ const TileShape* tile_shape(int tile) {
         {256, 64, 2, 64},
         {64, 64, 1, 32},
         {64, 192, 1, 96},
+        {128, 192, 1, 96},
+        {128, 128, 1, 64},
     };
-    if (tile < 1 || tile > 11) return nullptr;
+    if (tile < 1 || tile > 13) return nullptr;
     return &shapes[tile];
 }
 

@@ -12,7 +12,8 @@ from gpu_util import TOL_BF16, TOL_MID, mid_err, rel_err, row_err, run_attn_chai
 pytestmark = pytest.mark.gpu
 
 ALL_TILES = [ds.TILE_256x256, ds.TILE_256x128, ds.TILE_128x256, ds.TILE_128x128, ds.TILE_64x128, ds.TILE_64x64,
-             ds.TILE_256x192, ds.TILE_128x192, ds.TILE_256x64, ds.TILE_64x64_DEEP, ds.TILE_64x192]
+             ds.TILE_256x192, ds.TILE_128x192, ds.TILE_256x64, ds.TILE_64x64_DEEP, ds.TILE_64x192,
+             ds.TILE_128x192_DEEP, ds.TILE_128x128_DEEP]
 MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN, ds.MODE_FUSED]
 KINDS = [ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC]
 

@@ -19,7 +19,8 @@ def _oracle(t):
 
 
 @pytest.mark.parametrize("kind", KINDS)
-@pytest.mark.parametrize("tile", [ds.TILE_256x256, ds.TILE_128x128, ds.TILE_64x64, ds.TILE_256x192, ds.TILE_128x192, ds.TILE_256x64, ds.TILE_64x64_DEEP, ds.TILE_64x192])
+@pytest.mark.parametrize("tile", [ds.TILE_256x256, ds.TILE_128x128, ds.TILE_64x64, ds.TILE_256x192, ds.TILE_128x192, ds.TILE_256x64, ds.TILE_64x64_DEEP, ds.TILE_64x192,
+                                  ds.TILE_128x192_DEEP, ds.TILE_128x128_DEEP])
 def test_conv_chain_small_images_all_policies(kind, tile):
     # 3 images of 13x11 pixels (429 rows of the implicit GeMM: several row tiles, ragged tail, images
     # that straddle tile boundaries), 64 -> 128 -> 64 channels

@@ -12,7 +12,8 @@ from gpu_util import TOL_BF16, TOL_FP16, TOL_MID, mid_err, rel_err, run_gemm_cha
 pytestmark = pytest.mark.gpu
 
 ALL_TILES = [ds.TILE_256x256, ds.TILE_256x128, ds.TILE_128x256, ds.TILE_128x128, ds.TILE_64x128, ds.TILE_64x64,
-             ds.TILE_256x192, ds.TILE_128x192, ds.TILE_256x64, ds.TILE_64x64_DEEP, ds.TILE_64x192]
+             ds.TILE_256x192, ds.TILE_128x192, ds.TILE_256x64, ds.TILE_64x64_DEEP, ds.TILE_64x192,
+             ds.TILE_128x192_DEEP, ds.TILE_128x128_DEEP]
 MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN, ds.MODE_FUSED]
 
 
@@ -321,7 +322,7 @@ def test_split_k_matches_oracle_and_does_not_depend_on_timing(ksplit, kind):
     M, K1, N1, N2 = 200, 1536, 1536, 328
     t = inputs.mlp(M, K1, N1, N2, seed=37)
     Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
-    for tile in (ds.TILE_64x64, ds.TILE_128x128, ds.TILE_128x192):
+    for tile in (ds.TILE_64x64, ds.TILE_128x128, ds.TILE_128x192, ds.TILE_128x192_DEEP):
         print(f"split-K ksplit={ksplit} kind={kind} tile={tile}", flush=True)
         pol = ds.SyncPolicy(kind, ksplit=ksplit)
         plan = ds.gemm_chain_plan(t["X"].cuda(), t["W1"].t().contiguous().cuda(), torch.empty((M, N1), dtype=torch.bfloat16, device="cuda"),
