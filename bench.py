@@ -306,6 +306,13 @@ def roofline(plan, lat_us):
     return roof, tflops
 
 
+def tile_label(ds, tile):
+    """'128x192', or '128x192 deep' for the shapes that also exist with a 4- or 8-stage operand pipeline."""
+    tm, tn = ds.tile_shape(tile)
+    deep = tile in (ds.TILE_64x64_DEEP, ds.TILE_128x192_DEEP, ds.TILE_128x128_DEEP)
+    return f"{tm}x{tn}" + (" deep" if deep else "")
+
+
 def sweep(args, torch, ds, inputs):
     """All configurations -> markdown table."""
     sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
@@ -337,10 +344,9 @@ def sweep(args, torch, ds, inputs):
         n_tiles = plan.n_prod + plan.n_mid + plan.n_cons
         util, final = trace_occupancy(ds, torch, wl, r["kinds"][r["best"][0]], r["modes"][r["best"][1]], 0, sp, sc,
                                       n_tiles, plan.slots)
-        tm, tn = ds.tile_shape(plan.tile_prod)
         mid = f" / {plan.n_mid}" if plan.n_mid else ""
         lines.append(
-            f"| {wl.name} | {tm}x{tn} | {plan.n_prod}{mid} / {plan.n_cons} | {plan.slots} | "
+            f"| {wl.name} | {tile_label(ds, plan.tile_prod)} | {plan.n_prod}{mid} / {plan.n_cons} | {plan.slots} | "
             f"{plan.waves_streamsync} / {plan.waves_fine} | {lat:.1f} ({r['best'][0]}/{r['best'][1]}) | {r['ss']:.1f} | "
             f"{r['plain']:.1f} | {r['ss'] / lat:.3f} | {r['plain'] / lat:.3f} | {tflops:.0f} | "
             f"{roof['bound']} {100 * roof['frac']:.1f} % | {fmt(util)} | {fmt(final)} |")
@@ -537,6 +543,7 @@ def main():
         "ms_per_step": lat / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": wl.name, "M": M, "policy": best_pol, "launch": best_mode, "tile": ds.tile_shape(plan.tile_prod),
+                   "tile_name": tile_label(ds, plan.tile_prod),
                    "tiles_producer": plan.n_prod, "tiles_middle": plan.n_mid, "tiles_consumer": plan.n_cons,
                    "slots": plan.slots, "waves_streamsync": plan.waves_streamsync, "waves_fine": plan.waves_fine},
         "latency_us": {f"{pn}/{mn}": round(v, 2) for (pn, mn), v in results.items()},
