@@ -32,8 +32,11 @@ def test_strerror_and_tile_shapes():
     assert b"invalid" in ds._lib().depsync_strerror(ds.EINVAL)
     assert ds.tile_shape(ds.TILE_256x256) == (256, 256)
     assert ds.tile_shape(ds.TILE_64x128) == (64, 128)
+    assert ds.tile_shape(ds.TILE_128x192_DEEP) == (128, 192) and ds.tile_shape(ds.TILE_128x128_DEEP) == (128, 128)
     with pytest.raises(ds.DepsyncError):
         ds.tile_shape(0)
+    with pytest.raises(ds.DepsyncError):
+        ds.tile_shape(ds.TILE_128x128_DEEP + 1)      # one past the last shape
 
 
 def test_policy_mirrors_match_oracle_model():
