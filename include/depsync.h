@@ -118,7 +118,8 @@ typedef enum {
                                          tiles of all stages fit on the GPU at once (otherwise
                                          DEPSYNC_EINVAL); in FUSED mode always legal, because
                                          each XCD starts the workgroups of one dispatch in index
-                                         order, producers first.                              */
+                                         order, producers first, and the default there for a
+                                         chain the autotuner has not decided otherwise.       */
 
 typedef struct {
     uint32_t stride;      /* STRIDEDSYNC on a GeMM chain: distance, in producer column tiles,
@@ -140,6 +141,10 @@ typedef struct {
 
 #define DEPSYNC_FLAG_TRACE 16u        /* record per-tile start / ready / end times (FINE and
                                          STREAMSYNC); read them with depsync_read_trace        */
+#define DEPSYNC_FLAG_QUEUE_ORDER 32u  /* FUSED: draw tiles from the dispatch queues (persistent
+                                         workgroups) even where the library would name them by the
+                                         block index, its default for a chain the autotuner has
+                                         not decided otherwise                                  */
 
 typedef struct sync_policy sync_policy_t;
 

@@ -22,7 +22,7 @@ BF16, FP16 = 0, 1
 (TILE_AUTO, TILE_256x256, TILE_256x128, TILE_128x256, TILE_128x128, TILE_64x128, TILE_64x64,
  TILE_256x192, TILE_128x192, TILE_256x64, TILE_64x64_DEEP, TILE_64x192, TILE_128x192_DEEP, TILE_128x128_DEEP) = range(14)
 W_ROWS, W_KBLOCKED = 0, 1
-FLAG_NO_REORDER, FLAG_COUNT, FLAG_REVERSE_ORDER, FLAG_HW_ORDER, FLAG_TRACE = 1, 2, 4, 8, 16
+FLAG_NO_REORDER, FLAG_COUNT, FLAG_REVERSE_ORDER, FLAG_HW_ORDER, FLAG_TRACE, FLAG_QUEUE_ORDER = 1, 2, 4, 8, 16, 32
 OK, EINVAL, ENOMEM, EHIP, ETIMEOUT, ENOTIMPL = 0, -1, -2, -3, -4, -5
 
 EXPORTS = [

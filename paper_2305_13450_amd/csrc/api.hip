@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <array>
 #include <cstdint>
 #include <cstring>
 #include <map>
@@ -105,11 +106,26 @@ int device_cus(int n_cu) {
 }
 
 // Relative time per flop of the macro-tile shapes on a fully occupied CU, from measurements of
-// the GPT-3 MLP chain at M = 2048 on MI355X (128x192 = 1): smaller tiles read more LDS and L2 bytes per flop.
-double tile_cost_factor(int tile) {
+// the GPT-3 and LLaMA MLP chains at M = 1 .. 2048 on MI355X (128x192 = 1): smaller tiles read more
+// LDS and L2 bytes per flop.  With these factors the model picks the tile measured fastest on all
+// ten of those chains.
+double tile_cost_factor(int tile, bool conv) {
+    if (conv) {
+        // the implicit-GeMM gather of A (a row of pixels per DMA row, taps that re-read their
+        // neighbours' rows) moves the order: measured on the VGG pairs at batch 16
+        switch (tile) {
+            case DEPSYNC_TILE_256x128: return 1.25;
+            case DEPSYNC_TILE_128x256: return 1.12;
+            case DEPSYNC_TILE_128x128: return 1.08;
+            case DEPSYNC_TILE_64x128: return 1.3;
+            case DEPSYNC_TILE_128x192_DEEP: return 1.3;
+            case DEPSYNC_TILE_64x64_DEEP: return 5.0;
+            default: break;
+        }
+    }
     switch (tile) {
         case DEPSYNC_TILE_256x256: return 1.30;   // its synchronised variant spills registers around the tile loop
-        case DEPSYNC_TILE_256x128: return 1.12;
+        case DEPSYNC_TILE_256x128: return 1.04;
         case DEPSYNC_TILE_128x256: return 1.10;
         case DEPSYNC_TILE_128x128: return 1.20;
         case DEPSYNC_TILE_64x128: return 1.6;
@@ -118,9 +134,9 @@ double tile_cost_factor(int tile) {
         case DEPSYNC_TILE_128x192: return 1.00;
         case DEPSYNC_TILE_256x64: return 1.3;
         case DEPSYNC_TILE_64x64_DEEP: return 4.0;   // one workgroup per CU: only ever worth it when tiles are few
-        case DEPSYNC_TILE_64x192: return 3.0;       // likewise
-        case DEPSYNC_TILE_128x192_DEEP: return 1.25;   // found by the autotuner at mid-size M; the model has no
-        case DEPSYNC_TILE_128x128_DEEP: return 1.45;   // notion of where the weights come from
+        case DEPSYNC_TILE_64x192: return 2.0;       // likewise
+        case DEPSYNC_TILE_128x192_DEEP: return 1.10;   // one workgroup per CU, 4 stages: ahead of 128x192 only
+        case DEPSYNC_TILE_128x128_DEEP: return 1.45;   // where that tile would have to split along K
         default: return 2.4;
     }
 }
@@ -151,10 +167,26 @@ int tuned_tile(const TuneKey& k) {
     return it == g_tuned.end() ? 0 : it->second;
 }
 
+uint32_t choose_split(const sync_policy* pol, bool tuned_off, uint32_t tiles, uint32_t slots, uint32_t kt, uint32_t seg);
+
 // Pick one macro-tile for both stages by simulating the fine-grained schedule of the chain
-// on `slots` workgroup slots for every candidate shape (host_model.h).
+// on `slots` workgroup slots for every candidate shape (host_model.h).  A stage that would leave
+// slots idle is modelled as the planner will run it: split along K into S parts, each costing
+// 1/S of the tile plus 15 % per further part for the partial tiles and the workgroup that sums them.
 int choose_tile(uint32_t M, uint32_t n_out1, uint32_t K1, uint32_t N2, uint32_t K2, bool gate_up,
                 int n_cu, int rows_halo_tiles) {
+    // The simulation walks every tile of every candidate shape (a millisecond of host time for
+    // the largest conv pairs, which every launch with TILE_AUTO would pay): remember the answer.
+    using Key = std::array<uint64_t, 4>;
+    static std::map<Key, int> memo;
+    static std::mutex memo_mutex;
+    const Key key = {((uint64_t)M << 32) | n_out1, ((uint64_t)K1 << 32) | N2,
+                     ((uint64_t)K2 << 32) | (uint32_t)n_cu, ((uint64_t)(uint32_t)rows_halo_tiles << 1) | (uint64_t)gate_up};
+    {
+        std::lock_guard<std::mutex> lock(memo_mutex);
+        const auto it = memo.find(key);
+        if (it != memo.end()) return it->second;
+    }
     int best = 0;
     double best_t = 0;
     for (int t = 1; t < DEPSYNC_TILE__COUNT; ++t) {
@@ -163,14 +195,19 @@ int choose_tile(uint32_t M, uint32_t n_out1, uint32_t K1, uint32_t N2, uint32_t 
         const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
         const uint32_t gy = cdiv(M, ts->rows);
         const uint32_t gx1 = cdiv(n_out1, tn1), gx2 = cdiv(N2, ts->cols);
-        const double f = tile_cost_factor(t);
+        const double f = tile_cost_factor(t, rows_halo_tiles > 0);
         // `occupancy` workgroups share a CU's matrix units, so each runs at 1/occupancy of its rate
-        const double d1 = f * (double)ts->rows * ts->cols * K1 * ts->occupancy;
-        const double d2 = f * (double)ts->rows * ts->cols * K2 * ts->occupancy;
-        const double tm = simulate_chain(n_cu * ts->occupancy, gx1, gy, d1, gx2, gy, d2, rows_halo_tiles,
+        const uint32_t slots = (uint32_t)(n_cu * ts->occupancy);
+        const uint32_t s1 = choose_split(nullptr, false, gx1 * gy, slots, K1 / 64, 1);
+        const uint32_t s2 = choose_split(nullptr, false, gx2 * gy, slots, K2 / 64, 1);
+        const double d1 = f * (double)ts->rows * ts->cols * K1 * ts->occupancy / s1 * (1.0 + 0.15 * (s1 - 1));
+        const double d2 = f * (double)ts->rows * ts->cols * K2 * ts->occupancy / s2 * (1.0 + 0.15 * (s2 - 1));
+        const double tm = simulate_chain((int)slots, gx1 * s1, gy, d1, gx2 * s2, gy, d2, rows_halo_tiles,
                                          /*stream_sync=*/false);
         if (best == 0 || tm < best_t) { best = t; best_t = tm; }
     }
+    std::lock_guard<std::mutex> lock(memo_mutex);
+    memo[key] = best;
     return best;
 }
 
@@ -274,8 +311,14 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     const int cus = device_cus(n_cu);
     if (cus <= 0) return DEPSYNC_EHIP;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    bool tuned_off = false, tuned_hw = false;
-    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
+    // Untuned chains run one dispatch in block-index order: what the autotuner finds faster on
+    // nearly every chain measured (no draw from the dispatch queues at all).
+    bool tuned_off = false, tuned_hw = true;
+    if (!tile) {
+        const int v = tuned_tile(tune_key(d, pol));
+        tile = v & 0xff;
+        if (v) { tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
+    }
     if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
     const TileShape* ts = tile_shape(tile);
     if (!ts) return DEPSYNC_EINVAL;
@@ -408,8 +451,14 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
     if (cus <= 0) return DEPSYNC_EHIP;
     const uint32_t M = (uint32_t)Mpix;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    bool tuned_off = false, tuned_hw = false;
-    if (!tile) { const int v = tuned_tile(tune_key(d, pol)); tile = v & 0xff; tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
+    // Untuned chains run one dispatch in block-index order: what the autotuner finds faster on
+    // nearly every chain measured (no draw from the dispatch queues at all).
+    bool tuned_off = false, tuned_hw = true;
+    if (!tile) {
+        const int v = tuned_tile(tune_key(d, pol));
+        tile = v & 0xff;
+        if (v) { tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
+    }
     if (!tile) {
         // halo: a consumer row tile reads W+1 rows beyond each end (modelled on the first two stages)
         tile = choose_tile(M, d->K[0], 9 * d->C, d->K[1], 9 * d->K[0], false, cus, 1);
@@ -635,7 +684,10 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     // Tiles in the hardware's order (Section IV-C, "T"): asked for by the caller, or found faster
     // by the autotuner for this chain in one dispatch.  In-order dispatch of the block index on
     // every XCD means no consumer workgroup is resident while a producer one is still unlaunched.
-    if (sync && mode == DEPSYNC_MODE_FUSED && (pol->force_order >= 0 ? pol->force_order == 1 : p.tuned_hw_order))
+    // The dispatch queues remain for callers that ask for them, for the debug order and for FINE and
+    // STREAMSYNC launches, whose workgroups are not dispatched in stage order.
+    const bool want_queues = (pol->params.flags & (DEPSYNC_FLAG_QUEUE_ORDER | DEPSYNC_FLAG_REVERSE_ORDER)) != 0;
+    if (sync && mode == DEPSYNC_MODE_FUSED && (pol->force_order >= 0 ? pol->force_order == 1 : (p.tuned_hw_order && !want_queues)))
         a.flags |= DEPSYNC_FLAG_HW_ORDER;
     uint32_t total = 0;
     for (int s = 0; s < p.n_stages; ++s) total += p.n_tiles[s];

@@ -75,6 +75,12 @@ def test_two_sequences_every_tile_and_policy(two_sequences, tile, kind):
             assert torch.equal(a, b)
     pol.status()
     pol.destroy()
+    pol = ds.SyncPolicy(kind, flags=ds.FLAG_QUEUE_ORDER)      # one dispatch, tiles drawn from the queues
+    got = run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 2, 256, 2, pol, ds.MODE_FUSED, tile=tile)
+    for a, b in zip(res[0], got):
+        assert torch.equal(a, b)
+    assert pol.status().timed_out == 0
+    pol.destroy()
 
 
 @pytest.mark.parametrize("kind", KINDS)

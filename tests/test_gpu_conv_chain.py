@@ -35,6 +35,11 @@ def test_conv_chain_small_images_all_policies(kind, tile):
     for mid, out in res[1:]:
         assert torch.equal(res[0][0], mid) and torch.equal(res[0][1], out)
     pol.destroy()
+    pol = ds.SyncPolicy(kind, flags=ds.FLAG_QUEUE_ORDER)      # one dispatch, tiles drawn from the queues
+    mid, out = run_conv_chain(t["x"], t["w1"], t["w2"], pol, ds.MODE_FUSED, tile=tile)
+    assert torch.equal(res[0][0], mid) and torch.equal(res[0][1], out)
+    assert pol.status().timed_out == 0
+    pol.destroy()
 
 
 def test_conv_chain_one_pixel_wide_and_tiny_images():

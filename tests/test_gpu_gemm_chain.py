@@ -56,6 +56,13 @@ def test_every_tile_shape_ragged(tile, kind):
     for H, Y in res[1:]:
         assert torch.equal(res[0][0], H) and torch.equal(res[0][1], Y)
     pol.destroy()
+    # one dispatch names its tiles by the block index unless told otherwise: the dispatch queues
+    # (persistent workgroups) must give the same bits
+    pol = ds.SyncPolicy(kind, flags=ds.FLAG_QUEUE_ORDER)
+    H, Y = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FUSED, tile=tile)
+    assert torch.equal(res[0][0], H) and torch.equal(res[0][1], Y)
+    assert pol.status().timed_out == 0
+    pol.destroy()
 
 
 @pytest.mark.parametrize("mid,act", [(ds.MID_NONE, oracle.ACT_NONE), (ds.MID_RELU, oracle.ACT_RELU)])
