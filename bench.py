@@ -379,8 +379,11 @@ def ablation(args, torch, ds, wl):
     tile = args.tile or wl.autotune(tuner, sp)          # one tile shape for every row of the table
     tuner.destroy()
     for pn in wl.policies:
-        for label, flags, mn in ((f"{pn}, one dispatch", 0, "fused"), (f"{pn}, two streams", 0, "fine"),
-                                 (f"{pn}, one dispatch, wait before the weights are requested", ds.FLAG_NO_REORDER, "fused"),
+        # "one dispatch" here means persistent workgroups drawing from the dispatch queues, so that
+        # the last row of each group isolates the block-index order (the library's default otherwise)
+        for label, flags, mn in ((f"{pn}, one dispatch", ds.FLAG_QUEUE_ORDER, "fused"), (f"{pn}, two streams", 0, "fine"),
+                                 (f"{pn}, one dispatch, wait before the weights are requested",
+                                  ds.FLAG_NO_REORDER | ds.FLAG_QUEUE_ORDER, "fused"),
                                  (f"{pn}, one dispatch, one workgroup per tile in hardware order", ds.FLAG_HW_ORDER, "fused")):
             pol = ds.SyncPolicy(kinds[pn], flags=flags)
             pols.append(pol)
