@@ -125,6 +125,27 @@ def test_planner_auto_tile_prefers_more_tiles_for_small_m():
     assert r_small * c_small <= r_big * c_big and r_small <= 128
 
 
+@pytest.mark.parametrize("K1,N1,N2,mid,M,tile", [
+    (12288, 6144, 12288, ds.MID_GELU, 64, ds.TILE_64x192),
+    (12288, 6144, 12288, ds.MID_GELU, 256, ds.TILE_128x192_DEEP),
+    (12288, 6144, 12288, ds.MID_GELU, 512, ds.TILE_128x192_DEEP),
+    (12288, 6144, 12288, ds.MID_GELU, 1024, ds.TILE_128x192),
+    (12288, 6144, 12288, ds.MID_GELU, 2048, ds.TILE_128x192),
+    (8192, 2752, 8192, ds.MID_SWIGLU, 1, ds.TILE_64x128),
+    (8192, 2752, 8192, ds.MID_SWIGLU, 256, ds.TILE_128x128_DEEP),
+    (8192, 2752, 8192, ds.MID_SWIGLU, 1024, ds.TILE_256x128),
+    (8192, 2752, 8192, ds.MID_SWIGLU, 2048, ds.TILE_256x128),
+])
+def test_planner_auto_tile_matches_the_measured_choice(K1, N1, N2, mid, M, tile):
+    # the schedule model (split along K included) on a 256-CU chip picks the macro-tile that was
+    # measured fastest on these MLP chains; asked twice, it answers the same (the choice is remembered)
+    d = _fake_gemm_desc(M, K1, N1, N2, mid=mid)
+    info = ds.PlanInfo()
+    for _ in range(2):
+        assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+        assert info.tile_prod == tile and info.tile_cons == tile
+
+
 def test_conv_planner():
     d = ds.ConvChainDesc()
     d.B, d.H, d.W, d.C, d.K1, d.K2, d.dtype = 4, 56, 56, 256, 256, 256, ds.BF16
