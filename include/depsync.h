@@ -274,6 +274,10 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
                        sync_policy_t** out);
 /* Synchronises the device, then frees the workspace.                                      */
 int sync_policy_destroy(sync_policy_t* pol);
+/* Bytes of device memory sync_policy_create allocates for a policy's workspace (dispatch
+ * counters, status block, zero page, semaphores, trace records, arrival counters); the same
+ * for every policy.  The split-K partial tiles are extra and grow with the chains run.   */
+size_t depsync_workspace_bytes(void);
 /* Re-zero semaphores, dispatch counter and status on `stream` (a fill kernel, safe under
  * graph capture) and restart the launch epoch.  Needed only after DEPSYNC_ETIMEOUT.       */
 int dep_chain_reset(sync_policy_t* pol, void* stream);

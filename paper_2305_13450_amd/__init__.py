@@ -33,7 +33,7 @@ EXPORTS = [
     "depsync_tile_shape", "depsync_device_info", "depsync_gemm_chain_autotune", "depsync_conv_chain_autotune",
     "depsync_gemm_chain_tuned", "depsync_conv_chain_tuned", "depsync_gemm_chain_set_tuned", "depsync_conv_chain_set_tuned",
     "depsync_mfma_calibration", "dep_copy_chain", "depsync_copy_chain_plan",
-    "dep_conv_chain_n", "depsync_conv_chain_n_plan", "depsync_conv_chain_n_autotune",
+    "dep_conv_chain_n", "depsync_conv_chain_n_plan", "depsync_conv_chain_n_autotune", "depsync_workspace_bytes",
 ]
 
 
@@ -521,6 +521,13 @@ def tile_shape(tile):
     r, c = ctypes.c_int(), ctypes.c_int()
     _check(_lib().depsync_tile_shape(tile, ctypes.byref(r), ctypes.byref(c)), "depsync_tile_shape")
     return r.value, c.value
+
+
+def workspace_bytes() -> int:
+    """Device memory a policy's workspace takes (split-K partial tiles not included)."""
+    f = _lib().depsync_workspace_bytes
+    f.restype = ctypes.c_size_t
+    return int(f())
 
 
 def device_info():

@@ -1194,6 +1194,8 @@ int depsync_mfma_calibration(int zero_operands, int milliseconds, double* tflops
     return rc;
 }
 
+size_t depsync_workspace_bytes(void) { return (size_t)WS_WORDS * sizeof(uint32_t); }
+
 int depsync_device_info(int* n_cu, int* clock_khz) {
     if (!n_cu || !clock_khz) return DEPSYNC_EINVAL;
     int dev = 0;

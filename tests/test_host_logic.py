@@ -37,6 +37,8 @@ def test_strerror_and_tile_shapes():
         ds.tile_shape(0)
     with pytest.raises(ds.DepsyncError):
         ds.tile_shape(ds.TILE_128x128_DEEP + 1)      # one past the last shape
+    # 65536 semaphores and 32768 arrival counters with a 128-byte line each, plus the rest
+    assert (65536 + 32768) * 128 < ds.workspace_bytes() < 32 << 20
 
 
 def test_policy_mirrors_match_oracle_model():
