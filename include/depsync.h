@@ -16,7 +16,12 @@
  *    or reallocates them and keeps no reference after the call returns.
  *  - Calls that enqueue work are asynchronous.  On return, work enqueued later on
  *    stream_producer is ordered after the whole chain (the library forks the consumer
- *    stream off the producer stream with an event and joins it back).
+ *    stream off the producer stream with an event and joins it back).  One exception: a chain
+ *    whose stages are split along K keeps fp32 partial tiles in a scratch buffer the policy
+ *    owns, and the first chain that needs a larger one than any before it on that policy
+ *    synchronises the device and reallocates it (hipFree + hipMalloc) before it enqueues.
+ *    All chains that use one policy must be enqueued on the same stream_producer (the implicit
+ *    re-zeroing of the workspace is ordered on it).
  *  - Streams are hipStream_t handles passed as void*; NULL means the default stream for
  *    stream_producer and "use the policy's own internal stream" for stream_consumer.
  *  - Semaphores, the tile-dispatch counter and the status block live in a small workspace
@@ -47,6 +52,8 @@ extern "C" {
 #define DEPSYNC_EHIP (-3)     /* a HIP call failed; see depsync_last_hip_error()           */
 #define DEPSYNC_ETIMEOUT (-4) /* a bounded wait (spin_limit) expired; see depsync_last_status */
 #define DEPSYNC_ENOTIMPL (-5) /* valid request this build does not implement               */
+#define DEPSYNC_ELIMIT (-6)   /* dep_gemm_chain_static: the chain needs more semaphores, arrival
+                                 counters or split-K scratch than the fixed workspace holds   */
 
 /* Synchronisation policies (Section III-E and Section IV-B). */
 typedef enum {
@@ -162,7 +169,7 @@ typedef struct {
 } depsync_trace_rec;
 
 typedef struct {
-    int32_t timed_out;       /* number of tiles whose bounded wait expired                    */
+    int32_t timed_out;       /* number of waves (four per tile) whose bounded wait expired    */
     int32_t first_timeout;   /* dispatch ticket of the first such tile, -1 if none            */
     uint32_t posts;          /* with DEPSYNC_FLAG_COUNT: semaphore increments                 */
     uint32_t waits;          /* with DEPSYNC_FLAG_COUNT: semaphore waits executed             */
@@ -349,6 +356,17 @@ int depsync_conv_chain_tuned(const depsync_conv_chain_desc* d, const sync_policy
 int depsync_gemm_chain_set_tuned(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int tile, int flags);
 int depsync_conv_chain_set_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int tile, int flags);
 
+
+/* Host-side check of the wait placement (no device needed; n_cu as for the planners; pointers in
+ * `d` are validated but not dereferenced): plans the chain for the given policy kind and
+ * parameters, walks every consumer tile's K loop the way the kernel does, and counts in
+ * *uncovered the (row tile, K part) pairs for which some K step loads a slice of the previous
+ * stage's output that no wait issued at or before that step covers (Section III-C: a tile may
+ * only read what the tiles it depends on have posted).  0 for every chain the library accepts. */
+int depsync_gemm_chain_check_waits(const depsync_gemm_chain_desc* d, depsync_policy_kind kind,
+                                   const depsync_policy_params* params, int n_cu, int64_t* uncovered);
+int depsync_conv_chain_n_check_waits(const depsync_conv_chain_n_desc* d, depsync_policy_kind kind,
+                                     const depsync_policy_params* params, int n_cu, int64_t* uncovered);
 
 /* ---- copy -> copy chain: what the synchronisation itself costs (Section V, overhead of
  * synchronisation: tile i of the consumer depends on tile i of the producer and the kernels

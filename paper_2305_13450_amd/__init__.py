@@ -23,7 +23,7 @@ BF16, FP16 = 0, 1
  TILE_256x192, TILE_128x192, TILE_256x64, TILE_64x64_DEEP, TILE_64x192, TILE_128x192_DEEP, TILE_128x128_DEEP) = range(14)
 W_ROWS, W_KBLOCKED = 0, 1
 FLAG_NO_REORDER, FLAG_COUNT, FLAG_REVERSE_ORDER, FLAG_HW_ORDER, FLAG_TRACE, FLAG_QUEUE_ORDER = 1, 2, 4, 8, 16, 32
-OK, EINVAL, ENOMEM, EHIP, ETIMEOUT, ENOTIMPL = 0, -1, -2, -3, -4, -5
+OK, EINVAL, ENOMEM, EHIP, ETIMEOUT, ENOTIMPL, ELIMIT = 0, -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "sync_policy_create", "sync_policy_destroy", "dep_chain_reset", "depsync_last_status", "depsync_read_trace",
@@ -34,6 +34,7 @@ EXPORTS = [
     "depsync_gemm_chain_tuned", "depsync_conv_chain_tuned", "depsync_gemm_chain_set_tuned", "depsync_conv_chain_set_tuned",
     "depsync_mfma_calibration", "dep_copy_chain", "depsync_copy_chain_plan",
     "dep_conv_chain_n", "depsync_conv_chain_n_plan", "depsync_conv_chain_n_autotune", "depsync_workspace_bytes",
+    "depsync_gemm_chain_check_waits", "depsync_conv_chain_n_check_waits",
 ]
 
 
@@ -146,6 +147,9 @@ def _lib() -> ctypes.CDLL:
         L.depsync_conv_chain_tuned.argtypes = [ctypes.POINTER(ConvChainDesc), vp, ctypes.POINTER(i32), ctypes.POINTER(i32)]
         L.depsync_gemm_chain_set_tuned.argtypes = [ctypes.POINTER(GemmChainDesc), vp, i32, i32]
         L.depsync_conv_chain_set_tuned.argtypes = [ctypes.POINTER(ConvChainDesc), vp, i32, i32]
+        i64p = ctypes.POINTER(ctypes.c_int64)
+        L.depsync_gemm_chain_check_waits.argtypes = [ctypes.POINTER(GemmChainDesc), i32, ctypes.POINTER(PolicyParams), i32, i64p]
+        L.depsync_conv_chain_n_check_waits.argtypes = [ctypes.POINTER(ConvChainNDesc), i32, ctypes.POINTER(PolicyParams), i32, i64p]
         L.depsync_row_major.argtypes = [i32] * 4
         L.depsync_policy_sem.argtypes = [i32] * 6
         L.depsync_policy_value.argtypes = [i32] * 4
@@ -478,6 +482,23 @@ def copy_chain_plan(src, mid, dst, policy: SyncPolicy, tile_bytes: int = 0, n_cu
     _check(_lib().depsync_copy_chain_plan(ctypes.byref(d), policy.handle, n_cu, ctypes.byref(info)),
            "depsync_copy_chain_plan")
     return info
+
+
+def gemm_chain_check_waits(desc: GemmChainDesc, kind: int, n_cu: int = 0, **params) -> int:
+    """(row tile, K part) pairs of the planned chain with an operand slice no wait covers (0 = sound)."""
+    pp = PolicyParams(**params)
+    n = ctypes.c_int64(-1)
+    _check(_lib().depsync_gemm_chain_check_waits(ctypes.byref(desc), kind, ctypes.byref(pp), n_cu, ctypes.byref(n)),
+           "depsync_gemm_chain_check_waits")
+    return n.value
+
+
+def conv_chain_n_check_waits(desc: ConvChainNDesc, kind: int, n_cu: int = 0, **params) -> int:
+    pp = PolicyParams(**params)
+    n = ctypes.c_int64(-1)
+    _check(_lib().depsync_conv_chain_n_check_waits(ctypes.byref(desc), kind, ctypes.byref(pp), n_cu, ctypes.byref(n)),
+           "depsync_conv_chain_n_check_waits")
+    return n.value
 
 
 # ---- host mirrors -------------------------------------------------------------------------

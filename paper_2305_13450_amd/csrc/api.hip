@@ -13,6 +13,7 @@
 
 #include "../../include/depsync.h"
 #include "chain_args.h"
+#include "dep_map.hpp"
 #include "host_model.h"
 #include "launch.h"
 
@@ -29,13 +30,28 @@ constexpr uint32_t WS_STATUS = WS_TICKET_WORDS;          // StatusBlock, 8 words
 constexpr uint32_t WS_ZERO_PAGE = WS_STATUS + 64;        // 64 words = 256 zero bytes (never written after init)
 constexpr uint32_t WS_SEMS = 2048;                       // one semaphore per 128-byte line
 static_assert(WS_ZERO_PAGE + 64 <= WS_SEMS && WS_SEMS % SYNC_WORD_STRIDE == 0, "counters, status and zero page end before the semaphores");
-constexpr uint32_t WS_MAX_SEMS = 1u << 16;
-constexpr uint32_t WS_SEM_WORDS = WS_MAX_SEMS * SYNC_WORD_STRIDE;
-constexpr uint32_t WS_TRACE = WS_SEMS + WS_SEM_WORDS;     // TraceRec[WS_TRACE_CAP], 12 words each
-constexpr uint32_t WS_TRACE_CAP = 8192;
-constexpr uint32_t WS_ARRIVE = WS_TRACE + WS_TRACE_CAP * (sizeof(TraceRec) / 4);   // split-K arrival counters
-constexpr uint32_t WS_MAX_ARRIVE = 1u << 15;
-constexpr uint32_t WS_WORDS = WS_ARRIVE + WS_MAX_ARRIVE * SYNC_WORD_STRIDE;   // one 128-byte line per counter
+
+// What follows the fixed part differs between a policy's own workspace (hipMalloc'ed by
+// sync_policy_create) and the smaller one inside the library's static device array.
+struct WsLayout {
+    uint32_t max_sems;      // semaphores, from word WS_SEMS on
+    uint32_t trace;         // word offset of the trace records
+    uint32_t trace_cap;     // records (0: tracing unavailable)
+    uint32_t arrive;        // word offset of the split-K arrival counters, one 128-byte line each
+    uint32_t max_arrive;
+    uint32_t words;         // total size in 32-bit words
+};
+constexpr WsLayout make_layout(uint32_t max_sems, uint32_t trace_cap, uint32_t max_arrive) {
+    WsLayout l{};
+    l.max_sems = max_sems;
+    l.trace = WS_SEMS + max_sems * SYNC_WORD_STRIDE;
+    l.trace_cap = trace_cap;
+    l.arrive = l.trace + trace_cap * (uint32_t)(sizeof(TraceRec) / 4);
+    l.max_arrive = max_arrive;
+    l.words = l.arrive + max_arrive * SYNC_WORD_STRIDE;
+    return l;
+}
+constexpr WsLayout HEAP_LAYOUT = make_layout(1u << 16, 8192, 1u << 15);
 
 int hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
@@ -68,6 +84,8 @@ struct sync_policy {
     size_t scratch_floats;
     uint32_t sems_dirty;   // semaphores that may be non-zero (largest count used since they were last cleared)
     bool need_reset;
+    WsLayout lay;          // where things are in ws
+    bool fixed_scratch;    // ws and scratch are parts of the static device array: never (re)allocated
 };
 
 namespace {
@@ -86,6 +104,7 @@ struct Plan {
     uint32_t arrive_off[4];          // first arrival counter of the stage
     size_t partial_off[4];           // first float of the stage's partial tiles
     size_t partial_floats;           // scratch the chain needs
+    uint32_t n_arrive;               // arrival counters the chain needs
     uint32_t n_sems;
     int slots;
     double flops, bytes;
@@ -191,7 +210,7 @@ int choose_tile(uint32_t M, uint32_t n_out1, uint32_t K1, uint32_t N2, uint32_t 
     double best_t = 0;
     for (int t = 1; t < DEPSYNC_TILE__COUNT; ++t) {
         const TileShape* ts = tile_shape(t);
-        if (gate_up && ts->wave_cols % 64) continue;
+        if (gate_up && (ts->wave_cols % 64 || (ts->cols / 2) % 64)) continue;
         const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
         const uint32_t gy = cdiv(M, ts->rows);
         const uint32_t gx1 = cdiv(n_out1, tn1), gx2 = cdiv(N2, ts->cols);
@@ -258,8 +277,8 @@ int finish_split(Plan& p) {
             fl += (size_t)real * p.ksplit[s] * ts->rows * ts->cols;
         }
     }
-    if (arr > WS_MAX_ARRIVE) return DEPSYNC_ENOMEM;
     p.partial_floats = fl;
+    p.n_arrive = arr;
     return DEPSYNC_OK;
 }
 
@@ -323,6 +342,9 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     const TileShape* ts = tile_shape(tile);
     if (!ts) return DEPSYNC_EINVAL;
     if (gate_up && ts->wave_cols % 64) return DEPSYNC_EINVAL;   // a wave needs whole gate/up pairs of 32-column blocks
+    // a K step of the next stage (64 columns of the intermediate) must not straddle two producer
+    // tiles: the per-tile waits are issued per producer column tile as the K loop reaches it
+    if (gate_up && (ts->cols / 2) % 64) return DEPSYNC_EINVAL;
 
     std::memset(&p, 0, sizeof(p));
     const int last = attn ? 2 : 1;
@@ -380,7 +402,6 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
         off += p.sem_count[s];
     }
     p.n_sems = off;
-    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * ts->occupancy;
     // split along K where a stage is much smaller than the chip (not the prompt-phase attention stage)
     p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.slots, d->K1 / 64, 1);
@@ -494,7 +515,6 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
         }
         p.n_sems += p.sem_count[s];
     }
-    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.slots, 9u * d->C / 64, 1);
     for (int s = 1; s < n; ++s) {
         uint32_t seg = 1;                                   // CONV_ROW: the whole halo is waited for by every part
@@ -546,7 +566,6 @@ int plan_copy(const depsync_copy_chain_desc* d, const sync_policy* pol, int n_cu
     p.sem_count[1] = row ? 1u : tiles;
     p.sem_value[1] = row ? tiles : 1u;
     p.n_sems = p.sem_count[1];
-    if (p.n_sems > WS_MAX_SEMS) return DEPSYNC_ENOMEM;
     p.slots = cus * 8;                     // 256 threads, no LDS to speak of: eight workgroups per CU
     p.flops = 0.0;
     p.bytes = 4.0 * (double)d->bytes;      // each stage reads the buffer once and writes it once
@@ -599,6 +618,13 @@ int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t*
         // zero the dispatch counter and every semaphore the previous geometry may have touched
         hipError_t e = launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, stream);
         if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, stream);
+        if (e == hipSuccess && pol->need_reset) {
+            // a chain gave up a wait: tiles it skipped may have left arrival counts behind, and
+            // the status block still shows its time-out
+            e = launch_fill_u32(pol->ws + pol->lay.arrive, 0u, pol->lay.max_arrive * SYNC_WORD_STRIDE, stream);
+            if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, stream);
+            if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_STATUS + 1, 0xffffffffu, 1, stream);   // first_timeout = -1
+        }
         if (e != hipSuccess) return hip_fail(e);
         pol->epoch = 0;
         pol->queue_epoch = 0;
@@ -611,9 +637,19 @@ int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t*
     return DEPSYNC_OK;
 }
 
+// Does the chain fit the policy's workspace?
+int check_limits(const sync_policy* pol, const Plan& p) {
+    const WsLayout& l = pol ? pol->lay : HEAP_LAYOUT;
+    const bool fixed = pol && pol->fixed_scratch;
+    if (p.n_sems > l.max_sems || p.n_arrive > l.max_arrive) return fixed ? DEPSYNC_ELIMIT : DEPSYNC_ENOMEM;
+    if (fixed && p.partial_floats > pol->scratch_floats) return DEPSYNC_ELIMIT;
+    return DEPSYNC_OK;
+}
+
 // Make the policy's scratch buffer large enough for the chain's split-K partial tiles.
 int ensure_scratch(sync_policy* pol, const Plan& p) {
     if (p.partial_floats <= pol->scratch_floats) return DEPSYNC_OK;
+    if (pol->fixed_scratch) return DEPSYNC_ELIMIT;   // a fixed part of the static array: never grown
     HIP_TRY(hipDeviceSynchronize());               // earlier chains may still use the old buffer
     if (pol->scratch) (void)hipFree(pol->scratch);
     pol->scratch = nullptr;
@@ -624,6 +660,30 @@ int ensure_scratch(sync_policy* pol, const Plan& p) {
     pol->scratch = buf;
     pol->scratch_floats = p.partial_floats;
     return DEPSYNC_OK;
+}
+
+// Grid, split and dependency geometry of stage s (everything the index arithmetic of
+// dep_map.hpp reads); pointers and epoch-dependent values are filled in by fill_common.
+void fill_stage_geometry(StageDesc& st, const Plan& p, int s) {
+    st.grid_x = p.grid_x[s];
+    st.grid_y = p.grid_y[s];
+    st.queue_by_col = p.grid_x[s] >= 8 ? 1u : 0u;
+    st.ksplit = p.ksplit[s];
+    st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
+    if (s > 0) {
+        st.sem_value = p.sem_value[s];
+        st.prod_tm = p.out_tm[s - 1];
+        st.prod_tn = p.out_tn[s - 1];
+        st.prod_grid_x = p.grid_x[s - 1];
+        st.prod_grid_y = p.grid_y[s - 1];
+        st.stride = p.stride[s];
+    }
+    if (s + 1 < p.n_stages) {
+        st.post_kind = p.dep_kind[s + 1];
+        st.post_stride = p.stride[s + 1];
+    } else {
+        st.post_kind = DEP_NONE;
+    }
 }
 
 void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) {
@@ -645,35 +705,19 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
     a.delay_tile = pol->params.delay_tile;
     a.delay_iters = pol->params.delay_iters;
     a.status = reinterpret_cast<StatusBlock*>(pol->ws + WS_STATUS);
-    a.trace = reinterpret_cast<TraceRec*>(pol->ws + WS_TRACE);
-    a.trace_cap = WS_TRACE_CAP;
+    a.trace = pol->lay.trace_cap ? reinterpret_cast<TraceRec*>(pol->ws + pol->lay.trace) : nullptr;
+    a.trace_cap = pol->lay.trace_cap;
     for (int s = 0; s < p.n_stages; ++s) {
         StageDesc& st = a.st[s];
-        st.grid_x = p.grid_x[s];
-        st.grid_y = p.grid_y[s];
-        st.queue_by_col = p.grid_x[s] >= 8 ? 1u : 0u;
-        st.ksplit = p.ksplit[s];
+        fill_stage_geometry(st, p, s);
         st.partials = pol->scratch ? pol->scratch + p.partial_off[s] : nullptr;
-        st.arrive = pol->ws + WS_ARRIVE + p.arrive_off[s] * SYNC_WORD_STRIDE;
+        st.arrive = pol->ws + pol->lay.arrive + p.arrive_off[s] * SYNC_WORD_STRIDE;
         st.zero_page = pol->ws + WS_ZERO_PAGE;
-        st.dep_kind = s > 0 ? p.dep_kind[s] : DEP_NONE;
         if (s > 0) {
             st.sems = pol->ws + WS_SEMS + p.sem_off[s] * SYNC_WORD_STRIDE;
-            st.sem_value = p.sem_value[s];
             st.sem_target_base = epoch * p.sem_value[s];
-            st.prod_tm = p.out_tm[s - 1];
-            st.prod_tn = p.out_tn[s - 1];
-            st.prod_grid_x = p.grid_x[s - 1];
-            st.prod_grid_y = p.grid_y[s - 1];
-            st.stride = p.stride[s];
         }
-        if (s + 1 < p.n_stages) {
-            st.post_kind = p.dep_kind[s + 1];
-            st.post_sems = pol->ws + WS_SEMS + p.sem_off[s + 1] * SYNC_WORD_STRIDE;
-            st.post_stride = p.stride[s + 1];
-        } else {
-            st.post_kind = DEP_NONE;
-        }
+        if (s + 1 < p.n_stages) st.post_sems = pol->ws + WS_SEMS + p.sem_off[s + 1] * SYNC_WORD_STRIDE;
     }
 }
 
@@ -747,6 +791,78 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     return DEPSYNC_OK;
 }
 
+
+// Operand pointers, shapes and epilogues of a GeMM chain's stages (what does not depend on the plan).
+void fill_gemm_stages(ChainArgs& a, const depsync_gemm_chain_desc* d) {
+    const bool gate_up = d->mid == DEPSYNC_MID_SWIGLU;
+    StageDesc& s0 = a.st[0];
+    s0.A = d->X; s0.B = d->W1t; s0.C = d->H;
+    s0.M = d->M; s0.N = d->N1; s0.K = d->K1;
+    s0.lda = (uint32_t)d->ldx; s0.ldb = (uint32_t)d->ldw1; s0.ldc = (uint32_t)d->ldh;
+    const bool kblocked = d->w_layout == DEPSYNC_W_KBLOCKED;
+    s0.b_row_bytes = kblocked ? 128u : 2u * (uint32_t)d->ldw1;
+    s0.b_kstep_bytes = kblocked ? 128u * (uint32_t)(gate_up ? 2 * d->N1 : d->N1) : 128u;
+    s0.op = OP_GEMM; s0.amode = A_DENSE; s0.bmode = gate_up ? B_GATE_UP : B_DENSE;
+    s0.act = d->mid == DEPSYNC_MID_GELU ? ACT_GELU : d->mid == DEPSYNC_MID_RELU ? ACT_RELU
+             : gate_up ? ACT_SWIGLU : ACT_NONE;
+    const bool attn = d->mid == DEPSYNC_MID_CAUSAL_ATTN;
+    if (attn) {
+        StageDesc& sa = a.st[1];
+        sa.A = d->H; sa.C = d->T;
+        sa.M = d->M; sa.N = d->heads * 128; sa.K = 128;
+        sa.lda = (uint32_t)d->ldh; sa.ldc = (uint32_t)d->ldt;
+        sa.op = OP_ATTN; sa.amode = A_DENSE; sa.bmode = B_DENSE; sa.act = ACT_NONE;
+        sa.batch = d->batch; sa.seq = d->seq; sa.heads = d->heads; sa.head_dim = 128;
+        sa.kcache = d->cached > 0 ? d->k_cache : nullptr; sa.vcache = d->cached > 0 ? d->v_cache : nullptr;
+        sa.cached = (uint32_t)d->cached; sa.ld_cache = (uint32_t)d->ld_cache;
+    }
+    StageDesc& s1 = a.st[attn ? 2 : 1];
+    s1.A = attn ? d->T : d->H; s1.B = d->W2t; s1.C = d->Y;
+    s1.M = d->M; s1.N = d->N2; s1.K = attn ? d->heads * 128 : d->N1;
+    s1.lda = (uint32_t)(attn ? d->ldt : d->ldh); s1.ldb = (uint32_t)d->ldw2; s1.ldc = (uint32_t)d->ldy;
+    s1.b_row_bytes = kblocked ? 128u : 2u * (uint32_t)d->ldw2;
+    s1.b_kstep_bytes = kblocked ? 128u * (uint32_t)d->N2 : 128u;
+    s1.op = OP_GEMM; s1.amode = A_DENSE; s1.bmode = B_DENSE; s1.act = ACT_NONE;
+}
+
+void fill_conv_stages(ChainArgs& a, const depsync_conv_chain_n_desc* d) {
+    const uint32_t M = (uint32_t)d->B * d->H * d->W;
+    for (int i = 0; i < d->n; ++i) {
+        const uint32_t cin = i == 0 ? (uint32_t)d->C : (uint32_t)d->K[i - 1];
+        StageDesc& st = a.st[i];
+        st.A = i == 0 ? d->in : d->out[i - 1]; st.B = d->w[i]; st.C = d->out[i];
+        st.M = M; st.N = d->K[i]; st.K = 9u * cin;
+        st.lda = cin; st.ldb = 9u * cin; st.ldc = d->K[i];
+        st.b_row_bytes = 18u * cin; st.b_kstep_bytes = 128u;
+        st.op = OP_GEMM; st.amode = A_CONV3X3; st.bmode = B_DENSE;
+        st.act = i == d->n - 1 ? ACT_NONE : ACT_RELU;
+        st.H = d->H; st.W = d->W; st.Cin = cin;
+    }
+}
+
+int gemm_chain_impl(const depsync_gemm_chain_desc* d, sync_policy* pol, depsync_mode mode, void* stream_producer,
+                    void* stream_consumer) {
+    if (!pol) return DEPSYNC_EINVAL;
+    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN &&
+        mode != DEPSYNC_MODE_FUSED)
+        return DEPSYNC_EINVAL;
+    Plan p;
+    int rc = plan_gemm(d, pol, 0, p);
+    if (rc == DEPSYNC_OK) rc = check_limits(pol, p);
+    if (rc != DEPSYNC_OK) return rc;
+    uint32_t epoch = 0;
+    if (mode != DEPSYNC_MODE_PLAIN) {
+        rc = prepare_epoch(pol, p, static_cast<hipStream_t>(stream_producer), &epoch);
+        if (rc != DEPSYNC_OK) return rc;
+    }
+    ChainArgs a;
+    std::memset(&a, 0, sizeof(a));
+    fill_gemm_stages(a, d);
+    if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
+    fill_common(a, pol, p, epoch);
+    return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
+}
+
 }  // namespace
 
 extern "C" {
@@ -760,9 +876,9 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
     p->kind = kind;
     if (params) p->params = *params; else std::memset(&p->params, 0, sizeof(p->params));
     hipError_t e = hipGetDevice(&p->device);
-    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->ws), WS_WORDS * sizeof(uint32_t));
+    if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&p->ws), HEAP_LAYOUT.words * sizeof(uint32_t));
     if (e != hipSuccess) { delete p; return e == hipErrorOutOfMemory ? DEPSYNC_ENOMEM : hip_fail(e); }
-    e = hipMemset(p->ws, 0, WS_WORDS * sizeof(uint32_t));
+    e = hipMemset(p->ws, 0, HEAP_LAYOUT.words * sizeof(uint32_t));
     if (e == hipSuccess) {
         StatusBlock sb{};
         sb.first_timeout = -1;
@@ -785,6 +901,8 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
     p->scratch = nullptr;
     p->scratch_floats = 0;
     p->need_reset = false;
+    p->lay = HEAP_LAYOUT;
+    p->fixed_scratch = false;
     *out = p;
     return DEPSYNC_OK;
 }
@@ -809,7 +927,7 @@ int dep_chain_reset(sync_policy_t* pol, void* stream) {
     if (!pol) return DEPSYNC_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, st));
-    HIP_TRY(launch_fill_u32(pol->ws + WS_ARRIVE, 0u, WS_MAX_ARRIVE * SYNC_WORD_STRIDE, st));
+    HIP_TRY(launch_fill_u32(pol->ws + pol->lay.arrive, 0u, pol->lay.max_arrive * SYNC_WORD_STRIDE, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS + 1, 0xffffffffu, 1, st));   // first_timeout = -1
     HIP_TRY(launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, st));
@@ -840,8 +958,9 @@ int depsync_read_trace(sync_policy_t* pol, depsync_trace_rec* out, int max_recor
     if (!pol || !out || max_records < 0) return DEPSYNC_EINVAL;
     static_assert(sizeof(depsync_trace_rec) == sizeof(TraceRec), "trace record layout");
     HIP_TRY(hipDeviceSynchronize());
-    const size_t n = std::min<size_t>((size_t)max_records, WS_TRACE_CAP);
-    HIP_TRY(hipMemcpy(out, pol->ws + WS_TRACE, n * sizeof(TraceRec), hipMemcpyDeviceToHost));
+    const size_t n = std::min<size_t>((size_t)max_records, pol->lay.trace_cap);
+    if (n == 0) return 0;
+    HIP_TRY(hipMemcpy(out, pol->ws + pol->lay.trace, n * sizeof(TraceRec), hipMemcpyDeviceToHost));
     return (int)n;
 }
 
@@ -850,6 +969,7 @@ int depsync_gemm_chain_plan(const depsync_gemm_chain_desc* d, const sync_policy_
     if (!out) return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_gemm(d, pol, n_cu, p);
+    if (rc == DEPSYNC_OK) rc = check_limits(pol, p);
     if (rc != DEPSYNC_OK) return rc;
     fill_plan_info(p, out);
     return DEPSYNC_OK;
@@ -860,6 +980,7 @@ int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_
     if (!out) return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_conv(d, pol, n_cu, p);
+    if (rc == DEPSYNC_OK) rc = check_limits(pol, p);
     if (rc != DEPSYNC_OK) return rc;
     fill_plan_info(p, out);
     return DEPSYNC_OK;
@@ -867,52 +988,7 @@ int depsync_conv_chain_plan(const depsync_conv_chain_desc* d, const sync_policy_
 
 int dep_gemm_chain(const depsync_gemm_chain_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
                    void* stream_consumer) {
-    if (!pol) return DEPSYNC_EINVAL;
-    if (mode != DEPSYNC_MODE_FINE && mode != DEPSYNC_MODE_STREAMSYNC && mode != DEPSYNC_MODE_PLAIN &&
-        mode != DEPSYNC_MODE_FUSED)
-        return DEPSYNC_EINVAL;
-    Plan p;
-    int rc = plan_gemm(d, pol, 0, p);
-    if (rc != DEPSYNC_OK) return rc;
-    uint32_t epoch = 0;
-    if (mode != DEPSYNC_MODE_PLAIN) {
-        rc = prepare_epoch(pol, p, static_cast<hipStream_t>(stream_producer), &epoch);
-        if (rc != DEPSYNC_OK) return rc;
-    }
-    ChainArgs a;
-    std::memset(&a, 0, sizeof(a));
-    const bool gate_up = d->mid == DEPSYNC_MID_SWIGLU;
-    StageDesc& s0 = a.st[0];
-    s0.A = d->X; s0.B = d->W1t; s0.C = d->H;
-    s0.M = d->M; s0.N = d->N1; s0.K = d->K1;
-    s0.lda = (uint32_t)d->ldx; s0.ldb = (uint32_t)d->ldw1; s0.ldc = (uint32_t)d->ldh;
-    const bool kblocked = d->w_layout == DEPSYNC_W_KBLOCKED;
-    s0.b_row_bytes = kblocked ? 128u : 2u * (uint32_t)d->ldw1;
-    s0.b_kstep_bytes = kblocked ? 128u * (uint32_t)(gate_up ? 2 * d->N1 : d->N1) : 128u;
-    s0.op = OP_GEMM; s0.amode = A_DENSE; s0.bmode = gate_up ? B_GATE_UP : B_DENSE;
-    s0.act = d->mid == DEPSYNC_MID_GELU ? ACT_GELU : d->mid == DEPSYNC_MID_RELU ? ACT_RELU
-             : gate_up ? ACT_SWIGLU : ACT_NONE;
-    const bool attn = d->mid == DEPSYNC_MID_CAUSAL_ATTN;
-    if (attn) {
-        StageDesc& sa = a.st[1];
-        sa.A = d->H; sa.C = d->T;
-        sa.M = d->M; sa.N = d->heads * 128; sa.K = 128;
-        sa.lda = (uint32_t)d->ldh; sa.ldc = (uint32_t)d->ldt;
-        sa.op = OP_ATTN; sa.amode = A_DENSE; sa.bmode = B_DENSE; sa.act = ACT_NONE;
-        sa.batch = d->batch; sa.seq = d->seq; sa.heads = d->heads; sa.head_dim = 128;
-        sa.kcache = d->cached > 0 ? d->k_cache : nullptr; sa.vcache = d->cached > 0 ? d->v_cache : nullptr;
-        sa.cached = (uint32_t)d->cached; sa.ld_cache = (uint32_t)d->ld_cache;
-    }
-    StageDesc& s1 = a.st[attn ? 2 : 1];
-    s1.A = attn ? d->T : d->H; s1.B = d->W2t; s1.C = d->Y;
-    s1.M = d->M; s1.N = d->N2; s1.K = attn ? d->heads * 128 : d->N1;
-    s1.lda = (uint32_t)(attn ? d->ldt : d->ldh); s1.ldb = (uint32_t)d->ldw2; s1.ldc = (uint32_t)d->ldy;
-    s1.b_row_bytes = kblocked ? 128u : 2u * (uint32_t)d->ldw2;
-    s1.b_kstep_bytes = kblocked ? 128u * (uint32_t)d->N2 : 128u;
-    s1.op = OP_GEMM; s1.amode = A_DENSE; s1.bmode = B_DENSE; s1.act = ACT_NONE;
-    if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
-    fill_common(a, pol, p, epoch);
-    return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
+    return gemm_chain_impl(d, pol, mode, stream_producer, stream_consumer);
 }
 
 int dep_conv_chain_n(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, depsync_mode mode, void* stream_producer,
@@ -923,6 +999,7 @@ int dep_conv_chain_n(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, dep
         return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_conv_n(d, pol, 0, p);
+    if (rc == DEPSYNC_OK) rc = check_limits(pol, p);
     if (rc != DEPSYNC_OK) return rc;
     uint32_t epoch = 0;
     if (mode != DEPSYNC_MODE_PLAIN) {
@@ -931,18 +1008,7 @@ int dep_conv_chain_n(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, dep
     }
     ChainArgs a;
     std::memset(&a, 0, sizeof(a));
-    const uint32_t M = (uint32_t)d->B * d->H * d->W;
-    for (int i = 0; i < d->n; ++i) {
-        const uint32_t cin = i == 0 ? (uint32_t)d->C : (uint32_t)d->K[i - 1];
-        StageDesc& st = a.st[i];
-        st.A = i == 0 ? d->in : d->out[i - 1]; st.B = d->w[i]; st.C = d->out[i];
-        st.M = M; st.N = d->K[i]; st.K = 9u * cin;
-        st.lda = cin; st.ldb = 9u * cin; st.ldc = d->K[i];
-        st.b_row_bytes = 18u * cin; st.b_kstep_bytes = 128u;
-        st.op = OP_GEMM; st.amode = A_CONV3X3; st.bmode = B_DENSE;
-        st.act = i == d->n - 1 ? ACT_NONE : ACT_RELU;
-        st.H = d->H; st.W = d->W; st.Cin = cin;
-    }
+    fill_conv_stages(a, d);
     if (int rs = ensure_scratch(pol, p); rs != DEPSYNC_OK) return rs;
     fill_common(a, pol, p, epoch);
     return launch_chain(pol, p, a, mode, stream_producer, stream_consumer);
@@ -959,6 +1025,7 @@ int depsync_conv_chain_n_plan(const depsync_conv_chain_n_desc* d, const sync_pol
     if (!out) return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_conv_n(d, pol, n_cu, p);
+    if (rc == DEPSYNC_OK) rc = check_limits(pol, p);
     if (rc != DEPSYNC_OK) return rc;
     fill_plan_info(p, out);
     return DEPSYNC_OK;
@@ -968,6 +1035,7 @@ int depsync_copy_chain_plan(const depsync_copy_chain_desc* d, const sync_policy_
     if (!out) return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_copy(d, pol, n_cu, p);
+    if (rc == DEPSYNC_OK) rc = check_limits(pol, p);
     if (rc != DEPSYNC_OK) return rc;
     fill_plan_info(p, out);
     return DEPSYNC_OK;
@@ -981,6 +1049,7 @@ int dep_copy_chain(const depsync_copy_chain_desc* d, sync_policy_t* pol, depsync
         return DEPSYNC_EINVAL;
     Plan p;
     int rc = plan_copy(d, pol, 0, p);
+    if (rc == DEPSYNC_OK) rc = check_limits(pol, p);
     if (rc != DEPSYNC_OK) return rc;
     uint32_t epoch = 0;
     if (mode != DEPSYNC_MODE_PLAIN) {
@@ -1130,6 +1199,7 @@ const char* depsync_strerror(int status) {
         case DEPSYNC_EHIP: return "a HIP call failed (see depsync_last_hip_error)";
         case DEPSYNC_ETIMEOUT: return "a bounded semaphore wait expired";
         case DEPSYNC_ENOTIMPL: return "not implemented in this build";
+        case DEPSYNC_ELIMIT: return "the chain needs more semaphores, arrival counters or split-K scratch than the fixed static workspace holds";
         default: return "unknown status";
     }
 }
@@ -1194,7 +1264,7 @@ int depsync_mfma_calibration(int zero_operands, int milliseconds, double* tflops
     return rc;
 }
 
-size_t depsync_workspace_bytes(void) { return (size_t)WS_WORDS * sizeof(uint32_t); }
+size_t depsync_workspace_bytes(void) { return (size_t)HEAP_LAYOUT.words * sizeof(uint32_t); }
 
 int depsync_device_info(int* n_cu, int* clock_khz) {
     if (!n_cu || !clock_khz) return DEPSYNC_EINVAL;
@@ -1202,6 +1272,109 @@ int depsync_device_info(int* n_cu, int* clock_khz) {
     HIP_TRY(hipGetDevice(&dev));
     HIP_TRY(hipDeviceGetAttribute(n_cu, hipDeviceAttributeMultiprocessorCount, dev));
     HIP_TRY(hipDeviceGetAttribute(clock_khz, hipDeviceAttributeClockRate, dev));
+    return DEPSYNC_OK;
+}
+
+}  // extern "C"
+
+namespace {
+
+// Consumer tiles (row tile, K part) of stage s whose operand slices are not all covered by a
+// wait issued at or before the K step that loads them.
+int64_t uncovered_waits(const Plan& p, const ChainArgs& a, int s) {
+    const StageDesc& st = a.st[s];
+    const TileShape* ts = tile_shape(p.tile[s]);
+    if (!ts || st.dep_kind == DEP_NONE || st.op != OP_GEMM) return 0;
+    const uint32_t TM = (uint32_t)ts->rows;
+    const uint32_t KT = st.K / 64, S = st.ksplit;
+    const uint32_t seg_steps = dep_seg_steps(st);
+    int64_t bad = 0;
+    std::vector<uint8_t> waited(p.sem_count[s]);
+    for (uint32_t ty = 0; ty < st.grid_y; ++ty) {
+        const uint32_t m0 = ty * TM, m_last = std::min(m0 + TM, st.M) - 1;
+        for (uint32_t kz = 0; kz < S; ++kz) {
+            std::fill(waited.begin(), waited.end(), 0);
+            const uint32_t kb = kz * (KT / S), ke = kb + KT / S;
+            uint32_t seg_next = kb;
+            bool ok = true;
+            for (uint32_t k = kb; k < ke && ok; ++k) {
+                if (k == seg_next) {
+                    seg_next = seg_steps ? seg_next + seg_steps : 0xffffffffu;
+                    DepRange r;
+                    if (dep_segment(st, m0, TM, k, kb, r))
+                        for (uint32_t y = r.y0; y <= r.y1; ++y) waited[policy_sem(st.dep_kind, r.x, y, st.prod_grid_y, st.stride)] = 1;
+                }
+                // producer tiles whose output this K step's slice of A is read from
+                const uint32_t k0 = k * 64;
+                auto need = [&](uint32_t row, uint32_t col) {
+                    const uint32_t x = col / st.prod_tn, y = row / st.prod_tm;
+                    if (x >= st.prod_grid_x || y >= st.prod_grid_y || !waited[policy_sem(st.dep_kind, x, y, st.prod_grid_y, st.stride)]) ok = false;
+                };
+                if (st.amode == A_CONV3X3) {
+                    const uint32_t tap = k0 / st.Cin, c0 = k0 % st.Cin;
+                    const int fr = (int)(tap / 3) - 1, fs = (int)(tap % 3) - 1;
+                    for (uint32_t m = m0; m <= m_last; ++m) {
+                        const uint32_t rem = m % (st.H * st.W);
+                        const int y = (int)(rem / st.W) + fr, x = (int)(rem % st.W) + fs;
+                        if (y < 0 || y >= (int)st.H || x < 0 || x >= (int)st.W) continue;   // padding: nothing is read
+                        const uint32_t row = (uint32_t)((int)m + fr * (int)st.W + fs);
+                        need(row, c0); need(row, c0 + 63);
+                    }
+                } else {
+                    need(m0, k0); need(m0, k0 + 63); need(m_last, k0); need(m_last, k0 + 63);
+                    for (uint32_t y = m0 / st.prod_tm; y <= m_last / st.prod_tm; ++y) need(y * st.prod_tm, k0);
+                }
+            }
+            if (!ok) ++bad;
+        }
+    }
+    return bad;
+}
+
+// A policy object that exists on the host only (kind and parameters for the planner).
+sync_policy host_policy(int kind, const depsync_policy_params* params) {
+    sync_policy hp;
+    std::memset(&hp, 0, sizeof(hp));
+    hp.kind = kind;
+    if (params) hp.params = *params;
+    hp.lay = HEAP_LAYOUT;
+    hp.force_order = -1;
+    return hp;
+}
+
+bool valid_kind(int kind) { return kind == DEPSYNC_ROWSYNC || kind == DEPSYNC_TILESYNC || kind == DEPSYNC_STRIDEDSYNC; }
+
+}  // namespace
+
+extern "C" {
+
+int depsync_gemm_chain_check_waits(const depsync_gemm_chain_desc* d, depsync_policy_kind kind,
+                                   const depsync_policy_params* params, int n_cu, int64_t* uncovered) {
+    if (!uncovered || !valid_kind(kind)) return DEPSYNC_EINVAL;
+    const sync_policy hp = host_policy(kind, params);
+    Plan p;
+    if (int rc = plan_gemm(d, &hp, n_cu, p); rc != DEPSYNC_OK) return rc;
+    ChainArgs a;
+    std::memset(&a, 0, sizeof(a));
+    fill_gemm_stages(a, d);
+    for (int s = 0; s < p.n_stages; ++s) fill_stage_geometry(a.st[s], p, s);
+    *uncovered = 0;
+    for (int s = 1; s < p.n_stages; ++s) *uncovered += uncovered_waits(p, a, s);
+    return DEPSYNC_OK;
+}
+
+int depsync_conv_chain_n_check_waits(const depsync_conv_chain_n_desc* d, depsync_policy_kind kind,
+                                     const depsync_policy_params* params, int n_cu, int64_t* uncovered) {
+    if (!uncovered || !valid_kind(kind)) return DEPSYNC_EINVAL;
+    const sync_policy hp = host_policy(kind, params);
+    Plan p;
+    if (int rc = plan_conv_n(d, &hp, n_cu, p); rc != DEPSYNC_OK) return rc;
+    ChainArgs a;
+    std::memset(&a, 0, sizeof(a));
+    fill_conv_stages(a, d);
+    for (int s = 0; s < p.n_stages; ++s) fill_stage_geometry(a.st[s], p, s);
+    *uncovered = 0;
+    for (int s = 1; s < p.n_stages; ++s) *uncovered += uncovered_waits(p, a, s);
     return DEPSYNC_OK;
 }
 

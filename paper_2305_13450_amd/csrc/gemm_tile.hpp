@@ -16,6 +16,7 @@
 #include <type_traits>
 
 #include "chain_args.h"
+#include "dep_map.hpp"
 #include "sync_device.hpp"
 
 namespace depsync {
@@ -112,61 +113,6 @@ __device__ __forceinline__ float gelu_erf(float x) {
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
 // ---- dependency bookkeeping of a consumer tile -------------------------------------------
-
-// Range of producer row tiles and the producer column tile a K step depends on.
-struct DepRange {
-    uint32_t y0, y1;   // inclusive producer row-tile range
-    uint32_t x;        // producer column tile (TILE / STRIDED kinds)
-};
-
-// Does the A slice of K step kt start a new dependency segment, and on what?
-// kb: first K step of this workgroup's K range (0 unless the stage is split along K).
-__device__ __forceinline__ bool dep_segment(const StageDesc& s, uint32_t m0, uint32_t tm, uint32_t kt, uint32_t kb, DepRange& r) {
-    const uint32_t m_last = min(m0 + tm, s.M) - 1;
-    switch (s.dep_kind) {
-        case DEP_ROW:
-            if (kt != kb) return false;
-            r.y0 = m0 / s.prod_tm; r.y1 = m_last / s.prod_tm; r.x = 0;
-            return true;
-        case DEP_TILE:
-        case DEP_STRIDED: {
-            const uint32_t k0 = kt * 64;
-            if (k0 % s.prod_tn != 0) return false;
-            r.x = k0 / s.prod_tn;
-            // same semaphore as x - stride, which this workgroup has already waited for if that
-            // segment lies inside its K range
-            if (s.dep_kind == DEP_STRIDED && r.x >= s.stride && (r.x - s.stride) * (s.prod_tn / 64) >= kb) return false;
-            r.y0 = m0 / s.prod_tm; r.y1 = m_last / s.prod_tm;
-            return true;
-        }
-        case DEP_CONV_ROW: {
-            if (kt != kb) return false;
-            const int lo = (int)m0 - (int)s.W - 1, hi = (int)m_last + (int)s.W + 1;
-            r.y0 = (uint32_t)max(lo, 0) / s.prod_tm;
-            r.y1 = (uint32_t)min(hi, (int)s.M - 1) / s.prod_tm; r.x = 0;
-            return true;
-        }
-        case DEP_CONV_TAPROW:
-        case DEP_CONV_TILE: {
-            // K runs filter-row major: k = ((fr*3 + fs) * Cin + c).  A new segment starts with
-            // every filter row (TAPROW) or every producer channel tile of a filter row's first tap (TILE).
-            const uint32_t k0 = kt * 64;
-            const uint32_t tap = k0 / s.Cin, c0 = k0 % s.Cin;
-            const uint32_t fr = tap / 3, fs = tap % 3;
-            if (fs != 0) return false;
-            if (s.dep_kind == DEP_CONV_TAPROW) { if (c0 != 0) return false; r.x = 0; }
-            else { if (c0 % s.prod_tn != 0) return false; r.x = c0 / s.prod_tn; }
-            const int sh = ((int)fr - 1) * (int)s.W;
-            const int lo = (int)m0 + sh - 1, hi = (int)m_last + sh + 1;
-            if (hi < 0 || lo > (int)s.M - 1) return false;      // whole filter row is padding
-            r.y0 = (uint32_t)max(lo, 0) / s.prod_tm;
-            r.y1 = (uint32_t)min(hi, (int)s.M - 1) / s.prod_tm;
-            return true;
-        }
-        default:
-            return false;
-    }
-}
 
 // Wait for the semaphores of one dependency segment.  Acquire ordering without a cache
 // invalidate: the semaphore reads are agent-scope atomic loads whose values this wave branches
@@ -333,20 +279,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
 
     // Dependency segments start at multiples of seg_steps K steps (0: only at step 0).
     uint32_t seg_steps = 0, seg_next = kb;   // the host makes K ranges start on segment boundaries
-    if constexpr (DEP) {
-        switch (s.dep_kind) {
-            case DEP_TILE: case DEP_STRIDED: seg_steps = s.prod_tn / 64; break;
-            case DEP_CONV_TAPROW: seg_steps = 3 * cCin / 64; break;
-            case DEP_CONV_TILE: {   // starts of filter rows and of producer channel tiles inside them
-                uint32_t a = 3 * cCin / 64, b = s.prod_tn / 64;
-                while (b != 0) { const uint32_t r = a % b; a = b; b = r; }
-                seg_steps = a;
-                break;
-            }
-            default: seg_steps = 0; break;
-        }
-        seg_steps = uni(seg_steps);
-    }
+    if constexpr (DEP) seg_steps = uni(dep_seg_steps(s));
     // Called before the A slice of K step k (< KT) is requested into `stage`: if a dependency
     // segment starts there, make sure its producer tiles have posted.  The semaphores are looked
     // at 64 segments at a time (lane l tests the segment l places ahead, one load instruction

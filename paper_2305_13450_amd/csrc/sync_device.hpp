@@ -19,6 +19,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include "chain_args.h"
+#include "dep_map.hpp"
 
 namespace depsync {
 
@@ -92,23 +93,6 @@ __device__ __forceinline__ void count_wait(const ChainArgs& a, bool polled) {
         __hip_atomic_fetch_add(&a.status->waits, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (polled)
             __hip_atomic_fetch_add(&a.status->polling_waits, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-}
-
-// Semaphore a producer tile (x,y) posts to / a consumer looks at, per policy (Fig. 4b):
-//   row:     sem = y                      value = grid_x
-//   tile:    sem = x*grid_y + y           value = 1
-//   strided: sem = y*stride + x % stride  value = grid_x / stride
-__device__ __forceinline__ uint32_t policy_sem(uint32_t kind, uint32_t x, uint32_t y, uint32_t grid_y, uint32_t stride) {
-    switch (kind) {
-        case DEP_TILE:
-        case DEP_CONV_TILE:
-            return x * grid_y + y;
-        case DEP_STRIDED:
-        case DEP_ATTN_QKV:
-            return y * stride + (x % stride);
-        default:
-            return y;
     }
 }
 

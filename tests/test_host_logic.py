@@ -183,6 +183,76 @@ def test_planner_splits_small_stages_along_k_on_segment_boundaries():
     assert info.n_prod == 32 * 4 and info.n_cons == 32 * 3      # first conv: four parts of 18 steps; second: filter rows
 
 
+def _fake_conv_n_desc(B, H, W, C, Ks, tile=0):
+    d = ds.ConvChainNDesc()
+    d.B, d.H, d.W, d.C, d.n, d.dtype = B, H, W, C, len(Ks), ds.BF16
+    d.inp = 0x1000
+    for i, k in enumerate(Ks):
+        d.K[i], d.w[i], d.out[i] = k, 0x1000, 0x1000
+    d.tile_prod = d.tile_cons = tile
+    return d
+
+
+ALL_TILES = list(range(1, ds.TILE_128x128_DEEP + 1))
+
+
+@pytest.mark.parametrize("kind", [ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC])
+def test_every_slice_a_consumer_tile_loads_is_covered_by_a_wait(kind):
+    # Section III-C: a consumer tile may read a producer tile's output only after waiting for it.
+    # The library's own walk of every consumer K loop (same index functions as the kernel) finds
+    # no K step whose slice of the intermediate lacks a wait at or before it, for every tile shape
+    # it accepts, ragged M, split along K, the gated MLP (producer tiles half as wide) and attention.
+    checked = 0
+    for tile in ALL_TILES:
+        for (M, K1, N1, N2, mid, extra) in (
+                (300, 256, 768, 384, ds.MID_GELU, {}), (64, 12288, 6144, 12288, ds.MID_GELU, {}),
+                (2048, 1024, 6144, 1536, ds.MID_GELU, {}), (200, 512, 1408, 512, ds.MID_SWIGLU, {}),
+                (1, 8192, 2752, 8192, ds.MID_SWIGLU, {}),
+                (512, 256, 3 * 256, 256, ds.MID_CAUSAL_ATTN, dict(batch=2, seq=256, heads=2, head_dim=128))):
+            for ksplit in (0, 1, 2):
+                d = _fake_gemm_desc(M, K1, N1, N2, mid=mid, tile=tile)
+                if mid == ds.MID_CAUSAL_ATTN:
+                    d.T, d.ldt, d.ldw2 = 0x1000, extra["heads"] * 128, extra["heads"] * 128
+                    d.batch, d.seq, d.heads, d.head_dim = extra["batch"], extra["seq"], extra["heads"], 128
+                try:
+                    n = ds.gemm_chain_check_waits(d, kind, n_cu=256, ksplit=ksplit)
+                except ds.DepsyncError as e:
+                    assert e.status in (ds.EINVAL, ds.ENOTIMPL)      # shape the tile or policy cannot run
+                    continue
+                assert n == 0, (tile, M, K1, N1, N2, mid, ksplit)
+                checked += 1
+    assert checked > 100
+
+
+def test_gated_mlp_rejects_tiles_whose_producer_half_is_narrower_than_a_k_step():
+    # 256x64 would leave 32-column producer tiles: a 64-wide K step of the consumer would then
+    # read two producer tiles but wait for one (Section III-C's TileSync semantics broken)
+    d = _fake_gemm_desc(256, 8192, 2752, 8192, mid=ds.MID_SWIGLU, tile=ds.TILE_256x64)
+    info = ds.PlanInfo()
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.EINVAL
+    with pytest.raises(ds.DepsyncError):
+        ds.gemm_chain_check_waits(d, ds.TILESYNC, n_cu=256)
+
+
+@pytest.mark.parametrize("kind", [ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC])
+def test_conv_chain_waits_cover_the_halo(kind):
+    # 3x3 convolution: a consumer row tile reads pixels up to W+1 rows beyond its own rows
+    checked = 0
+    for tile in ALL_TILES:
+        for (B, H, W, C, Ks) in ((1, 14, 14, 512, (512, 512)), (2, 28, 28, 128, (128, 64)), (1, 56, 56, 64, (64, 64, 64)),
+                                 (3, 9, 17, 64, (128, 64, 64, 8)), (16, 14, 14, 64, (64, 64))):
+            for ksplit in (0, 1, 3):
+                d = _fake_conv_n_desc(B, H, W, C, Ks, tile=tile)
+                try:
+                    n = ds.conv_chain_n_check_waits(d, kind, n_cu=256, ksplit=ksplit)
+                except ds.DepsyncError as e:
+                    assert e.status in (ds.EINVAL, ds.ENOTIMPL)
+                    continue
+                assert n == 0, (tile, B, H, W, C, Ks, ksplit)
+                checked += 1
+    assert checked > 100
+
+
 def test_k_blocked_layout_is_validated():
     info = ds.PlanInfo()
     d = _fake_gemm_desc(256, 1024, 4096, 1024)
