@@ -357,6 +357,26 @@ int depsync_gemm_chain_set_tuned(const depsync_gemm_chain_desc* d, const sync_po
 int depsync_conv_chain_set_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int tile, int flags);
 
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  The same chain as dep_gemm_chain in DEPSYNC_MODE_FUSED (one
+ * dispatch on `stream`, per-tile semaphores, bit-identical results for the same policy kind and
+ * parameters), but it needs no sync_policy_t object and calls no hipMalloc / hipFree or any other
+ * allocating routine: dispatch counters, semaphores, arrival counters and the split-K partial tiles
+ * live in one fixed array in device memory that is part of the library's code object (129.5 MiB:
+ * 1.5 MiB for counters and up to 8192 semaphores and 4096 arrival counters, 128 MiB for partial
+ * tiles; every GPU the library runs on holds its own copy until the process ends).  A chain that
+ * needs more than that returns DEPSYNC_ELIMIT and enqueues nothing; params->ksplit = 1 (no split
+ * along K) makes any chain need no partial tiles.  DEPSYNC_FLAG_TRACE is not available here
+ * (DEPSYNC_EINVAL).  `kind` and `params` (nullable) are what sync_policy_create would be given.
+ * The first call on a device looks up the array's device address and enqueues one small fill
+ * kernel before the chain.  All calls on one GPU share that GPU's array, which keeps what the last
+ * call left in it (the library re-zeroes by fill kernels on `stream` whatever must start at zero
+ * when the chain's geometry changes): calls must be enqueued on one stream, or otherwise be ordered
+ * one after the other; chains of this entry point that overlap on one GPU race.  The status of
+ * bounded waits is not readable through this entry point.                                         */
+int dep_gemm_chain_static(const depsync_gemm_chain_desc* d, depsync_policy_kind kind,
+                          const depsync_policy_params* params, void* stream);
+
 /* Host-side check of the wait placement (no device needed; n_cu as for the planners; pointers in
  * `d` are validated but not dereferenced): plans the chain for the given policy kind and
  * parameters, walks every consumer tile's K loop the way the kernel does, and counts in

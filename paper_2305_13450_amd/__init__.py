@@ -34,7 +34,7 @@ EXPORTS = [
     "depsync_gemm_chain_tuned", "depsync_conv_chain_tuned", "depsync_gemm_chain_set_tuned", "depsync_conv_chain_set_tuned",
     "depsync_mfma_calibration", "dep_copy_chain", "depsync_copy_chain_plan",
     "dep_conv_chain_n", "depsync_conv_chain_n_plan", "depsync_conv_chain_n_autotune", "depsync_workspace_bytes",
-    "depsync_gemm_chain_check_waits", "depsync_conv_chain_n_check_waits",
+    "depsync_gemm_chain_check_waits", "depsync_conv_chain_n_check_waits", "dep_gemm_chain_static",
 ]
 
 
@@ -150,6 +150,7 @@ def _lib() -> ctypes.CDLL:
         i64p = ctypes.POINTER(ctypes.c_int64)
         L.depsync_gemm_chain_check_waits.argtypes = [ctypes.POINTER(GemmChainDesc), i32, ctypes.POINTER(PolicyParams), i32, i64p]
         L.depsync_conv_chain_n_check_waits.argtypes = [ctypes.POINTER(ConvChainNDesc), i32, ctypes.POINTER(PolicyParams), i32, i64p]
+        L.dep_gemm_chain_static.argtypes = [ctypes.POINTER(GemmChainDesc), i32, ctypes.POINTER(PolicyParams), vp]
         L.depsync_row_major.argtypes = [i32] * 4
         L.depsync_policy_sem.argtypes = [i32] * 6
         L.depsync_policy_value.argtypes = [i32] * 4
@@ -316,6 +317,17 @@ def dep_gemm_chain(X, W1t, H, W2t, Y, policy: SyncPolicy, mode: int = MODE_FINE,
     d = _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T, batch, seq, heads, head_dim, k_cache, v_cache)
     _check(_lib().dep_gemm_chain(ctypes.byref(d), policy.handle, mode, _stream_handle(stream_producer),
                                  _stream_handle(stream_consumer)), "dep_gemm_chain")
+
+
+def dep_gemm_chain_static(X, W1t, H, W2t, Y, kind: int, mid: int = MID_GELU, tile: int = TILE_AUTO, stream=None,
+                          T=None, batch: int = 0, seq: int = 0, heads: int = 0, head_dim: int = 0,
+                          k_cache=None, v_cache=None, **params) -> None:
+    """The chain in one dispatch on `stream` with the library's fixed device workspace: no policy
+    object, no allocation.  `params`: fields of PolicyParams (flags, ksplit, ...)."""
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T, batch, seq, heads, head_dim, k_cache, v_cache)
+    pp = PolicyParams(**params)
+    _check(_lib().dep_gemm_chain_static(ctypes.byref(d), kind, ctypes.byref(pp), _stream_handle(stream)),
+           "dep_gemm_chain_static")
 
 
 def gemm_chain_plan(X, W1t, H, W2t, Y, policy: Optional[SyncPolicy], mid: int = MID_GELU, tile: int = TILE_AUTO,

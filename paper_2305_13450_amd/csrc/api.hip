@@ -53,6 +53,14 @@ constexpr WsLayout make_layout(uint32_t max_sems, uint32_t trace_cap, uint32_t m
 }
 constexpr WsLayout HEAP_LAYOUT = make_layout(1u << 16, 8192, 1u << 15);
 
+// The allocation-free entry point's workspace: a fixed array in device memory (one copy per GPU
+// that loads the library, held until the process ends).  1.5 MiB of counters, semaphores and
+// arrival counters, then 128 MiB for split-K partial tiles.
+constexpr WsLayout STATIC_LAYOUT = make_layout(8192, 0, 4096);
+constexpr size_t STATIC_PARTIAL_FLOATS = 32u << 20;
+static_assert(STATIC_LAYOUT.words % 64 == 0, "the partial tiles start on a 256-byte boundary");
+constexpr size_t STATIC_WORDS = (size_t)STATIC_LAYOUT.words + STATIC_PARTIAL_FLOATS;
+
 int hip_fail(hipError_t e) {
     g_last_hip_error = (int)e;
     return DEPSYNC_EHIP;
@@ -1277,7 +1285,51 @@ int depsync_device_info(int* n_cu, int* clock_khz) {
 
 }  // extern "C"
 
+// ---- allocation-free entry point -----------------------------------------------------------
+
+// Workspace of dep_gemm_chain_static: dispatch counters, status, zero page, semaphores and
+// arrival counters (STATIC_LAYOUT), then the split-K partial tiles.  In host code this name is
+// only a handle for hipGetSymbolAddress; the device address it returns (one per GPU) is what
+// kernels and fills are given.
+static __device__ __align__(256) uint32_t scratch[STATIC_WORDS];
+
 namespace {
+
+constexpr int STATIC_MAX_DEVICES = 64;
+struct StaticState {
+    sync_policy pol;
+    bool ready;
+};
+StaticState g_static[STATIC_MAX_DEVICES];
+std::mutex g_static_mutex;
+
+// The static policy of the current device, set up on first use (device address of the array,
+// status block).  Called with g_static_mutex held.
+int static_policy(hipStream_t st, sync_policy** out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= STATIC_MAX_DEVICES) return DEPSYNC_EINVAL;
+    StaticState& S = g_static[dev];
+    if (!S.ready) {
+        uint32_t* ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)));
+        if (!ptr || (reinterpret_cast<uintptr_t>(ptr) & 255u)) return DEPSYNC_EHIP;
+        // the array is zero when the library's code is loaded onto the device; only the status
+        // block's "no time-out yet" marker is not zero
+        HIP_TRY(launch_fill_u32(ptr + WS_STATUS + 1, 0xffffffffu, 1, st));
+        std::memset(&S.pol, 0, sizeof(S.pol));
+        S.pol.device = dev;
+        S.pol.ws = ptr;
+        S.pol.lay = STATIC_LAYOUT;
+        S.pol.fixed_scratch = true;
+        S.pol.scratch = reinterpret_cast<float*>(ptr + STATIC_LAYOUT.words);
+        S.pol.scratch_floats = STATIC_PARTIAL_FLOATS;
+        S.pol.force_order = -1;
+        S.ready = true;
+    }
+    *out = &S.pol;
+    return DEPSYNC_OK;
+}
 
 // Consumer tiles (row tile, K part) of stage s whose operand slices are not all covered by a
 // wait issued at or before the K step that loads them.
@@ -1347,6 +1399,18 @@ bool valid_kind(int kind) { return kind == DEPSYNC_ROWSYNC || kind == DEPSYNC_TI
 }  // namespace
 
 extern "C" {
+
+int dep_gemm_chain_static(const depsync_gemm_chain_desc* d, depsync_policy_kind kind, const depsync_policy_params* params,
+                          void* stream) {
+    if (!valid_kind(kind)) return DEPSYNC_EINVAL;
+    if (params && (params->flags & DEPSYNC_FLAG_TRACE)) return DEPSYNC_EINVAL;   // the static workspace has no trace area
+    std::lock_guard<std::mutex> g(g_static_mutex);
+    sync_policy* pol = nullptr;
+    if (int rc = static_policy(static_cast<hipStream_t>(stream), &pol); rc != DEPSYNC_OK) return rc;
+    pol->kind = kind;
+    if (params) pol->params = *params; else std::memset(&pol->params, 0, sizeof(pol->params));
+    return gemm_chain_impl(d, pol, DEPSYNC_MODE_FUSED, stream, nullptr);
+}
 
 int depsync_gemm_chain_check_waits(const depsync_gemm_chain_desc* d, depsync_policy_kind kind,
                                    const depsync_policy_params* params, int n_cu, int64_t* uncovered) {
