@@ -25,22 +25,28 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int TM_, int TN_, int WM_, int WN_, int MINB_, int NSTAGE_>
+template <int TM_, int TN_, int WM_, int WN_, int MINB_, int NSTAGE_, int BK_ = 64, int DBG_ = 0, int NGD_ = 0, int NSTB_ = 0>
 struct TileCfg {
-    static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_, MINB = MINB_;
-    static constexpr int BK = 64;                     // K elements per pipeline step
+    static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_, MINB = MINB_, DBG = DBG_;
+    static constexpr int NGD_OVERRIDE = NGD_;
+    static constexpr int BK = BK_;                    // K elements per pipeline step (64 or 32)
     static constexpr int ROWB = BK * 2;               // bytes per LDS row
-    static constexpr int NSTAGE = NSTAGE_;               // LDS stages: NSTAGE-1 K steps in flight
+    static constexpr int KK = BK / 16;                // 16-wide K slices (one MFMA deep) per step
+    static constexpr int RPD = 1024 / ROWB;           // operand rows one 1 KB DMA instruction fills
+    static constexpr int LPR = ROWB / 16;             // lanes (16-byte chunks) per row
+    static constexpr int NSTAGE = NSTAGE_;               // LDS stages of the A operand: NSTAGE-1 K steps in flight
+    static constexpr int NSTB = NSTB_ ? NSTB_ : NSTAGE_; // LDS stages of the B operand (no more than A's)
     static constexpr int WTM = TM / WM, WTN = TN / WN;  // wave sub-tile
     static constexpr int FM = WTM / 32, FN = WTN / 32;  // 32x32 blocks per wave
-    static constexpr int NIA = TM / 32, NIB = TN / 32;  // 1 KB DMA instructions per wave per step
+    static constexpr int NIA = TM / (4 * RPD), NIB = TN / (4 * RPD);  // 1 KB DMA instructions per wave per step
     static constexpr int A_BYTES = TM * ROWB, B_BYTES = TN * ROWB;
-    static constexpr int STAGE_BYTES = A_BYTES + B_BYTES;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE_BYTES;
+    static constexpr int B_BASE = NSTAGE * A_BYTES;      // the B stages follow the A stages
+    static constexpr int LDS_BYTES = NSTAGE * A_BYTES + NSTB * B_BYTES;
+    static_assert(BK == 64 || BK == 32, "steps of 64 or 32 K elements");
     static_assert(WM * WN == 4, "four waves per workgroup");
-    static_assert(NSTAGE >= 2 && MINB * LDS_BYTES <= 160 * 1024, "stages must fit the 160 KB LDS");
+    static_assert(NSTB >= 2 && NSTAGE >= NSTB && MINB * LDS_BYTES <= 160 * 1024, "stages must fit the 160 KB LDS");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
-    static_assert(TM % 32 == 0 && TN % 32 == 0, "each wave issues whole 8-row DMA groups");
+    static_assert(TM % (4 * RPD) == 0 && TN % (4 * RPD) == 0, "each wave issues whole DMA groups");
 };
 
 template <typename T> struct Mma;
@@ -57,11 +63,17 @@ template <> struct Mma<_Float16> {
     }
 };
 
-// Position swizzle of the 16-byte chunks of LDS row r.  Any 8 consecutive rows get 8 distinct
-// positions (32 banks), and any 16 consecutive rows get 16 distinct (position, row parity)
-// pairs (64 banks).  The pattern repeats every 16 rows, so fragment blocks 32 rows apart share
-// one per-lane offset.
-__device__ __forceinline__ uint32_t swz(uint32_t r) { return (r & 7u) ^ ((r >> 3) & 1u); }
+// Position swizzle of the 16-byte chunks of LDS row r.  128-byte rows: any 8 consecutive rows
+// get 8 distinct positions (32 banks), and any 16 consecutive rows get 16 distinct (position, row
+// parity) pairs (64 banks).  64-byte rows: four consecutive rows fill one 256-byte line of banks,
+// and the rows 4 apart that share a quarter of it get distinct positions, so 8 or 16 consecutive
+// rows read without conflict.  Both patterns repeat every 16 rows, so fragment blocks 32 rows
+// apart share one per-lane offset.
+template <int ROWB>
+__device__ __forceinline__ uint32_t swz(uint32_t r) {
+    if constexpr (ROWB == 128) return (r & 7u) ^ ((r >> 3) & 1u);
+    else return (r >> 2) & 3u;
+}
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -166,8 +178,10 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const uint32_t S = uni(s.ksplit);                      // workgroups per output tile (split along K)
     const uint32_t ty = tyz / S, kz = tyz % S;
     const uint32_t m0 = ty * TM, n0 = tx * tn_out;
-    const uint32_t KT = uni(s.K / 64);
-    const uint32_t kb = kz * (KT / S), ke = kb + KT / S;   // this workgroup's K steps
+    constexpr uint32_t BK = Cfg::BK, ROWB = Cfg::ROWB, SPK = 64 / Cfg::BK;   // SPK: pipeline steps per 64 K elements
+    const uint32_t KT64 = uni(s.K / 64);
+    const uint32_t kb64 = kz * (KT64 / S), ke64 = kb64 + KT64 / S;   // this workgroup's K range in units of 64 (what dependencies count in)
+    const uint32_t kb = kb64 * SPK, ke = ke64 * SPK;                 // ... and in pipeline steps
     const char* const Abase = uni_ptr(s.A);
     const char* const Bbase = uni_ptr(s.B);
     const uint32_t bkstep = uni(s.b_kstep_bytes);
@@ -181,13 +195,13 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     if (tracing) t_start = now_ticks();
 
     // ---- per-lane DMA source offsets (bytes from the operand base, K step 0) ----
-    const uint32_t lrow = lane >> 3, lpos = lane & 7u;
+    const uint32_t lrow = lane / Cfg::LPR, lpos = lane % Cfg::LPR;
     uint32_t offA[NIA], offB[NIB];
     uint32_t pixyx[AMODE == A_CONV3X3 ? NIA : 1];   // conv: (y << 16) | x of the output pixel of each DMA row
 #pragma unroll
     for (int i = 0; i < NIA; ++i) {
-        const uint32_t r = (wave * NIA + i) * 8 + lrow;
-        const uint32_t c = lpos ^ swz(r);
+        const uint32_t r = (wave * NIA + i) * Cfg::RPD + lrow;
+        const uint32_t c = lpos ^ swz<ROWB>(r);
         const uint32_t m = min(m0 + r, sM - 1);
         offA[i] = m * s.lda * 2u + c * 16u;
         if constexpr (AMODE == A_CONV3X3) {
@@ -197,8 +211,8 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     }
 #pragma unroll
     for (int i = 0; i < NIB; ++i) {
-        const uint32_t q = (wave * NIB + i) * 8 + lrow;
-        const uint32_t c = lpos ^ swz(q);
+        const uint32_t q = (wave * NIB + i) * Cfg::RPD + lrow;
+        const uint32_t c = lpos ^ swz<ROWB>(q);
         uint32_t row;
         if (gate_up) {
             const uint32_t blk = q >> 5, within = q & 31u;
@@ -213,29 +227,37 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // Source of the K step that is being requested ("next" step): a byte offset for B and the
     // dense A, and for the conv the filter tap (fr, fs in -1..1) and the byte shift of that tap.
     struct NextStep {
-        uint32_t kbytes;     // kt * 128
+        uint32_t kbytes;     // byte offset of the K step in a row of A
         uint32_t kbytes_b;   // byte offset of the K step in B
         uint32_t tap, c0;    // conv: filter tap 0..8 and first input channel of the step
         int fr, fs;
         long shift;
     } nx;
-    auto set_next = [&](uint32_t kt) __attribute__((always_inline)) {
-        nx.kbytes = kt * 128u;
-        nx.kbytes_b = kt * bkstep;
+    // (A and B may be requested a different number of steps ahead, so each has its own "next")
+    auto set_next_A = [&](uint32_t kt) __attribute__((always_inline)) {
+        if constexpr (Cfg::DBG == 1) kt &= 7u;
+        nx.kbytes = kt * ROWB;
         if constexpr (AMODE == A_CONV3X3) {
-            const uint32_t k0 = kt * 64u;
+            const uint32_t k0 = kt * BK;
             nx.tap = k0 / cCin; nx.c0 = k0 % cCin;
             nx.fr = (int)(nx.tap / 3) - 1; nx.fs = (int)(nx.tap % 3) - 1;
             nx.shift = ((long)nx.fr * (long)cW + nx.fs) * (long)cCin * 2 + (long)nx.c0 * 2;
         }
     };
+    auto set_next_B = [&](uint32_t kt) __attribute__((always_inline)) {
+        if constexpr (Cfg::DBG == 1) kt &= 7u;
+        // B is addressed in blocks of 64 K elements (b_kstep_bytes apart); a step of 32 is half a block
+        nx.kbytes_b = BK == 64 ? kt * bkstep : (kt >> 1) * bkstep + (kt & 1u) * 64u;
+    };
     // One 1 KB DMA instruction of the B (weights) or A operand of the next K step into `stage`.
     auto dma_B = [&](uint32_t stage, int i) __attribute__((always_inline)) {
-        char* l = lds + stage * Cfg::STAGE_BYTES + Cfg::A_BYTES + wave * (NIB * 1024);
+        char* l = lds + Cfg::B_BASE + stage * Cfg::B_BYTES + wave * (NIB * 1024);
+        if constexpr (Cfg::DBG == 3) { dma16(Bbase + lane * 16u + (i & 7) * 1024, l + i * 1024); return; }   // L1-resident source
+        if constexpr (Cfg::DBG == 4) { if (i & 1) return; }
         dma16(Bbase + nx.kbytes_b + offB[i], l + i * 1024);
     };
     auto dma_A = [&](uint32_t stage, int i) __attribute__((always_inline)) {
-        char* l = lds + stage * Cfg::STAGE_BYTES + wave * (NIA * 1024);
+        char* l = lds + stage * Cfg::A_BYTES + wave * (NIA * 1024);
         const char* src;
         if constexpr (AMODE == A_CONV3X3) {
             const int y = (int)(pixyx[i] >> 16) + nx.fr, x = (int)(pixyx[i] & 0xffffu) + nx.fs;
@@ -244,6 +266,8 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         } else {
             src = Abase + nx.kbytes + offA[i];
         }
+        if constexpr (Cfg::DBG == 3) src = Abase + lane * 16u + (i & 7) * 1024;
+        if constexpr (Cfg::DBG == 4) { if (i & 1) return; }
         dma16(src, l + i * 1024);
     };
     auto issue_B = [&](uint32_t stage) __attribute__((always_inline)) {
@@ -256,14 +280,15 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     };
 
     // ---- per-lane fragment read offsets (bytes inside the A / B part of a stage) ----
-    uint32_t aoff[4], boff[4];
+    constexpr int KK = Cfg::KK;
+    uint32_t aoff[KK], boff[KK];
     {
         const uint32_t ra = wm * Cfg::WTM + (lane & 31u), rb = wn * Cfg::WTN + (lane & 31u);
         const uint32_t h = lane >> 5;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            aoff[kk] = ra * 128u + ((((uint32_t)kk * 2u + h) ^ swz(ra)) << 4);
-            boff[kk] = rb * 128u + ((((uint32_t)kk * 2u + h) ^ swz(rb)) << 4);
+        for (int kk = 0; kk < KK; ++kk) {
+            aoff[kk] = ra * ROWB + ((((uint32_t)kk * 2u + h) ^ swz<ROWB>(ra)) << 4);
+            boff[kk] = rb * ROWB + ((((uint32_t)kk * 2u + h) ^ swz<ROWB>(rb)) << 4);
         }
     }
 
@@ -278,9 +303,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const bool reorder = !(args.flags & DS_FLAG_NO_REORDER);
 
     // Dependency segments start at multiples of seg_steps K steps (0: only at step 0).
-    uint32_t seg_steps = 0, seg_next = kb;   // the host makes K ranges start on segment boundaries
+    uint32_t seg_steps = 0, seg_next = kb64;   // the host makes K ranges start on segment boundaries
     if constexpr (DEP) seg_steps = uni(dep_seg_steps(s));
-    // Called before the A slice of K step k (< KT) is requested into `stage`: if a dependency
+    // Called before the A slice that starts 64-element K block k (< KT64) is requested into `stage`: if a dependency
     // segment starts there, make sure its producer tiles have posted.  The semaphores are looked
     // at 64 segments at a time (lane l tests the segment l places ahead, one load instruction
     // for the wave), so a tile whose producers are long done pays one round trip for its whole
@@ -288,18 +313,18 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // weights of the step are requested first (the load/wait reordering) and then the wave
     // really waits; the caller requests the slice (and, harmlessly, the weights again) afterwards.
     uint32_t ready_until = 0;      // every segment that starts before this K step is known to be posted
-    auto dep_before_request = [&](uint32_t k, uint32_t stage) __attribute__((always_inline)) {
+    auto dep_before_request = [&](uint32_t k, uint32_t stage, bool b_due) __attribute__((always_inline)) {
         if constexpr (DEP) {
             if (k == seg_next) {
                 seg_next = seg_steps ? seg_next + seg_steps : 0xffffffffu;
                 DepRange dr;
-                if (!dep_segment(s, m0, TM, k, kb, dr)) return;
+                if (!dep_segment(s, m0, TM, k, kb64, dr)) return;
                 bool polled = false;
                 if (k >= ready_until) {
                     const uint32_t ka = k + lane * seg_steps;          // lane's segment start
                     bool ok = true;
                     DepRange la;
-                    if (ka < ke && (lane == 0 || seg_steps != 0) && dep_segment(s, m0, TM, ka, kb, la)) {
+                    if (ka < ke64 && (lane == 0 || seg_steps != 0) && dep_segment(s, m0, TM, ka, kb64, la)) {
                         const uint32_t target = s.sem_target_base + s.sem_value;
                         for (uint32_t y = la.y0; y <= la.y1; ++y) {
                             const uint32_t* sem = s.sems + policy_sem(s.dep_kind, la.x, y, s.prod_grid_y, s.stride) * SYNC_WORD_STRIDE;
@@ -309,7 +334,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                     const uint64_t mask = __ballot(ok);
                     const uint32_t n_ready = (~mask == 0) ? 64u : (uint32_t)__builtin_ctzll(~mask);
                     if (n_ready == 0) {
-                        if (reorder) issue_B(stage);
+                        if (reorder && b_due) issue_B(stage);
                         dep_wait(wctx, s, dr);
                         polled = true;
                         ready_until = k + 1;
@@ -324,16 +349,20 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         }
     };
 
-    // ---- prologue: K steps 0 .. NST-2 into stages 0 .. NST-2 ----
-    constexpr int NST = Cfg::NSTAGE;
-    constexpr int NG = 4 * FM;            // MFMA groups per step
+    // ---- prologue ----
+    // A is requested NSA-1 steps ahead into a ring of NSA stages, B NSB-1 steps ahead into a ring
+    // of NSB <= NSA stages (a tile too large for three stages of both keeps three of A and two of B:
+    // then only B's requests of a step, issued first, have to land within the step, and A's
+    // are spread over the rest of it with a step more to land).
+    constexpr int NSA = Cfg::NSTAGE, NSB = Cfg::NSTB;
+    constexpr int NG = KK * FM;           // MFMA groups per step
     constexpr int ND = NIA + NIB;         // DMA instructions per step
     // groups the DMA instructions are spread over: with two stages the step's requests must
     // have landed by the end of the same step, so they go out at its start (measured on the
     // GPT-3 chain at M = 2048: 128x192 601 -> 581 us, 128x128 727 -> 669 us with all of them in
     // the first group; the 256-row tiles, with twice the requests per wave, do best with a
     // quarter of the groups: 256x192 714 -> 684 us)
-    constexpr int NGD = (NST > 2) ? NG : (FM <= 2 ? 1 : NG / 4);
+    constexpr int NGD = Cfg::NGD_OVERRIDE ? Cfg::NGD_OVERRIDE : (NSA > 2) ? NG : (FM <= 2 ? 1 : NG / 4);
     // Tiles that have a CU to themselves (one wave per SIMD) read all fragments of the next
     // 16-wide K slice together, a whole slice of MFMAs before their first use, with the order
     // pinned: left to itself the compiler issues each read right before the wait for it (while
@@ -341,84 +370,147 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // the CU nothing fills that round trip.  Measured on the GPT-3 chain at M = 2048: 256x128
     // 609 -> 585 us, 256x192 621 -> 612 us; with two workgroups per CU it gains nothing.
     constexpr bool S2 = (Cfg::MINB == 1);
-    static_assert((NST - 2) * ND <= 48, "outstanding DMA instructions must fit the vmcnt counter");
+    // At the top of step k the requests of A(k) and B(k) must have landed.  Requests complete in
+    // issue order, and a step issues B's before A's, so what may still be outstanding is what was
+    // issued after B(k): the A requests of that same step when A runs further ahead than B, and
+    // the NSB-2 whole steps after it.
+    constexpr int OUTSTANDING = (NSA > NSB ? NIA : 0) + (NSB - 2) * ND;
+    static_assert(OUTSTANDING <= 48, "outstanding DMA instructions must fit the vmcnt counter");
+    // the steps before the loop, in the order the loop itself would have issued them
+    // (a step of 32 that starts in the middle of a block of 64 belongs to the segment its first half started)
 #pragma unroll
-    for (int p = 0; p < NST - 1; ++p) {
-        set_next(min(kb + (uint32_t)p, ke - 1));
-        if (kb + (uint32_t)p < ke) dep_before_request(kb + p, p);
+    for (int p = 0; p < NSA - 1; ++p) {
+        const int pb = p - (NSA - NSB);    // B's step issued alongside A's step p
+        set_next_A(min(kb + (uint32_t)p, ke - 1));
+        if (pb >= 0) set_next_B(min(kb + (uint32_t)pb, ke - 1));
+        if (kb + (uint32_t)p < ke && (p % SPK) == 0) dep_before_request((kb + p) / SPK, pb >= 0 ? pb : 0, pb >= 0);
         if (p == 0 && tracing) t_ready = now_ticks();
-        issue_B(p);
+        if (pb >= 0) issue_B(pb);
         issue_A(p);
     }
 
-    // The K loop.  Per step and wave: 4*FM groups of FN MFMAs.  The DMA instructions of the step
-    // NST-1 ahead are spread over the first NGD of those groups (with three or more stages: all
-    // of them, since a wave that issues a burst sits at the memory pipeline's queue and starves
-    // its matrix unit, and the requests have a further step to land), weights first; the fragments of the
-    // next 16-wide K slice are read from LDS while the current slice's MFMAs run.  The body is
-    // free of branches: past the end the last slice is simply requested again into an idle stage.
-    uint32_t cur = 0, req = NST - 1;      // stage being computed on / stage being filled
-    for (uint32_t kt = kb; kt < ke; ++kt) {
-        // step kt's DMA group is complete when at most the NST-2 younger groups are outstanding
-        // (a bare s_barrier: __syncthreads() would also wait for the younger groups)
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NST - 2) * ND) : "memory");
-        // now stage `cur` is complete for all waves and nobody still reads stage `req`
-
-        const uint32_t kreq = kt + (NST - 1);
-        set_next(min(kreq, ke - 1));
-        if (kreq < ke) dep_before_request(kreq, req);
-
-        const char* la = lds + cur * Cfg::STAGE_BYTES;
-        const char* lb = la + Cfg::A_BYTES;
-        V8 af[2][FM], bf[2][FN];
+    // The K loop, as one stream of 16-wide K slices (KK per step, each KK*... FM groups of FN MFMAs
+    // per wave).  While a slice's MFMAs run, the fragments of the next slice are read from LDS
+    // into the other fragment buffer.  The workgroup barrier that hands over a step's stage sits
+    // before the LAST slice of the step before it: at that point every wave has read (not yet
+    // multiplied) its last fragments of the current stage, so the stage is free for new requests,
+    // and the next step's first fragments travel from LDS while the last slice's MFMAs run; no
+    // fragment read is exposed at a step boundary.  The DMA instructions a barrier releases (the
+    // steps NSB-1 / NSA-1 ahead, weights first) are spread over the first NGD of the NG groups
+    // that follow it.  Past the end of K the last step is simply requested again into an idle
+    // stage, so the body is free of branches.
+    V8 af[2][FM], bf[2][FN];
+    auto load_frags = [&](int buf, const char* la, const char* lb, int kk) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) af[0][i] = *(const V8*)(la + aoff[0] + i * (32 * 128));
+        for (int i = 0; i < FM; ++i) af[buf][i] = *(const V8*)(la + aoff[kk] + i * (32 * ROWB));
 #pragma unroll
-        for (int j = 0; j < FN; ++j) bf[0][j] = *(const V8*)(lb + boff[0] + j * (32 * 128));
+        for (int j = 0; j < FN; ++j) bf[buf][j] = *(const V8*)(lb + boff[kk] + j * (32 * ROWB));
+    };
+    uint32_t reqA = NSA - 1, reqB = NSB - 1;                 // stages the next requests go into
+    // DMA instructions of group g (counted from the barrier that released them)
+    auto dma_group = [&](int g) __attribute__((always_inline)) {
+        if (g < NGD && Cfg::DBG != 2 && Cfg::DBG != 5 && Cfg::DBG != 6) {
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
-            const int c = kk & 1, n = c ^ 1;
-            if constexpr (S2) {
-                // an empty asm that reads the current slice's fragments: the compiler's wait for
-                // them lands here, before the next slice's reads are issued
-                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-#pragma unroll
-                for (int i = 0; i < FM; ++i) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, af[c][i])));
-#pragma unroll
-                for (int j = 0; j < FN; ++j) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, bf[c][j])));
-                __builtin_amdgcn_sched_barrier(0);
-                if (kk < 3) {
-#pragma unroll
-                    for (int i = 0; i < FM; ++i) af[n][i] = *(const V8*)(la + aoff[kk + 1] + i * (32 * 128));
-#pragma unroll
-                    for (int j = 0; j < FN; ++j) bf[n][j] = *(const V8*)(lb + boff[kk + 1] + j * (32 * 128));
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-#pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int g = kk * FM + i;
-                if (!S2 && kk < 3) {
-                    af[n][i] = *(const V8*)(la + aoff[kk + 1] + i * (32 * 128));
-#pragma unroll
-                    for (int j = (i * FN) / FM; j < ((i + 1) * FN) / FM; ++j)
-                        bf[n][j] = *(const V8*)(lb + boff[kk + 1] + j * (32 * 128));
-                }
-                if (g < NGD) {
-#pragma unroll
-                    for (int d = (g * ND) / NGD; d < ((g + 1) * ND) / NGD; ++d) {
-                        if (d < NIB) dma_B(req, d);
-                        else dma_A(req, d - NIB);
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < FN; ++j) acc[i][j] = M::mma(af[c][i], bf[c][j], acc[i][j]);
-                if constexpr (S2) __builtin_amdgcn_sched_barrier(0);
+            for (int d = (g * ND) / NGD; d < ((g + 1) * ND) / NGD; ++d) {
+                if (d < NIB) dma_B(reqB, d);
+                else dma_A(reqA, d - NIB);
             }
         }
-        cur = (cur + 1 == NST) ? 0 : cur + 1;
-        req = (req + 1 == NST) ? 0 : req + 1;
+    };
+    // One slice: MFMAs on fragment buffer `buf`; meanwhile read the fragments of slice nkk of the
+    // stage at (nla, nlb) into the other buffer (nkk < 0: none) and issue the DMA groups g0 .. g0+FM-1
+    // (g0 < 0: none).
+    auto slice = [&](int buf, const char* nla, const char* nlb, int nkk, int g0) __attribute__((always_inline)) {
+        const int n = buf ^ 1;
+        if constexpr (S2) {
+            // One wave per SIMD: nothing else fills the matrix unit while this wave issues other
+            // instructions, and a run of fragment reads takes longer to issue than one MFMA to
+            // execute.  So the order is pinned: after each MFMA at most one fragment read of the
+            // next slice (the fragments the next slice needs first go first), DMA instructions at
+            // the start of a group.  The empty asm that reads the current slice's fragments is where
+            // the compiler's wait for them lands, before anything of this slice is issued.
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+#pragma unroll
+            for (int i = 0; i < FM; ++i) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, af[buf][i])));
+#pragma unroll
+            for (int j = 0; j < FN; ++j) asm volatile("" ::"v"(__builtin_bit_cast(u32x4, bf[buf][j])));
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < FM; ++i) {
+                if (g0 >= 0) dma_group(g0 + i);
+#pragma unroll
+                for (int j = 0; j < FN; ++j) {
+                    acc[i][j] = M::mma(af[buf][i], bf[buf][j], acc[i][j]);
+                    // fragment read number m of the next slice (A0, B0 .. B(FN-1), A1 ..) follows MFMA
+                    // number m; a wave tile of fewer MFMAs than fragments reads the rest after the last
+                    constexpr int NF = FM + FN, NM = FM * FN;
+                    const int m0 = i * FN + j, m1 = (m0 == NM - 1 && NM < NF) ? NF : m0 + 1;
+                    if (nkk >= 0 && Cfg::DBG != 5) {
+#pragma unroll
+                        for (int m = m0; m < m1; ++m) {
+                            if (m == 0) af[n][0] = *(const V8*)(nla + aoff[nkk]);
+                            else if (m <= FN) bf[n][m - 1] = *(const V8*)(nlb + boff[nkk] + (m - 1) * (32 * ROWB));
+                            else if (m < NF) af[n][m - FN] = *(const V8*)(nla + aoff[nkk] + (m - FN) * (32 * ROWB));
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            return;
+        }
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            if (nkk >= 0) {
+                af[n][i] = *(const V8*)(nla + aoff[nkk] + i * (32 * ROWB));
+#pragma unroll
+                for (int j = (i * FN) / FM; j < ((i + 1) * FN) / FM; ++j)
+                    bf[n][j] = *(const V8*)(nlb + boff[nkk] + j * (32 * ROWB));
+            }
+            if (g0 >= 0) dma_group(g0 + i);
+#pragma unroll
+            for (int j = 0; j < FN; ++j) acc[i][j] = M::mma(af[buf][i], bf[buf][j], acc[i][j]);
+        }
+    };
+    // Hand-over of step k's stage: its requests have landed for every wave (requests complete in
+    // issue order; a bare s_barrier, since __syncthreads() would also wait for the younger ones),
+    // and every wave has finished reading the stage of step k-1.  Then point the requests at the
+    // steps ahead of k (after waiting for what the A slice depends on, if a dependency segment starts).
+    auto hand_over = [&](uint32_t k) __attribute__((always_inline)) {
+        if constexpr (Cfg::DBG == 6) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(OUTSTANDING) : "memory");
+        else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(OUTSTANDING) : "memory");
+        const uint32_t kreq = k + (NSA - 1);
+        set_next_A(min(kreq, ke - 1));
+        set_next_B(min(k + (NSB - 1), ke - 1));
+        if (kreq < ke && (kreq % SPK) == 0) dep_before_request(kreq / SPK, reqB, true);
+    };
+    auto advance = [&](uint32_t& st, uint32_t n) __attribute__((always_inline)) { st = (st + 1 == n) ? 0 : st + 1; };
+    static_assert(KK % 2 == 0, "fragment buffers alternate with the slices");
+
+    // head: step kb's stage is handed over, its requests go out with slices 0 .. KK-2 (the groups
+    // that the missing slice before them would have carried are issued at once)
+    uint32_t curA = 0, curB = 0;
+    hand_over(kb);
+    const char* la = lds;
+    const char* lb = lds + Cfg::B_BASE;
+    load_frags(0, la, lb, 0);
+#pragma unroll
+    for (int g = 0; g < FM; ++g) dma_group(g);
+#pragma unroll
+    for (int kk = 0; kk < KK - 1; ++kk) slice(kk & 1, la, lb, kk + 1, (kk + 1) * FM);
+    advance(reqA, NSA); advance(reqB, NSB);
+    for (uint32_t kt = kb + 1; kt < ke; ++kt) {
+        // the last fragments of step kt-1 are in registers: hand over step kt's stage, multiply
+        // them while step kt's first fragments are read, then step kt's slices 0 .. KK-2
+        hand_over(kt);
+        advance(curA, NSA); advance(curB, NSB);
+        la = lds + curA * Cfg::A_BYTES;
+        lb = lds + Cfg::B_BASE + curB * Cfg::B_BYTES;
+        slice((KK - 1) & 1, la, lb, 0, 0);
+#pragma unroll
+        for (int kk = 0; kk < KK - 1; ++kk) slice(kk & 1, la, lb, kk + 1, (kk + 1) * FM);
+        advance(reqA, NSA); advance(reqB, NSB);
     }
+    slice((KK - 1) & 1, nullptr, nullptr, -1, -1);   // tail: the last slice of the last step
     // every DMA into LDS has landed before the staging area is given up
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     dr.peek();   // the look at the dispatch queues for this workgroup's next tile travels during the epilogue
