@@ -81,11 +81,14 @@ struct sync_policy {
     hipStream_t own_stream;    // second stream when the caller gives none
     hipStream_t third_stream;  // third stage of a chain in FINE mode
     hipStream_t fourth_stream; // fourth stage
-    hipEvent_t ev_fork, ev_join, ev_join3, ev_join4;
-    // epoch state: semaphores and the dispatch counter only ever grow between resets
+    hipStream_t last_side;     // the caller's second stream of the last two-stream chain, if it gave one
+    hipEvent_t ev_fork;
+    hipEvent_t ev_side;        // used to order the side streams before a reset of the workspace
+    bool side_used;            // a two-stream chain has been launched since the last reset
+    // epoch state: semaphores and the dispatch counters only ever grow between resets
     uint64_t geom_sig;
     uint32_t epoch;
-    uint32_t queue_epoch;  // chains that drew their tiles from the dispatch queues since the last reset
+    uint32_t queue_epoch;      // chains that drew their tiles from the dispatch queues since the last reset
     int force_order;       // autotuner only: -1 none, 0 dispatch queues, 1 hardware order
     uint32_t launches;
     float* scratch;        // split-K partial tiles, grown on demand
@@ -616,6 +619,30 @@ uint64_t geom_signature(const Plan& p) {
     return h;
 }
 
+// Two-stream launches are not joined back (see launch_chain), so a side stream's launch may still
+// be winding down when a later chain starts.  That is harmless while the workspace keeps its
+// meaning (such a launch draws with compare-and-swap and finds its epoch's queues handed out), but
+// before the workspace is re-zeroed every side launch must have ended: order the side streams'
+// work enqueued so far before whatever `stream` runs next.
+int settle_side_launches(sync_policy* pol, hipStream_t stream) {
+    if (!pol->side_used || !pol->ev_side) return DEPSYNC_OK;
+    hipStream_t side[4] = {pol->own_stream, pol->third_stream, pol->fourth_stream, pol->last_side};
+    for (int i = 0; i < 4; ++i) {
+        hipStream_t st = side[i];
+        if (!st) continue;
+        const hipError_t e = hipEventRecord(pol->ev_side, st);
+        if (e != hipSuccess) {
+            // a caller's stream that no longer exists has nothing left to order
+            if (i == 3) { (void)hipGetLastError(); continue; }
+            return hip_fail(e);
+        }
+        HIP_TRY(hipStreamWaitEvent(stream, pol->ev_side, 0));
+    }
+    pol->last_side = nullptr;
+    pol->side_used = false;
+    return DEPSYNC_OK;
+}
+
 // Make semaphores/counter consistent for a launch with geometry `p`; returns the epoch.
 int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t* epoch_out) {
     uint32_t total = 0, vmax = 1;
@@ -623,7 +650,9 @@ int prepare_epoch(sync_policy* pol, const Plan& p, hipStream_t stream, uint32_t*
     const uint64_t sig = geom_signature(p);
     const uint64_t next = (uint64_t)(pol->epoch + 2) * std::max(total, vmax);
     if (pol->need_reset || sig != pol->geom_sig || next >= (1ull << 31)) {
-        // zero the dispatch counter and every semaphore the previous geometry may have touched
+        // zero the dispatch counters and every semaphore the previous geometry may have touched,
+        // once no launch of an earlier chain can still be drawing from them
+        if (int rc = settle_side_launches(pol, stream); rc != DEPSYNC_OK) return rc;
         hipError_t e = launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, stream);
         if (e == hipSuccess) e = launch_fill_u32(pol->ws + WS_SEMS, 0u, pol->sems_dirty * SYNC_WORD_STRIDE, stream);
         if (e == hipSuccess && pol->need_reset) {
@@ -731,7 +760,6 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
 
 int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mode, void* sp_, void* sc_) {
     hipStream_t sp = static_cast<hipStream_t>(sp_);
-    hipStream_t sc = sc_ ? static_cast<hipStream_t>(sc_) : pol->own_stream;
     const bool sync = mode != DEPSYNC_MODE_PLAIN;
     // Tiles in the hardware's order (Section IV-C, "T"): asked for by the caller, or found faster
     // by the autotuner for this chain in one dispatch.  In-order dispatch of the block index on
@@ -751,44 +779,58 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     // has one workgroup per tile.
     const bool queues = sync && !(a.flags & DEPSYNC_FLAG_HW_ORDER);
     auto blocks = [&](uint32_t tiles) { return queues ? std::min<uint32_t>(tiles, (uint32_t)p.slots) : tiles; };
+    const int last = p.n_stages - 1;
     if (mode == DEPSYNC_MODE_FUSED) {
         // all stages in one dispatch; needs one macro-tile shape for the whole chain
         for (int s = 1; s < p.n_stages; ++s)
             if (p.tile[s] != p.tile[0]) return DEPSYNC_ENOTIMPL;
         a.block_offset = 0;
-        a.stage_lo = 0; a.stage_hi = (uint32_t)p.n_stages - 1;
+        a.stage_lo = 0; a.stage_hi = (uint32_t)last;
         HIP_TRY(launch_chain_kernel(p.tile[0], p.dtype, p.amode, true, blocks(total), sp, a));
-    } else {
-        if (mode == DEPSYNC_MODE_FINE) {
-            HIP_TRY(hipEventRecord(pol->ev_fork, sp));
-            HIP_TRY(hipStreamWaitEvent(sc, pol->ev_fork, 0));
-            if (p.n_stages > 2) HIP_TRY(hipStreamWaitEvent(pol->third_stream, pol->ev_fork, 0));
-            if (p.n_stages > 3) HIP_TRY(hipStreamWaitEvent(pol->fourth_stream, pol->ev_fork, 0));
-        }
+    } else if (mode == DEPSYNC_MODE_FINE) {
+        // Section III-A: the stages are launched on different streams and overlap.  The LAST stage
+        // goes on the caller's stream, the earlier ones on side streams forked off it with one
+        // event.  Nothing is joined back: every tile of an earlier stage is waited for by some
+        // tile of the stage after it, so the end of the last stage's launch is the end of the chain,
+        // and the caller's stream carries no wait for another stream (a cross-stream wait costs
+        // some 20 us here).  A launch works on its own stage and first helps with whatever earlier
+        // stages have not been handed out yet, so the chain completes even if a side stream's
+        // launch starts late: it then finds its tiles taken and ends.  Because it may run that
+        // late (into a later chain), a side launch draws with compare-and-swap on a value it has
+        // seen to lie in its own epoch, and never moves a counter otherwise.
+        if (!pol->ev_fork) return DEPSYNC_EINVAL;          // a policy without streams of its own
+        hipStream_t side[3] = {sc_ ? static_cast<hipStream_t>(sc_) : pol->own_stream, pol->third_stream, pol->fourth_stream};
+        if (sc_) pol->last_side = static_cast<hipStream_t>(sc_);
+        // When the last stage's launch has a workgroup of its own for every tile of the chain, all
+        // of them resident at once, a side launch could only ever find its tiles taken (it starts
+        // when the event has crossed streams, later than the caller's launch): it is left out, as
+        // the paper leaves out its wait kernel when both kernels fit the GPU together (Section IV-C).
+        const bool side_useful = !(queues && total <= (uint32_t)p.slots);
+        if (side_useful) HIP_TRY(hipEventRecord(pol->ev_fork, sp));
         uint32_t off = 0;
         for (int s = 0; s < p.n_stages; ++s) {
-            // producer on the caller's stream; later stages on the second stream in FINE mode
-            // (one stream per stage: launches on one stream would run one after the other)
-            hipStream_t st = mode != DEPSYNC_MODE_FINE || s == 0 ? sp : s == 1 ? sc : s == 2 ? pol->third_stream : pol->fourth_stream;
-            a.block_offset = off;
-            // a launch works on its own stage and, when launches overlap (FINE), first helps
-            // with whatever earlier stages have not been handed out yet
-            a.stage_lo = mode == DEPSYNC_MODE_FINE ? 0u : (uint32_t)s;
+            hipStream_t st = s == last ? sp : side[s];
+            if (s != last && !side_useful) { off += p.n_tiles[s]; continue; }
+            if (s != last) HIP_TRY(hipStreamWaitEvent(st, pol->ev_fork, 0));
+            // (drawing from the queues, the last stage's launch covers the whole chain from its first
+            // block on, so its first blocks go straight for the first stage's queues)
+            a.block_offset = (s == last && queues) ? 0u : off;
+            a.stage_lo = 0u;
             a.stage_hi = (uint32_t)s;
-            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, blocks(p.n_tiles[s]), st, a));
+            a.draw_cas = s == last ? 0u : 1u;
+            // (the last stage's launch may have to run the whole chain: as many workgroups as all of it could use)
+            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, true, blocks(s == last && queues ? total : p.n_tiles[s]), st, a));
             off += p.n_tiles[s];
         }
-        if (mode == DEPSYNC_MODE_FINE) {
-            HIP_TRY(hipEventRecord(pol->ev_join, sc));
-            HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join, 0));
-            if (p.n_stages > 2) {
-                HIP_TRY(hipEventRecord(pol->ev_join3, pol->third_stream));
-                HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join3, 0));
-            }
-            if (p.n_stages > 3) {
-                HIP_TRY(hipEventRecord(pol->ev_join4, pol->fourth_stream));
-                HIP_TRY(hipStreamWaitEvent(sp, pol->ev_join4, 0));
-            }
+        a.draw_cas = 0u;
+        if (side_useful) pol->side_used = true;
+    } else {
+        uint32_t off = 0;
+        for (int s = 0; s < p.n_stages; ++s) {   // one launch per stage on the caller's stream
+            a.block_offset = off;
+            a.stage_lo = a.stage_hi = (uint32_t)s;
+            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, blocks(p.n_tiles[s]), sp, a));
+            off += p.n_tiles[s];
         }
     }
     if (sync) {
@@ -798,7 +840,6 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     pol->launches += 1;
     return DEPSYNC_OK;
 }
-
 
 // Operand pointers, shapes and epilogues of a GeMM chain's stages (what does not depend on the plan).
 void fill_gemm_stages(ChainArgs& a, const depsync_gemm_chain_desc* d) {
@@ -894,14 +935,14 @@ int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* pa
     }
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->own_stream, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->third_stream, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join3, hipEventDisableTiming);
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->fourth_stream, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join4, hipEventDisableTiming);
     if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_side, hipEventDisableTiming);
     if (e != hipSuccess) { (void)hipFree(p->ws); delete p; return hip_fail(e); }
     p->epoch = 0;
     p->queue_epoch = 0;
+    p->side_used = false;
+    p->last_side = nullptr;
     p->force_order = -1;
     p->geom_sig = 0;
     p->launches = 0;
@@ -919,9 +960,7 @@ int sync_policy_destroy(sync_policy_t* pol) {
     if (!pol) return DEPSYNC_EINVAL;
     (void)hipDeviceSynchronize();
     (void)hipEventDestroy(pol->ev_fork);
-    (void)hipEventDestroy(pol->ev_join);
-    (void)hipEventDestroy(pol->ev_join3);
-    (void)hipEventDestroy(pol->ev_join4);
+    (void)hipEventDestroy(pol->ev_side);
     (void)hipStreamDestroy(pol->fourth_stream);
     (void)hipStreamDestroy(pol->own_stream);
     (void)hipStreamDestroy(pol->third_stream);
@@ -934,6 +973,7 @@ int sync_policy_destroy(sync_policy_t* pol) {
 int dep_chain_reset(sync_policy_t* pol, void* stream) {
     if (!pol) return DEPSYNC_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (int rc = settle_side_launches(pol, st); rc != DEPSYNC_OK) return rc;
     HIP_TRY(launch_fill_u32(pol->ws + WS_TICKET, 0u, WS_TICKET_WORDS, st));
     HIP_TRY(launch_fill_u32(pol->ws + pol->lay.arrive, 0u, pol->lay.max_arrive * SYNC_WORD_STRIDE, st));
     HIP_TRY(launch_fill_u32(pol->ws + WS_STATUS, 0u, 8, st));

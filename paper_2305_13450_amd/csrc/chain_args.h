@@ -106,6 +106,7 @@ struct ChainArgs {
     uint32_t queue_epoch;       // those of them that drew their tiles from the dispatch queues
     uint32_t block_offset;      // HW order / PLAIN: ticket of this launch's block 0
     uint32_t stage_lo, stage_hi; // stages the workgroups of this launch may draw tiles of
+    uint32_t draw_cas;          // this launch may run late, into a later chain: it draws with compare-and-swap
     uint32_t flags;             // DEPSYNC_FLAG_*
     uint32_t spin_limit;
     uint32_t delay_tile, delay_iters;

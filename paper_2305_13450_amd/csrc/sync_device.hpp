@@ -256,7 +256,7 @@ struct Drawer {
     // queue drawn from last; near its end only if the counter read by peek() shows entries,
     // else start reading all eight counters for draw().
     __device__ __forceinline__ void grab() {
-        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi || pending) return;
+        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi || pending || a.draw_cas) return;
         const uint32_t len = queue_len(a.st[open], cur_q);
         if (near_end()) {
             if (!peeked) return;                              // draw() will look first
@@ -283,8 +283,38 @@ struct Drawer {
         return true;
     }
 
+    // DRAW_THREAD, launches that may run late (into a later chain on the same workspace): look at
+    // the counters, and take an entry only by compare-and-swap on a value seen to lie inside this
+    // chain's part of the counter's range.  Such a launch never moves a counter of another chain.
+    __device__ __forceinline__ bool draw_late(uint32_t& stage, uint32_t& tx, uint32_t& ty) {
+        for (; open <= a.stage_hi; ++open) {
+            const StageDesc& st = a.st[open];
+            for (;;) {
+                look();
+                const uint32_t avail = available();
+                if (avail == 0) break;                        // handed out (or a later chain's): next stage
+                const uint32_t q = first_from_home(avail);
+                const uint32_t len = queue_len(st, q);
+                uint32_t seen = 0;                             // c[q] without indexing the array by a run-time value
+#pragma unroll
+                for (int j = 0; j < 8; ++j) seen = (uint32_t)j == q ? c[j] : seen;
+                uint32_t expected = seen;
+                if (__hip_atomic_compare_exchange_strong(counter(q), &expected, seen + 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT)) {
+                    uint32_t i = seen - base(len);
+                    cur_q = q; last_i = i;
+                    if (open == 0 && (a.flags & DS_FLAG_REVERSE_ORDER)) i = len - 1u - i;
+                    stage = open; queue_entry(st, q, i, tx, ty);
+                    return true;
+                }
+            }
+        }
+        return false;
+    }
+
     // DRAW_THREAD: draw a tile (blocking).
     __device__ __forceinline__ bool draw(uint32_t& stage, uint32_t& tx, uint32_t& ty) {
+        if (a.draw_cas) return draw_late(stage, tx, ty);
         // a workgroup launched for the first stage it may work on goes straight for its XCD's
         // queue the first time (one round trip); so does every workgroup that moves on to a
         // stage with at least a tile for each of them
