@@ -50,7 +50,10 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-autotune", action="store_true", help="use the library's model-based tile choice")
     ap.add_argument("--cpu-rows", type=int, default=2048, help="rows of X the CPU oracle is timed on")
-    ap.add_argument("--modes", default="fine,fused,streamsync,plain")
+    ap.add_argument("--modes", default="fine,fused,fused_hw,streamsync,plain",
+                    help="fine: two streams; fused: one dispatch, the library's tile order (dispatch queues unless every tile is "
+                         "resident at once); fused_hw: one dispatch, tiles named by the block index (DEPSYNC_FLAG_HW_ORDER, "
+                         "reported, never the headline); streamsync; plain")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="MiB",
                     help="also run a plain device-to-device copy of this many MiB three times, so that "
                          "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled to bytes")
@@ -265,13 +268,15 @@ def measure(args, torch, ds, wl, sp, sc, want, pol_names=None, tile=0, autotune=
     # `steps` launches (the chip's clock follows its power and temperature history, so variants
     # timed one after the other are not comparable); a variant's latency is the median of its blocks.
     pols = {pn: ds.SyncPolicy(kinds[pn]) for pn in pol_names}
+    pols_hw = {pn: ds.SyncPolicy(kinds[pn], flags=ds.FLAG_HW_ORDER) for pn in pol_names} if "fused_hw" in want else {}
     if tile == 0 and autotune:
         # outside the timed region: let the library time its macro-tile shapes on this chain once
         for pn in pol_names:
             wl.autotune(pols[pn], sp)
     variants = [(pn, mn) for pn in pol_names for mn in want
-                if mn in ("fine", "fused") or pn == pol_names[0]]   # stream-sync / plain: first policy only
-    calls = {(pn, mn): wl.caller(pols[pn], modes[mn], tile, sp, sc) for pn, mn in variants}
+                if mn in ("fine", "fused") or pn == pol_names[0]]   # stream-sync / plain / block-index order: first policy only
+    modes["fused_hw"] = ds.MODE_FUSED
+    calls = {(pn, mn): wl.caller(pols_hw[pn] if mn == "fused_hw" else pols[pn], modes[mn], tile, sp, sc) for pn, mn in variants}
     for v in variants:
         for _ in range(args.warmup):
             calls[v]()
@@ -298,11 +303,12 @@ def measure(args, torch, ds, wl, sp, sc, want, pol_names=None, tile=0, autotune=
         calls[best]()
     lat = time_block(torch, calls[best], sp, args.steps)
     best_plan = wl.plan(pols[best[0]], tile)
-    for pol in pols.values():
+    for pol in list(pols.values()) + list(pols_hw.values()):
         pol.status()
         pol.destroy()
     return dict(plan=best_plan, results=results, blocks=blocks, best=best, lat=lat, kinds=kinds, modes=modes,
-                ss=results.get((pol_names[0], "streamsync")), plain=results.get((pol_names[0], "plain")))
+                ss=results.get((pol_names[0], "streamsync")), plain=results.get((pol_names[0], "plain")),
+                hw=results.get((pol_names[0], "fused_hw")))
 
 
 def roofline(plan, lat_us):
@@ -342,14 +348,15 @@ def sweep(args, torch, ds, inputs):
         cases += [("llama_mlp", dict(M=m)) for m in inputs.CFG3["Ms"]]
         cases += [("gpt3_attn", dict(M=m)) for m in inputs.CFG4["Ms"]]
         cases += [("vgg_conv", dict(hw=hw, channels=ch, batch=b)) for hw, ch in inputs.CFG5["stages"] for b in (1, 16)]
-    lines = ["| workload | tile | P / (mid) / C tiles | slots | waves ss / fine | best fine-grained us (policy/launch) | "
-             "stream-sync us | plain us | speedup vs ss | vs plain | TFLOP/s | roofline | slot util. | final wave |",
-             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
+    lines = ["| workload | tile | P / (mid) / C tiles | slots | waves ss / fine | best fine-grained us (policy/launch) | two streams us | "
+             "stream-sync us | plain us | block-index order us | speedup vs ss | vs plain | TFLOP/s | roofline | slot util. | final wave |",
+             "|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|---|"]
     fmt = lambda v: "-" if v is None else f"{v:.2f}"
     for kind, kw in cases:
         wl = Workload(torch, ds, inputs, kind, **kw)
-        r = measure(args, torch, ds, wl, sp, sc, ["fine", "fused", "streamsync", "plain"], autotune=not args.no_autotune)
+        r = measure(args, torch, ds, wl, sp, sc, ["fine", "fused", "fused_hw", "streamsync", "plain"], autotune=not args.no_autotune)
         plan, lat = r["plan"], r["lat"]
+        two = min(v for (pn, mn), v in r["results"].items() if mn == "fine")
         roof, tflops = roofline(plan, lat)
         n_tiles = plan.n_prod + plan.n_mid + plan.n_cons
         util, final = trace_occupancy(ds, torch, wl, r["kinds"][r["best"][0]], r["modes"][r["best"][1]], 0, sp, sc,
@@ -357,8 +364,8 @@ def sweep(args, torch, ds, inputs):
         mid = f" / {plan.n_mid}" if plan.n_mid else ""
         lines.append(
             f"| {wl.name} | {tile_label(ds, plan.tile_prod)} | {plan.n_prod}{mid} / {plan.n_cons} | {plan.slots} | "
-            f"{plan.waves_streamsync} / {plan.waves_fine} | {lat:.1f} ({r['best'][0]}/{r['best'][1]}) | {r['ss']:.1f} | "
-            f"{r['plain']:.1f} | {r['ss'] / lat:.3f} | {r['plain'] / lat:.3f} | {tflops:.0f} | "
+            f"{plan.waves_streamsync} / {plan.waves_fine} | {lat:.1f} ({r['best'][0]}/{r['best'][1]}) | {two:.1f} | {r['ss']:.1f} | "
+            f"{r['plain']:.1f} | {r['hw']:.1f} | {r['ss'] / lat:.3f} | {r['plain'] / lat:.3f} | {tflops:.0f} | "
             f"{roof['bound']} {100 * roof['frac']:.1f} % | {fmt(util)} | {fmt(final)} |")
         print(lines[-1], file=sys.stderr, flush=True)
         del wl
@@ -544,6 +551,8 @@ def main():
     roof, tflops = roofline(plan, lat)
     default_shape = args.w_layout == "rows" and (args.workload != "vgg_conv" or (args.hw, args.channels, args.batch) == (56, 256, 16))
     roof["traffic"] = MEASURED_TRAFFIC_BYTES.get((args.workload, M, best_mode)) if default_shape else None
+    roof["traffic_source"] = ("rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this command, recorded in profiles/ "
+                              "(a constant from that run, not measured in this one)") if roof["traffic"] else None
     roof["kernel"] = "chain_kernel (all dispatches of one chain; one dispatch in fused mode)"
     roof["per_launch"] = {"flops": plan.flops, "bytes": plan.bytes, "duration_us": lat}
     n_tiles = plan.n_prod + plan.n_mid + plan.n_cons
@@ -555,7 +564,11 @@ def main():
         "value": lat, "unit": "us", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": lat / 1e3, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": wl.name, "M": M, "policy": best_pol, "launch": best_mode, "tile": ds.tile_shape(plan.tile_prod),
+        "config": {"workload": wl.name, "M": M, "policy": best_pol, "launch": best_mode,
+                   # tile order of the headline variant: the library draws tiles from its dispatch queues (producer tiles
+                   # always handed out first) unless every tile has a resident workgroup of its own
+                   "order": "block index" if n_tiles <= plan.slots else "dispatch queues",
+                   "tile": ds.tile_shape(plan.tile_prod),
                    "tile_name": tile_label(ds, plan.tile_prod),
                    "tiles_producer": plan.n_prod, "tiles_middle": plan.n_mid, "tiles_consumer": plan.n_cons,
                    "slots": plan.slots, "waves_streamsync": plan.waves_streamsync, "waves_fine": plan.waves_fine},
@@ -563,6 +576,9 @@ def main():
         "latency_blocks_us": {f"{pn}/{mn}": [round(x, 1) for x in b] for (pn, mn), b in blocks.items()},
         "speedup_vs_streamsync": (ss / lat) if ss else None,
         "speedup_vs_plain": (plain / lat) if plain else None,
+        # the same chain in one dispatch with tiles named by the block index (DEPSYNC_FLAG_HW_ORDER): faster by the cost of
+        # the draws, but progress then rests on in-order workgroup start per XCD, so it is reported and never the headline
+        "block_index_order_us": r["hw"],
         "tflops": tflops, "pct_bf16_mfma_peak": 100 * tflops / PEAK_BF16_TFLOPS,
         "slot_utilisation": util, "final_wave_occupancy": final,
         "device": {"cus": n_cu, "clock_mhz": clock_khz / 1e3},

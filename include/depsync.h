@@ -119,14 +119,18 @@ typedef enum {
                                          (switches off the reordering of Section IV-C)       */
 #define DEPSYNC_FLAG_COUNT 2u         /* count posts / waits / polling waits in the status   */
 #define DEPSYNC_FLAG_REVERSE_ORDER 4u /* debug: hand producer tiles out in reverse order     */
-#define DEPSYNC_FLAG_HW_ORDER 8u      /* FINE/STREAMSYNC: take the tile from the hardware
-                                         block index, no dispatch counter ("avoid custom tile
-                                         order", Section IV-C).  In FINE mode only legal when the
-                                         tiles of all stages fit on the GPU at once (otherwise
-                                         DEPSYNC_EINVAL); in FUSED mode always legal, because
-                                         each XCD starts the workgroups of one dispatch in index
-                                         order, producers first, and the default there for a
-                                         chain the autotuner has not decided otherwise.       */
+#define DEPSYNC_FLAG_HW_ORDER 8u      /* take the tile from the hardware block index, no dispatch
+                                         counter ("avoid custom tile order", Section IV-C).  In FINE
+                                         mode only legal when the tiles of all stages fit on the GPU
+                                         at once (otherwise DEPSYNC_EINVAL).  In FUSED mode legal for
+                                         any chain, but for a chain of more tiles than resident
+                                         workgroups it rests on each XCD starting the workgroups of
+                                         one dispatch in index order, producers first, which HIP
+                                         does not promise (observed on MI355X; the bounded wait turns
+                                         a violation into DEPSYNC_ETIMEOUT).  Without this flag the
+                                         library names tiles by the block index only when every tile
+                                         has a resident workgroup of its own, where any start order
+                                         is safe, and draws them from the dispatch queues otherwise. */
 
 typedef struct {
     uint32_t stride;      /* STRIDEDSYNC on a GeMM chain: distance, in producer column tiles,
@@ -150,8 +154,7 @@ typedef struct {
                                          STREAMSYNC); read them with depsync_read_trace        */
 #define DEPSYNC_FLAG_QUEUE_ORDER 32u  /* FUSED: draw tiles from the dispatch queues (persistent
                                          workgroups) even where the library would name them by the
-                                         block index, its default for a chain the autotuner has
-                                         not decided otherwise                                  */
+                                         block index (chains whose tiles are all resident at once) */
 
 typedef struct sync_policy sync_policy_t;
 
@@ -349,7 +352,9 @@ enum {
                                    * left to the overlap of the stages alone)                   */
     DEPSYNC_TUNED_HW_ORDER = 2    /* one-dispatch mode names tiles by the block index instead of
                                    * drawing them from the dispatch queues (Section IV-C, the
-                                   * optimisation that avoids a custom tile order)              */
+                                   * optimisation that avoids a custom tile order); honoured only
+                                   * for chains whose tiles are all resident at once, and measured
+                                   * by the autotuner only for those (or under DEPSYNC_FLAG_HW_ORDER) */
 };
 int depsync_gemm_chain_tuned(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int* tile, int* flags);
 int depsync_conv_chain_tuned(const depsync_conv_chain_desc* d, const sync_policy_t* pol, int* tile, int* flags);

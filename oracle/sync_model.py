@@ -143,3 +143,85 @@ def gemm_chain_tiles(prod_grid: Grid, cons_grid: Grid, prod_dur: float = 1.0,
         for _x in range(cons_grid[0]):
             tiles.append(SimTile(1, cons_dur, deps))
     return tiles
+
+
+# ---- forward progress under a dispatch order (Section III-B) ----------------
+
+def simulate_dispatch(n_slots: int, tiles: List[SimTile], dispatch: Sequence[int], by_ticket: bool,
+                      spin_limit: float = None):
+    """Workgroups started in the order `dispatch` (a permutation of range(len(tiles))) on `n_slots` slots.
+
+    by_ticket=False: workgroup i runs tile i (tiles named by the block index).  A workgroup holds
+    its slot from its start; it computes once every dependency has finished, and spins until then.
+    If the tiles it waits for belong to workgroups that cannot start because spinning workgroups
+    hold every slot, nothing moves any more: Section III-B's deadlock.
+    by_ticket=True: whatever workgroup starts next takes the next tile of the list (all tiles of a
+    stage before the next stage's), so a spinning workgroup's dependencies are always held by
+    workgroups that have already started.
+    spin_limit: a wait longer than this is given up (the tile then finishes at once, marked
+    timed out, as the library's bounded wait does); None = wait for ever.
+
+    Returns (makespan or None if deadlocked, number of tiles that timed out).
+    """
+    n = len(tiles)
+    assert sorted(dispatch) == list(range(n))
+    finish = [None] * n            # finish time of tile i once known
+    started = {}                   # tile -> (slot start time)
+    waiting = []                   # started tiles whose finish time is not known yet
+    free_at = [0.0] * n_slots      # when each slot is free again (inf while held by an unresolved workgroup)
+    INF = float("inf")
+    next_wg, ticket, timed_out = 0, 0, 0
+
+    def resolve():
+        """Fix the finish time of every started tile whose dependencies' finish times are known."""
+        nonlocal timed_out
+        progress = True
+        while progress:
+            progress = False
+            for t in list(waiting):
+                deps = tiles[t].deps
+                if all(finish[d] is not None for d in deps):
+                    ready = max([started[t][0]] + [finish[d] for d in deps])
+                    if spin_limit is not None and ready - started[t][0] > spin_limit:
+                        ready = started[t][0] + spin_limit
+                        finish[t] = ready           # gives up: no work done, its post still goes out
+                        timed_out += 1
+                    else:
+                        finish[t] = ready + tiles[t].duration
+                    free_at[started[t][1]] = finish[t]
+                    waiting.remove(t)
+                    progress = True
+
+    while next_wg < n:
+        slot = min(range(n_slots), key=lambda s: free_at[s])
+        if free_at[slot] == INF:
+            # every slot is held by a workgroup whose dependencies have not even started
+            if spin_limit is None:
+                return None, timed_out
+            # bounded waits: the longest-waiting workgroup gives up first
+            t = min(waiting, key=lambda w: started[w][0])
+            finish[t] = started[t][0] + spin_limit
+            free_at[started[t][1]] = finish[t]
+            waiting.remove(t)
+            timed_out += 1
+            resolve()
+            continue
+        tile = ticket if by_ticket else dispatch[next_wg]
+        ticket += 1
+        next_wg += 1
+        started[tile] = (free_at[slot], slot)
+        free_at[slot] = INF
+        waiting.append(tile)
+        resolve()
+    resolve()
+    if waiting:
+        if spin_limit is None:
+            return None, timed_out
+        while waiting:
+            t = min(waiting, key=lambda w: started[w][0])
+            finish[t] = started[t][0] + spin_limit
+            free_at[started[t][1]] = finish[t]
+            waiting.remove(t)
+            timed_out += 1
+            resolve()
+    return max(f for f in finish if f is not None), timed_out

@@ -121,7 +121,7 @@ struct Plan {
     double flops, bytes;
     uint32_t amode;
     int dtype;
-    bool tuned_hw_order;             // the autotuner found one workgroup per tile in hardware order faster
+    int order_pref;                  // tile order the autotuner found faster for one dispatch: -1 none, 0 queues, 1 block index
 };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -341,13 +341,12 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     const int cus = device_cus(n_cu);
     if (cus <= 0) return DEPSYNC_EHIP;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    // Untuned chains run one dispatch in block-index order: what the autotuner finds faster on
-    // nearly every chain measured (no draw from the dispatch queues at all).
-    bool tuned_off = false, tuned_hw = true;
+    bool tuned_off = false;
+    int order_pref = -1;
     if (!tile) {
         const int v = tuned_tile(tune_key(d, pol));
         tile = v & 0xff;
-        if (v) { tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
+        if (v) { tuned_off = (v & 0x100) != 0; order_pref = (v & 0x200) ? 1 : 0; }
     }
     if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
     const TileShape* ts = tile_shape(tile);
@@ -362,7 +361,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     p.n_stages = last + 1;
     p.amode = A_DENSE;
     p.dtype = d->dtype;
-    p.tuned_hw_order = tuned_hw;
+    p.order_pref = order_pref;
     for (int s = 0; s < p.n_stages; ++s) p.tile[s] = tile;
     const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
     p.grid_y[0] = p.grid_y[last] = cdiv(d->M, ts->rows);
@@ -483,13 +482,12 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
     if (cus <= 0) return DEPSYNC_EHIP;
     const uint32_t M = (uint32_t)Mpix;
     int tile = d->tile_prod ? d->tile_prod : d->tile_cons;
-    // Untuned chains run one dispatch in block-index order: what the autotuner finds faster on
-    // nearly every chain measured (no draw from the dispatch queues at all).
-    bool tuned_off = false, tuned_hw = true;
+    bool tuned_off = false;
+    int order_pref = -1;
     if (!tile) {
         const int v = tuned_tile(tune_key(d, pol));
         tile = v & 0xff;
-        if (v) { tuned_off = (v & 0x100) != 0; tuned_hw = (v & 0x200) != 0; }
+        if (v) { tuned_off = (v & 0x100) != 0; order_pref = (v & 0x200) ? 1 : 0; }
     }
     if (!tile) {
         // halo: a consumer row tile reads W+1 rows beyond each end (modelled on the first two stages)
@@ -502,7 +500,7 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
     p.n_stages = n;
     p.amode = A_CONV3X3;
     p.dtype = d->dtype;
-    p.tuned_hw_order = tuned_hw;
+    p.order_pref = order_pref;
     const int kind = pol ? pol->kind : DEPSYNC_STRIDEDSYNC;
     p.slots = cus * ts->occupancy;
     for (int s = 0; s < n; ++s) {
@@ -582,7 +580,7 @@ int plan_copy(const depsync_copy_chain_desc* d, const sync_policy* pol, int n_cu
     p.bytes = 4.0 * (double)d->bytes;      // each stage reads the buffer once and writes it once
     p.amode = A_COPY;
     p.dtype = 0;
-    p.tuned_hw_order = false;
+    p.order_pref = 0;
     return DEPSYNC_OK;
 }
 
@@ -761,17 +759,27 @@ void fill_common(ChainArgs& a, sync_policy* pol, const Plan& p, uint32_t epoch) 
 int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mode, void* sp_, void* sc_) {
     hipStream_t sp = static_cast<hipStream_t>(sp_);
     const bool sync = mode != DEPSYNC_MODE_PLAIN;
-    // Tiles in the hardware's order (Section IV-C, "T"): asked for by the caller, or found faster
-    // by the autotuner for this chain in one dispatch.  In-order dispatch of the block index on
-    // every XCD means no consumer workgroup is resident while a producer one is still unlaunched.
-    // The dispatch queues remain for callers that ask for them, for the debug order and for FINE and
-    // STREAMSYNC launches, whose workgroups are not dispatched in stage order.
-    const bool want_queues = (pol->params.flags & (DEPSYNC_FLAG_QUEUE_ORDER | DEPSYNC_FLAG_REVERSE_ORDER)) != 0;
-    if (sync && mode == DEPSYNC_MODE_FUSED && (pol->force_order >= 0 ? pol->force_order == 1 : (p.tuned_hw_order && !want_queues)))
-        a.flags |= DEPSYNC_FLAG_HW_ORDER;
     uint32_t total = 0;
     for (int s = 0; s < p.n_stages; ++s) total += p.n_tiles[s];
-    if (sync && (a.flags & DEPSYNC_FLAG_HW_ORDER) && mode == DEPSYNC_MODE_FINE && total > (uint32_t)p.slots)
+    // Tile order of a one-dispatch launch.  Drawn from the dispatch queues, producer tiles are
+    // always handed out before consumer tiles, whatever order the hardware starts workgroups in
+    // (Section III-B).  Named by the block index (Section IV-C, "avoid custom tile order"), a chain
+    // of more tiles than resident workgroups progresses only if every XCD starts the workgroups of
+    // a dispatch in index order, which HIP does not promise; so the library chooses that order on
+    // its own only when every tile's workgroup is resident at once (any start order is then safe),
+    // or when the autotuner measured it for such a chain; beyond that it is the caller's explicit
+    // choice (DEPSYNC_FLAG_HW_ORDER), backed by the bounded wait.
+    const bool want_queues = (pol->params.flags & (DEPSYNC_FLAG_QUEUE_ORDER | DEPSYNC_FLAG_REVERSE_ORDER)) != 0;
+    const bool caller_hw = (pol->params.flags & DEPSYNC_FLAG_HW_ORDER) != 0;
+    const bool all_resident = total <= (uint32_t)p.slots;
+    if (pol->force_order == 1 && !all_resident && !caller_hw) return DEPSYNC_EINVAL;   // not a candidate for the autotuner
+    bool hw;
+    if (pol->force_order >= 0) hw = pol->force_order == 1;
+    else if (want_queues) hw = false;
+    else if (caller_hw) hw = true;
+    else hw = all_resident && p.order_pref != 0;
+    if (sync && mode == DEPSYNC_MODE_FUSED && hw) a.flags |= DEPSYNC_FLAG_HW_ORDER;
+    if (sync && (a.flags & DEPSYNC_FLAG_HW_ORDER) && mode == DEPSYNC_MODE_FINE && !all_resident)
         return DEPSYNC_EINVAL;
 
     // With the dispatch queues a launch needs no more workgroups than fit on the chip at once:

@@ -357,3 +357,52 @@ def test_cached_attention_agrees_with_the_prompt_phase():
     qkv = np.array([[np.log(3.0), 0.0, 4.0]])
     T = oracle.cached_attention(qkv, np.array([[[1.0]]]), np.array([[[8.0]]]), 1, 1, 1, 1)
     assert abs(T[0, 0] - (0.75 * 8.0 + 0.25 * 4.0)) < 1e-12
+
+
+# ---- forward progress of the two tile orders (Section III-B) -----------------------------------
+
+def test_block_index_order_progresses_when_workgroups_start_in_index_order():
+    # tiles named by the block index: producers first in the index space, workgroups started in
+    # index order (the assumption the one-dispatch block-index order rests on) -> same makespan as
+    # the list schedule of Fig. 1c, nothing times out
+    tiles = sm.gemm_chain_tiles((3, 2), (3, 2))
+    order = list(range(len(tiles)))
+    span, timeouts = sm.simulate_dispatch(4, tiles, order, by_ticket=False)
+    assert span == sm.simulate(4, tiles, stream_sync=False) == 3.0 and timeouts == 0
+    big = sm.gemm_chain_tiles((32, 8), (64, 8), 2.0, 1.0)
+    span, timeouts = sm.simulate_dispatch(256, big, list(range(len(big))), by_ticket=False)
+    assert span == sm.simulate(256, big, stream_sync=False) and timeouts == 0
+
+
+def test_block_index_order_deadlocks_when_consumers_start_first_and_bounded_waits_turn_it_into_timeouts():
+    # the same chain, workgroups started consumers first: six consumer workgroups on four slots
+    # spin for producers that can never start (Section III-B's deadlock) ...
+    tiles = sm.gemm_chain_tiles((3, 2), (3, 2))
+    consumers_first = list(range(6, 12)) + list(range(6))
+    span, timeouts = sm.simulate_dispatch(4, tiles, consumers_first, by_ticket=False)
+    assert span is None
+    # ... with bounded waits every workgroup ends, some of them timed out: the library's
+    # DEPSYNC_ETIMEOUT instead of a hung GPU
+    span, timeouts = sm.simulate_dispatch(4, tiles, consumers_first, by_ticket=False, spin_limit=10.0)
+    assert span is not None and timeouts > 0
+    # enough slots for every workgroup: any start order is safe (the library's rule for choosing the
+    # block-index order on its own: all tiles of the chain resident at once)
+    span, timeouts = sm.simulate_dispatch(12, tiles, consumers_first, by_ticket=False)
+    assert span == 2.0 and timeouts == 0
+
+
+def test_tiles_drawn_on_arrival_progress_under_any_start_order():
+    # the dispatch queues: whichever workgroup starts next takes the next tile, producers before
+    # consumers -> no start order can deadlock, with any number of slots
+    import random
+    tiles = sm.gemm_chain_tiles((5, 3), (7, 3), 1.5, 1.0)
+    ref = sm.simulate(4, tiles, stream_sync=False)
+    rng = random.Random(0)
+    for slots in (1, 2, 4, 9):
+        for _ in range(20):
+            order = list(range(len(tiles)))
+            rng.shuffle(order)
+            span, timeouts = sm.simulate_dispatch(slots, tiles, order, by_ticket=True)
+            assert span is not None and timeouts == 0
+            if slots == 4:
+                assert span == ref
