@@ -59,7 +59,13 @@ extern "C" {
 typedef enum {
     DEPSYNC_ROWSYNC = 0,    /* all column tiles of a producer row share a semaphore       */
     DEPSYNC_TILESYNC = 1,   /* one semaphore per producer tile                            */
-    DEPSYNC_STRIDEDSYNC = 2 /* producer tiles at a fixed stride share a semaphore         */
+    DEPSYNC_STRIDEDSYNC = 2,/* producer tiles at a fixed stride share a semaphore         */
+    DEPSYNC_AUTOSYNC = 3    /* whichever of the three depsync_*_chain_autotune_policy measured
+                               fastest for the chain's shape (Section IV-A: the policy is part
+                               of what the paper's generator searches); where nothing was
+                               measured, the rule of thumb of Section V-C: TILESYNC up to 256
+                               rows, ROWSYNC beyond, STRIDEDSYNC for attention and convolutions;
+                               copy chains: TILESYNC                                           */
 } depsync_policy_kind;
 
 /* How the two kernels of a chain are ordered. */
@@ -339,6 +345,22 @@ int depsync_conv_chain_autotune(const depsync_conv_chain_desc* d, sync_policy_t*
                                 int reps, int* tile_out);
 int depsync_conv_chain_n_autotune(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, void* stream,
                                   int reps, int* tile_out);
+
+/* The policy part of that search: runs the autotuner above under each of ROWSYNC, TILESYNC and
+ * STRIDEDSYNC (kinds the chain cannot run under are skipped), remembers the fastest kind for this
+ * chain shape and element type for the rest of the process, and with it the tile choice of every
+ * kind tried.  Policies created as DEPSYNC_AUTOSYNC resolve to the remembered kind at every
+ * launch.  `pol` lends its workspace and parameters (any kind; unchanged on return).  *kind_out,
+ * *tile_out (nullable) receive the choice; us_out (nullable) points to three floats that receive
+ * the best one-dispatch latency under each kind in microseconds, -1 where the kind was skipped.    */
+int depsync_gemm_chain_autotune_policy(const depsync_gemm_chain_desc* d, sync_policy_t* pol, void* stream,
+                                       int reps, int* kind_out, int* tile_out, float* us_out);
+int depsync_conv_chain_n_autotune_policy(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, void* stream,
+                                         int reps, int* kind_out, int* tile_out, float* us_out);
+/* The kind a chain of this shape runs under with `pol`: pol's own, or what DEPSYNC_AUTOSYNC
+ * resolves to (no device access).                                                              */
+int depsync_gemm_chain_policy(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int* kind);
+int depsync_conv_chain_n_policy(const depsync_conv_chain_n_desc* d, const sync_policy_t* pol, int* kind);
 
 /* The remembered choice for this chain shape, element type and policy kind, read or set without
  * measuring (to carry a tuning result from one process to the next).  `tile` is a DEPSYNC_TILE_*

@@ -15,7 +15,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libdepsync.so")
 
 # enums of include/depsync.h
-ROWSYNC, TILESYNC, STRIDEDSYNC = 0, 1, 2
+ROWSYNC, TILESYNC, STRIDEDSYNC, AUTOSYNC = 0, 1, 2, 3
 MODE_FINE, MODE_STREAMSYNC, MODE_PLAIN, MODE_FUSED = 0, 1, 2, 3
 MID_NONE, MID_GELU, MID_RELU, MID_SWIGLU, MID_CAUSAL_ATTN = 0, 1, 2, 3, 4
 BF16, FP16 = 0, 1
@@ -35,6 +35,8 @@ EXPORTS = [
     "depsync_mfma_calibration", "dep_copy_chain", "depsync_copy_chain_plan",
     "dep_conv_chain_n", "depsync_conv_chain_n_plan", "depsync_conv_chain_n_autotune", "depsync_workspace_bytes",
     "depsync_gemm_chain_check_waits", "depsync_conv_chain_n_check_waits", "dep_gemm_chain_static",
+    "depsync_gemm_chain_autotune_policy", "depsync_conv_chain_n_autotune_policy", "depsync_gemm_chain_policy",
+    "depsync_conv_chain_n_policy",
 ]
 
 
@@ -150,6 +152,11 @@ def _lib() -> ctypes.CDLL:
         i64p = ctypes.POINTER(ctypes.c_int64)
         L.depsync_gemm_chain_check_waits.argtypes = [ctypes.POINTER(GemmChainDesc), i32, ctypes.POINTER(PolicyParams), i32, i64p]
         L.depsync_conv_chain_n_check_waits.argtypes = [ctypes.POINTER(ConvChainNDesc), i32, ctypes.POINTER(PolicyParams), i32, i64p]
+        f3 = ctypes.POINTER(ctypes.c_float)
+        L.depsync_gemm_chain_autotune_policy.argtypes = [ctypes.POINTER(GemmChainDesc), vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), f3]
+        L.depsync_conv_chain_n_autotune_policy.argtypes = [ctypes.POINTER(ConvChainNDesc), vp, vp, i32, ctypes.POINTER(i32), ctypes.POINTER(i32), f3]
+        L.depsync_gemm_chain_policy.argtypes = [ctypes.POINTER(GemmChainDesc), vp, ctypes.POINTER(i32)]
+        L.depsync_conv_chain_n_policy.argtypes = [ctypes.POINTER(ConvChainNDesc), vp, ctypes.POINTER(i32)]
         L.dep_gemm_chain_static.argtypes = [ctypes.POINTER(GemmChainDesc), i32, ctypes.POINTER(PolicyParams), vp]
         L.depsync_row_major.argtypes = [i32] * 4
         L.depsync_policy_sem.argtypes = [i32] * 6
@@ -355,6 +362,32 @@ def conv_chain_autotune(x, w1, mid, w2, out, policy: SyncPolicy, stream=None, re
     _check(_lib().depsync_conv_chain_autotune(ctypes.byref(d), policy.handle, _stream_handle(stream), reps,
                                               ctypes.byref(tile)), "depsync_conv_chain_autotune")
     return tile.value
+
+
+def gemm_chain_autotune_policy(X, W1t, H, W2t, Y, policy: SyncPolicy, mid: int = MID_GELU, stream=None, reps: int = 3, **attn):
+    """Autotune the chain under every policy kind and remember the fastest for its shape (what AUTOSYNC
+    policies resolve to).  Returns (kind, tile, [us under ROWSYNC, TILESYNC, STRIDEDSYNC; -1 = cannot run])."""
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, TILE_AUTO, **attn)
+    kind, tile, us = ctypes.c_int(-1), ctypes.c_int(0), (ctypes.c_float * 3)()
+    _check(_lib().depsync_gemm_chain_autotune_policy(ctypes.byref(d), policy.handle, _stream_handle(stream), reps,
+                                                     ctypes.byref(kind), ctypes.byref(tile), us), "depsync_gemm_chain_autotune_policy")
+    return kind.value, tile.value, list(us)
+
+
+def conv_chain_n_autotune_policy(x, ws, outs, policy: SyncPolicy, stream=None, reps: int = 3):
+    d = _conv_n_desc(x, ws, outs, TILE_AUTO)
+    kind, tile, us = ctypes.c_int(-1), ctypes.c_int(0), (ctypes.c_float * 3)()
+    _check(_lib().depsync_conv_chain_n_autotune_policy(ctypes.byref(d), policy.handle, _stream_handle(stream), reps,
+                                                       ctypes.byref(kind), ctypes.byref(tile), us), "depsync_conv_chain_n_autotune_policy")
+    return kind.value, tile.value, list(us)
+
+
+def gemm_chain_policy(X, W1t, H, W2t, Y, policy: SyncPolicy, mid: int = MID_GELU, **attn) -> int:
+    """The policy kind a chain of this shape runs under with `policy` (what AUTOSYNC resolves to)."""
+    d = _gemm_desc(X, W1t, H, W2t, Y, mid, TILE_AUTO, **attn)
+    kind = ctypes.c_int(-1)
+    _check(_lib().depsync_gemm_chain_policy(ctypes.byref(d), policy.handle, ctypes.byref(kind)), "depsync_gemm_chain_policy")
+    return kind.value
 
 
 TUNED_NO_SPLIT, TUNED_HW_ORDER = 1, 2

@@ -181,15 +181,34 @@ struct TuneKey {
 std::map<TuneKey, int> g_tuned;
 std::mutex g_tuned_mutex;
 
-TuneKey tune_key(const depsync_gemm_chain_desc* d, const sync_policy* pol) {
-    return TuneKey{{d->w_layout ? 2 : 0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, pol ? pol->kind : -1, d->heads, d->seq, d->cached, 0}};
+// `kind`: the policy kind the entry is for; -2 for the entry that remembers the best kind of a shape.
+TuneKey tune_key(const depsync_gemm_chain_desc* d, int kind) {
+    return TuneKey{{d->w_layout ? 2 : 0, d->M, d->K1, d->N1, d->N2, d->dtype, d->mid, kind, d->heads, d->seq, d->cached, 0}};
 }
-TuneKey tune_key(const depsync_conv_chain_desc* d, const sync_policy* pol) {
-    return TuneKey{{1, d->B, d->H, d->W, d->C, d->K1, d->K2, d->dtype, pol ? pol->kind : -1, 0, 0, 0}};
+TuneKey tune_key(const depsync_conv_chain_n_desc* d, int kind) {
+    if (d->n == 2) return TuneKey{{1, d->B, d->H, d->W, d->C, d->K[0], d->K[1], d->dtype, kind, 0, 0, 0}};
+    return TuneKey{{3, d->B, d->H, d->W, d->C, d->K[0], d->K[1], d->dtype, kind, d->n, d->K[2], d->n > 3 ? d->K[3] : 0}};
 }
-TuneKey tune_key(const depsync_conv_chain_n_desc* d, const sync_policy* pol) {
-    if (d->n == 2) return TuneKey{{1, d->B, d->H, d->W, d->C, d->K[0], d->K[1], d->dtype, pol ? pol->kind : -1, 0, 0, 0}};
-    return TuneKey{{3, d->B, d->H, d->W, d->C, d->K[0], d->K[1], d->dtype, pol ? pol->kind : -1, d->n, d->K[2], d->n > 3 ? d->K[3] : 0}};
+depsync_conv_chain_n_desc as_chain_n(const depsync_conv_chain_desc& d);
+TuneKey tune_key(const depsync_conv_chain_desc* d, int kind) {
+    const depsync_conv_chain_n_desc c = as_chain_n(*d);
+    return tune_key(&c, kind);
+}
+// The policy kind a chain runs under: the policy's own, or for DEPSYNC_AUTOSYNC the one
+// depsync_*_chain_autotune_policy measured fastest for the chain's shape, else `fallback`.
+int tuned_tile(const TuneKey& k);
+template <class Desc>
+int effective_kind(const Desc* d, const sync_policy* pol, int fallback) {
+    if (!pol) return fallback;
+    if (pol->kind != DEPSYNC_AUTOSYNC) return pol->kind;
+    const int v = tuned_tile(tune_key(d, -2));
+    return v ? v - 1 : fallback;
+}
+// Rule of thumb where nothing was measured (Section V-C): per-tile waits up to 256 rows, per-row
+// waits beyond; the attention chain waits on strided groups of tiles.
+int default_kind(const depsync_gemm_chain_desc* d) {
+    if (d->mid == DEPSYNC_MID_CAUSAL_ATTN) return DEPSYNC_STRIDEDSYNC;
+    return d->M <= 256 ? DEPSYNC_TILESYNC : DEPSYNC_ROWSYNC;
 }
 int tuned_tile(const TuneKey& k) {
     std::lock_guard<std::mutex> g(g_tuned_mutex);
@@ -344,7 +363,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     bool tuned_off = false;
     int order_pref = -1;
     if (!tile) {
-        const int v = tuned_tile(tune_key(d, pol));
+        const int v = tuned_tile(tune_key(d, pol ? effective_kind(d, pol, default_kind(d)) : -1));
         tile = v & 0xff;
         if (v) { tuned_off = (v & 0x100) != 0; order_pref = (v & 0x200) ? 1 : 0; }
     }
@@ -377,7 +396,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     for (int s = 0; s < p.n_stages; ++s) { p.n_tiles[s] = p.grid_x[s] * p.grid_y[s]; p.ksplit[s] = 1; }
 
     // dependency of stage s on stage s-1, per policy
-    const int kind = pol ? pol->kind : DEPSYNC_ROWSYNC;
+    const int kind = effective_kind(d, pol, pol ? default_kind(d) : DEPSYNC_ROWSYNC);
     uint32_t off = 0;
     for (int s = 1; s < p.n_stages; ++s) {
         uint32_t dk = policy_dep_kind_gemm(kind);
@@ -485,7 +504,7 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
     bool tuned_off = false;
     int order_pref = -1;
     if (!tile) {
-        const int v = tuned_tile(tune_key(d, pol));
+        const int v = tuned_tile(tune_key(d, pol ? effective_kind(d, pol, DEPSYNC_STRIDEDSYNC) : -1));
         tile = v & 0xff;
         if (v) { tuned_off = (v & 0x100) != 0; order_pref = (v & 0x200) ? 1 : 0; }
     }
@@ -501,7 +520,7 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
     p.amode = A_CONV3X3;
     p.dtype = d->dtype;
     p.order_pref = order_pref;
-    const int kind = pol ? pol->kind : DEPSYNC_STRIDEDSYNC;
+    const int kind = effective_kind(d, pol, DEPSYNC_STRIDEDSYNC);
     p.slots = cus * ts->occupancy;
     for (int s = 0; s < n; ++s) {
         p.tile[s] = tile;
@@ -556,7 +575,7 @@ int plan_copy(const depsync_copy_chain_desc* d, const sync_policy* pol, int n_cu
     if (!aligned16(d->src) || !aligned16(d->dst) || (reinterpret_cast<uintptr_t>(d->mid) & 127u)) return DEPSYNC_EINVAL;
     const uint32_t tb = d->tile_bytes ? d->tile_bytes : 65536u;
     if (tb % 4096u) return DEPSYNC_EINVAL;
-    if (pol->kind == DEPSYNC_STRIDEDSYNC) return DEPSYNC_ENOTIMPL;
+    if (pol->kind == DEPSYNC_STRIDEDSYNC) return DEPSYNC_ENOTIMPL;   // (DEPSYNC_AUTOSYNC: per-tile waits)
     const uint64_t tiles64 = (d->bytes + tb - 1) / tb;
     if (tiles64 > (1u << 20) || (d->bytes >> 4) > 0xffffffffull) return DEPSYNC_EINVAL;
     const uint32_t tiles = (uint32_t)tiles64;
@@ -826,8 +845,12 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
             a.stage_lo = 0u;
             a.stage_hi = (uint32_t)s;
             a.draw_cas = s == last ? 0u : 1u;
-            // (the last stage's launch may have to run the whole chain: as many workgroups as all of it could use)
-            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, true, blocks(s == last && queues ? total : p.n_tiles[s]), st, a));
+            // (the last stage's launch may have to run the whole chain: as many workgroups as all of it
+            // could use; the side launches together take at most half of the slots, so that whichever
+            // launch starts first, the caller's finds room next to them)
+            uint32_t nb = blocks(s == last && queues ? total : p.n_tiles[s]);
+            if (s != last && queues) nb = std::min<uint32_t>(nb, std::max<uint32_t>(1u, (uint32_t)p.slots / (2u * (uint32_t)last)));
+            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, true, nb, st, a));
             off += p.n_tiles[s];
         }
         a.draw_cas = 0u;
@@ -927,7 +950,8 @@ extern "C" {
 int sync_policy_create(depsync_policy_kind kind, const depsync_policy_params* params, sync_policy_t** out) {
     if (!out) return DEPSYNC_EINVAL;
     *out = nullptr;
-    if (kind != DEPSYNC_ROWSYNC && kind != DEPSYNC_TILESYNC && kind != DEPSYNC_STRIDEDSYNC) return DEPSYNC_EINVAL;
+    if (kind != DEPSYNC_ROWSYNC && kind != DEPSYNC_TILESYNC && kind != DEPSYNC_STRIDEDSYNC && kind != DEPSYNC_AUTOSYNC)
+        return DEPSYNC_EINVAL;
     sync_policy* p = new (std::nothrow) sync_policy();
     if (!p) return DEPSYNC_ENOMEM;
     p->kind = kind;
@@ -1135,8 +1159,9 @@ namespace {
 // along K and with tiles drawn from the dispatch queues or named by the block index (one-dispatch mode, HIP events on the caller's stream, two passes, blocks long enough
 // to time), and remember the fastest combination.
 template <class Desc, class Run>
-int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* tile_out, Run run) {
+int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* tile_out, Run run, float* best_ms_out = nullptr) {
     if (!d || !pol) return DEPSYNC_EINVAL;
+    if (pol->kind == DEPSYNC_AUTOSYNC) return DEPSYNC_EINVAL;   // per kind: see autotune_policy
     if (reps <= 0) reps = 3;
     hipEvent_t e0, e1;
     HIP_TRY(hipEventCreate(&e0));
@@ -1186,16 +1211,17 @@ int autotune(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* til
     if (best == 0) return DEPSYNC_EINVAL;
     {
         std::lock_guard<std::mutex> g(g_tuned_mutex);
-        g_tuned[tune_key(d, pol)] = best;
+        g_tuned[tune_key(d, pol->kind)] = best;
     }
     if (tile_out) *tile_out = best & 0xff;
+    if (best_ms_out) *best_ms_out = best_ms;
     return DEPSYNC_OK;
 }
 // flags of a remembered choice: bit 0 no split along K, bit 1 tiles in hardware order
 template <class Desc>
 int get_tuned(const Desc* d, const sync_policy* pol, int* tile, int* flags) {
     if (!d || !pol || !tile || !flags) return DEPSYNC_EINVAL;
-    const int v = tuned_tile(tune_key(d, pol));
+    const int v = tuned_tile(tune_key(d, effective_kind(d, pol, -1)));
     *tile = v & 0xff;
     *flags = (v >> 8) & 3;
     return DEPSYNC_OK;
@@ -1204,14 +1230,71 @@ template <class Desc>
 int set_tuned(const Desc* d, const sync_policy* pol, int tile, int flags) {
     if (!d || !pol || tile < 0 || tile >= DEPSYNC_TILE__COUNT || (flags & ~3)) return DEPSYNC_EINVAL;
     std::lock_guard<std::mutex> g(g_tuned_mutex);
-    if (tile == 0) g_tuned.erase(tune_key(d, pol));
-    else g_tuned[tune_key(d, pol)] = tile | (flags << 8);
+    if (pol->kind == DEPSYNC_AUTOSYNC) return DEPSYNC_EINVAL;
+    if (tile == 0) g_tuned.erase(tune_key(d, pol->kind));
+    else g_tuned[tune_key(d, pol->kind)] = tile | (flags << 8);
+    return DEPSYNC_OK;
+}
+
+
+// The policy part of the search of Section IV-A: autotune the chain under every policy kind it can
+// run with and remember the kind of the fastest for the chain's shape (what DEPSYNC_AUTOSYNC
+// policies then resolve to).  `pol` lends its workspace and parameters; its kind is restored.
+template <class Desc, class Run>
+int autotune_policy(const Desc* d, sync_policy* pol, hipStream_t sp, int reps, int* kind_out, int* tile_out, float* us_out, Run run) {
+    if (!d || !pol) return DEPSYNC_EINVAL;
+    const int own_kind = pol->kind;
+    int best_kind = -1, best_tile = 0, rc = DEPSYNC_OK;
+    float best_ms = 0.f;
+    for (int kind = DEPSYNC_ROWSYNC; kind <= DEPSYNC_STRIDEDSYNC; ++kind) {
+        pol->kind = kind;
+        int tile = 0;
+        float ms = 0.f;
+        const int r = autotune(d, pol, sp, reps, &tile, run, &ms);
+        if (us_out) us_out[kind] = r == DEPSYNC_OK ? ms * 1e3f : -1.f;
+        if (r == DEPSYNC_EINVAL || r == DEPSYNC_ENOTIMPL) continue;     // the chain cannot run under this kind
+        if (r != DEPSYNC_OK) { rc = r; break; }
+        if (best_kind < 0 || ms < best_ms) { best_kind = kind; best_ms = ms; best_tile = tile; }
+    }
+    pol->kind = own_kind;
+    if (rc != DEPSYNC_OK) return rc;
+    if (best_kind < 0) return DEPSYNC_EINVAL;
+    {
+        std::lock_guard<std::mutex> g(g_tuned_mutex);
+        g_tuned[tune_key(d, -2)] = best_kind + 1;
+    }
+    if (kind_out) *kind_out = best_kind;
+    if (tile_out) *tile_out = best_tile;
     return DEPSYNC_OK;
 }
 
 }  // namespace
 
 extern "C" {
+
+int depsync_gemm_chain_autotune_policy(const depsync_gemm_chain_desc* d, sync_policy_t* pol, void* stream, int reps,
+                                       int* kind_out, int* tile_out, float* us_out) {
+    return autotune_policy(d, pol, static_cast<hipStream_t>(stream), reps, kind_out, tile_out, us_out,
+                           [&](const depsync_gemm_chain_desc* dd) { return dep_gemm_chain(dd, pol, DEPSYNC_MODE_FUSED, stream, nullptr); });
+}
+
+int depsync_conv_chain_n_autotune_policy(const depsync_conv_chain_n_desc* d, sync_policy_t* pol, void* stream, int reps,
+                                         int* kind_out, int* tile_out, float* us_out) {
+    return autotune_policy(d, pol, static_cast<hipStream_t>(stream), reps, kind_out, tile_out, us_out,
+                           [&](const depsync_conv_chain_n_desc* dd) { return dep_conv_chain_n(dd, pol, DEPSYNC_MODE_FUSED, stream, nullptr); });
+}
+
+int depsync_gemm_chain_policy(const depsync_gemm_chain_desc* d, const sync_policy_t* pol, int* kind) {
+    if (!d || !pol || !kind) return DEPSYNC_EINVAL;
+    *kind = effective_kind(d, pol, default_kind(d));
+    return DEPSYNC_OK;
+}
+
+int depsync_conv_chain_n_policy(const depsync_conv_chain_n_desc* d, const sync_policy_t* pol, int* kind) {
+    if (!d || !pol || !kind) return DEPSYNC_EINVAL;
+    *kind = effective_kind(d, pol, DEPSYNC_STRIDEDSYNC);
+    return DEPSYNC_OK;
+}
 
 int depsync_gemm_chain_autotune(const depsync_gemm_chain_desc* d, sync_policy_t* pol, void* stream, int reps,
                                 int* tile_out) {
@@ -1442,7 +1525,7 @@ sync_policy host_policy(int kind, const depsync_policy_params* params) {
     return hp;
 }
 
-bool valid_kind(int kind) { return kind == DEPSYNC_ROWSYNC || kind == DEPSYNC_TILESYNC || kind == DEPSYNC_STRIDEDSYNC; }
+bool valid_kind(int kind) { return kind == DEPSYNC_ROWSYNC || kind == DEPSYNC_TILESYNC || kind == DEPSYNC_STRIDEDSYNC || kind == DEPSYNC_AUTOSYNC; }
 
 }  // namespace
 

@@ -383,9 +383,12 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         const int pb = p - (NSA - NSB);    // B's step issued alongside A's step p
         set_next_A(min(kb + (uint32_t)p, ke - 1));
         if (pb >= 0) set_next_B(min(kb + (uint32_t)pb, ke - 1));
-        if (kb + (uint32_t)p < ke && (p % SPK) == 0) dep_before_request((kb + p) / SPK, pb >= 0 ? pb : 0, pb >= 0);
+        // the weights of the step go out before the look at the semaphores (the load/wait reordering
+        // of Section IV-C), so the poll's round trip is not added to their latency
+        if (reorder && pb >= 0) issue_B(pb);
+        if (kb + (uint32_t)p < ke && (p % SPK) == 0) dep_before_request((kb + p) / SPK, pb >= 0 ? pb : 0, false);
         if (p == 0 && tracing) t_ready = now_ticks();
-        if (pb >= 0) issue_B(pb);
+        if (!reorder && pb >= 0) issue_B(pb);
         issue_A(p);
     }
 

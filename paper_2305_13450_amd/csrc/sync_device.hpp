@@ -72,13 +72,14 @@ __device__ __forceinline__ void sem_wait(WaitCtx& w, const uint32_t* sem, uint32
     uint32_t spins = 0;
     uint32_t nap = 0;
     while (!sem_reached(v, target)) {
-        // back off: 8, 16, 32, 64, then 127 units of 64 clocks (about 3 us) between polls, so that
-        // hundreds of waiting waves do not queue up on the semaphore's memory channel
-        if (nap == 0) __builtin_amdgcn_s_sleep(8);
-        else if (nap == 1) __builtin_amdgcn_s_sleep(16);
-        else if (nap == 2) __builtin_amdgcn_s_sleep(32);
-        else if (nap == 3) __builtin_amdgcn_s_sleep(64);
-        else __builtin_amdgcn_s_sleep(127);
+        // back off: 2, 4, 8, then 16 units of 64 clocks (about 0.5 us) between polls: a producer
+        // tile of a short chain lasts a few microseconds, and a wave that sleeps through its
+        // post adds the rest of its nap to the chain; waiting waves poll a few dozen
+        // different lines, which the L2 serves without trouble at that rate
+        if (nap == 0) __builtin_amdgcn_s_sleep(2);
+        else if (nap == 1) __builtin_amdgcn_s_sleep(4);
+        else if (nap == 2) __builtin_amdgcn_s_sleep(8);
+        else __builtin_amdgcn_s_sleep(16);
         ++nap;
         v = sem_load(sem);
         if (limit != 0 && ++spins >= limit) {
@@ -287,17 +288,24 @@ struct Drawer {
     // the counters, and take an entry only by compare-and-swap on a value seen to lie inside this
     // chain's part of the counter's range.  Such a launch never moves a counter of another chain.
     __device__ __forceinline__ bool draw_late(uint32_t& stage, uint32_t& tx, uint32_t& ty) {
-        for (; open <= a.stage_hi; ++open) {
+        for (; open <= a.stage_hi; ++open, cur_q = home) {
             const StageDesc& st = a.st[open];
+            bool all = false;                                  // look at the queue drawn from last first, then at all eight
             for (;;) {
-                look();
-                const uint32_t avail = available();
-                if (avail == 0) break;                        // handed out (or a later chain's): next stage
-                const uint32_t q = first_from_home(avail);
-                const uint32_t len = queue_len(st, q);
-                uint32_t seen = 0;                             // c[q] without indexing the array by a run-time value
+                uint32_t q = cur_q, seen;
+                if (!all) {
+                    seen = __hip_atomic_load(counter(q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if (seen - base(queue_len(st, q)) >= queue_len(st, q)) { all = true; continue; }
+                } else {
+                    look();
+                    const uint32_t avail = available();
+                    if (avail == 0) break;                    // handed out (or a later chain's): next stage
+                    q = first_from_home(avail);
+                    seen = 0;                                  // c[q] without indexing the array by a run-time value
 #pragma unroll
-                for (int j = 0; j < 8; ++j) seen = (uint32_t)j == q ? c[j] : seen;
+                    for (int j = 0; j < 8; ++j) seen = (uint32_t)j == q ? c[j] : seen;
+                }
+                const uint32_t len = queue_len(st, q);
                 uint32_t expected = seen;
                 if (__hip_atomic_compare_exchange_strong(counter(q), &expected, seen + 1u, __ATOMIC_RELAXED, __ATOMIC_RELAXED,
                                                          __HIP_MEMORY_SCOPE_AGENT)) {

@@ -262,11 +262,11 @@ def test_autotune_picks_a_tile_the_library_then_uses():
 
 
 def test_remembered_hardware_order_alternates_with_the_dispatch_queues():
-    # A remembered choice with TUNED_HW_ORDER makes one-dispatch launches name tiles by the block
-    # index while two-stream and stream-sync launches of the same policy keep drawing from the
-    # queues: the queue counters then advance on some chains only.  More tiles than workgroup
-    # slots, several chains of each kind on one policy, same bits every time.
-    M, K1, N1, N2 = 2048, 256, 2048, 1024
+    # On a chain whose tiles are all resident at once, one-dispatch launches name tiles by the block
+    # index (also with a remembered TUNED_HW_ORDER) while two-stream and stream-sync launches of the
+    # same policy draw from the queues: the queue counters then advance on some chains only.
+    # Several chains of each kind on one policy, same bits every time.
+    M, K1, N1, N2 = 512, 256, 2048, 1024
     t = inputs.mlp(M, K1, N1, N2, seed=61)
     Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
     X, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
@@ -277,7 +277,7 @@ def test_remembered_hardware_order_alternates_with_the_dispatch_queues():
     ds.gemm_chain_set_tuned(X, W1t, H, W2t, Y, pol, ds.TILE_64x64, ds.TUNED_HW_ORDER | ds.TUNED_NO_SPLIT)
     assert ds.gemm_chain_tuned(X, W1t, H, W2t, Y, pol) == (ds.TILE_64x64, ds.TUNED_HW_ORDER | ds.TUNED_NO_SPLIT)
     plan = ds.gemm_chain_plan(X, W1t, H, W2t, Y, pol)
-    assert plan.tile_prod == ds.TILE_64x64 and plan.n_prod + plan.n_cons > plan.slots
+    assert plan.tile_prod == ds.TILE_64x64 and plan.n_prod + plan.n_cons <= plan.slots
     order = [ds.MODE_FUSED, ds.MODE_FINE, ds.MODE_FUSED, ds.MODE_STREAMSYNC, ds.MODE_FUSED, ds.MODE_FUSED,
              ds.MODE_FINE, ds.MODE_FINE, ds.MODE_FUSED]
     first = None
@@ -294,6 +294,42 @@ def test_remembered_hardware_order_alternates_with_the_dispatch_queues():
     with pytest.raises(ds.DepsyncError):
         ds.gemm_chain_set_tuned(X, W1t, H, W2t, Y, pol, 99)
     pol.destroy()
+
+
+def test_autosync_policy_resolves_to_the_measured_kind():
+    # Section IV-A: the policy is part of the search.  An AUTOSYNC policy runs under the rule of
+    # thumb (per-tile waits up to 256 rows) until depsync_gemm_chain_autotune_policy has measured
+    # the chain under every kind; then it runs under the remembered kind.  Either way its results
+    # are those of a policy created with that kind, bit for bit.
+    M, K1, N1, N2 = 192, 512, 1152, 640       # a shape no other test uses (choices are kept per shape)
+    t = inputs.mlp(M, K1, N1, N2, seed=71)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    X, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
+    H = torch.empty((M, N1), dtype=X.dtype, device="cuda")
+    Y = torch.empty((M, N2), dtype=X.dtype, device="cuda")
+    auto = ds.SyncPolicy(ds.AUTOSYNC, flags=ds.FLAG_COUNT)
+    assert ds.gemm_chain_policy(X, W1t, H, W2t, Y, auto) == ds.TILESYNC
+    big = torch.empty((512, K1), dtype=X.dtype, device="cuda")
+    assert ds.gemm_chain_policy(big, W1t, torch.empty((512, N1), dtype=X.dtype, device="cuda"), W2t,
+                                torch.empty((512, N2), dtype=X.dtype, device="cuda"), auto) == ds.ROWSYNC
+    kind, tile, us = ds.gemm_chain_autotune_policy(X, W1t, H, W2t, Y, auto, reps=2)
+    print(f"autotune_policy: kind {kind} tile {tile} us {us}", flush=True)
+    assert kind in (ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC) and us[kind] > 0 and us[kind] == min(u for u in us if u > 0)
+    assert ds.gemm_chain_policy(X, W1t, H, W2t, Y, auto) == kind
+    auto.destroy()
+    auto = ds.SyncPolicy(ds.AUTOSYNC, flags=ds.FLAG_COUNT)     # a fresh one: the tuning runs counted on the other
+    explicit = ds.SyncPolicy(kind, flags=ds.FLAG_COUNT)
+    assert ds.gemm_chain_plan(X, W1t, H, W2t, Y, auto).as_dict() == ds.gemm_chain_plan(X, W1t, H, W2t, Y, explicit).as_dict()
+    assert ds.gemm_chain_plan(X, W1t, H, W2t, Y, auto).tile_prod == tile
+    for mode in MODES:
+        Ha, Ya = run_gemm_chain(t["X"], t["W1"], t["W2"], auto, mode)
+        He, Ye = run_gemm_chain(t["X"], t["W1"], t["W2"], explicit, mode)
+        assert torch.equal(Ha, He) and torch.equal(Ya, Ye)
+        assert mid_err(Ha, Href) <= TOL_MID and rel_err(Ya, Yref) <= TOL_BF16
+    sa, se = auto.status(), explicit.status()
+    assert (sa.posts, sa.waits) == (se.posts, se.waits) and sa.timed_out == 0      # the same semaphore traffic: the same policy
+    auto.destroy()
+    explicit.destroy()
 
 
 def test_trace_records_cover_every_tile_in_order():
