@@ -116,6 +116,7 @@ struct Plan {
     size_t partial_off[4];           // first float of the stage's partial tiles
     size_t partial_floats;           // scratch the chain needs
     uint32_t n_arrive;               // arrival counters the chain needs
+    uint32_t part_floats[4];         // floats one part of a split tile of the stage leaves in the scratch buffer (0: rows x columns of its tile)
     uint32_t n_sems;
     int slots;
     double flops, bytes;
@@ -304,7 +305,7 @@ int finish_split(Plan& p) {
         if (p.ksplit[s] > 1) {
             const TileShape* ts = tile_shape(p.tile[s]);
             arr += real;
-            fl += (size_t)real * p.ksplit[s] * ts->rows * ts->cols;
+            fl += (size_t)real * p.ksplit[s] * (p.part_floats[s] ? p.part_floats[s] : (uint32_t)(ts->rows * ts->cols));
         }
     }
     p.partial_floats = fl;
@@ -440,6 +441,20 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
         uint32_t ks = std::min<uint32_t>(8u, ((uint32_t)d->cached + 1u) / 256u);
         while (ks > 1 && p.n_tiles[1] * ks > (uint32_t)p.slots) --ks;
         p.ksplit[1] = std::max<uint32_t>(ks, 1u);
+        p.part_floats[1] = 130;
+    } else if (attn) {
+        // prompt phase: a causal tile walks its key blocks one after the other, the last query block
+        // of a sequence the most.  Where the stage leaves most of the chip idle its keys are split
+        // over up to 8 workgroups of at least 4 key blocks (256 keys) each.  A stage of many tiles is
+        // left alone: measured on the GPT-3 shard at 2048 tokens, the parts (which re-read the
+        // queries and exchange 65 KB of partial results each) shorten the stage but crowd out the
+        // output GeMM's tiles that otherwise run next to the long attention tiles (404 -> 450 us).
+        const uint32_t max_blocks = ((uint32_t)d->cached + (uint32_t)d->seq - 1u) / 64u + 1u;
+        const uint32_t want = pol ? pol->params.ksplit : 0;
+        const bool sparse = 2u * p.n_tiles[1] < (uint32_t)p.slots;
+        uint32_t ks = want ? want : ((tuned_off || !sparse) ? 1u : (max_blocks + 3u) / 4u);
+        p.ksplit[1] = std::min<uint32_t>(8u, std::max<uint32_t>(ks, 1u));
+        p.part_floats[1] = 256 * 64 + 2 * 256;
     }
     {
         const uint32_t dk = p.dep_kind[last];

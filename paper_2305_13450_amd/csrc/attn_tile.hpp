@@ -63,8 +63,15 @@ __device__ __forceinline__ void attn_wait_qkv(WaitCtx& w, const StageDesc& s, ui
     }
 }
 
+// Floats one part of a tile split along the keys leaves in the scratch buffer: the un-normalised
+// O^T accumulators of the 256 lanes (64 each), then every lane's running maximum and sum.
+constexpr uint32_t ATT_PART_FLOATS = 256 * 64 + 2 * 256;
+// Key blocks per part when a tile's keys are split over workgroups (at least this many: a part
+// re-reads the queries and leaves 65 KB of partial results).
+constexpr uint32_t ATT_MIN_PART_BLOCKS = 4;
+
 template <typename T, bool SYNC, class DR>
-__device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc& s, uint32_t head, uint32_t qblk,
+__device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc& s, uint32_t head, uint32_t tyz,
                                           uint32_t rel_ticket, char* lds, uint64_t t_enter, DR& dr) {
     using M = Mma<T>;
     using V8 = typename M::V8;
@@ -76,6 +83,13 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     const uint32_t seq = uni(s.seq), heads = uni(s.heads);
     const uint32_t E = heads * ATT_D;
     const uint32_t ld = uni(s.lda), ldt = uni(s.ldc);
+    // A long causal tile is one dependent chain of key blocks, so the stage may split every tile's
+    // keys over KS workgroups (the stage's split, as for the GeMM tiles): part z takes a run of
+    // whole key blocks, leaves un-normalised results, maxima and sums in the scratch buffer and
+    // counts itself in; the last part to arrive combines the parts in key order, normalises,
+    // stores and posts.  Tiles of few key blocks use fewer parts (the rest find nothing to do).
+    const uint32_t KS = uni(s.ksplit);
+    const uint32_t qblk = tyz / KS, part = tyz % KS;
     const uint32_t qblocks = (seq + ATT_BQ - 1) / ATT_BQ;
     const uint32_t b = qblk / qblocks, qb = qblk % qblocks;      // sequence, query block inside it
     const uint32_t seq_row0 = b * seq;                            // first row of the sequence
@@ -92,6 +106,20 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     const bool tracing = SYNC && (args.flags & DS_FLAG_TRACE) && args.trace != nullptr && rel_ticket < args.trace_cap;
     uint64_t t_start = 0, t_ready = 0;
     if (tracing) t_start = now_ticks();
+
+    const uint32_t nblk = (cached + q_last) / ATT_BK + 1;         // key blocks the tile touches
+    const uint32_t chunk = max((nblk + KS - 1) / KS, ATT_MIN_PART_BLOCKS);   // key blocks per part
+    const uint32_t nparts = (nblk + chunk - 1) / chunk;           // parts that have any (<= KS)
+    const uint32_t kb_begin = part * chunk, kb_end = min(nblk, kb_begin + chunk);
+    if (part >= nparts) {                                          // nothing for this part: the tile is short
+        if (tracing && tid == 0) {
+            TraceRec r;
+            r.rel = rel_ticket; r.where = hw_where(2u); r.tx = head; r.ty = tyz;
+            r.t_enter = t_enter; r.t_start = t_start; r.t_ready = t_start; r.t_end = now_ticks();
+            args.trace[rel_ticket] = r;
+        }
+        return;
+    }
 
     attn_wait_qkv<SYNC>(wctx, s, head, seq_row0, seq_row0 + q_last);
     if (tracing) t_ready = now_ticks();
@@ -117,7 +145,6 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     // While block kb is used, the K and V rows of block kb+1 are DMA'd into LDS (no registers
     // held); V is transposed LDS to LDS at the top of the next iteration.
     const uint32_t wave_q_last = min(q0 + wave * 32 + 31, seq - 1);
-    const uint32_t nblk = (cached + q_last) / ATT_BK + 1;         // key blocks the tile touches
     char* const ldsVraw = lds + 2 * ATT_BLK_BYTES;
     char* const ldsV = lds + 3 * ATT_BLK_BYTES;
     auto fetch = [&](uint32_t kb) __attribute__((always_inline)) {
@@ -140,9 +167,9 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
             dma16(gv + chunk * 16, ldsVraw + (i * 256 + wave * 64) * 16);   // V rows, same swizzle
         }
     };
-    fetch(0);
+    fetch(kb_begin);
 
-    for (uint32_t kb = 0; kb < nblk; ++kb) {
+    for (uint32_t kb = kb_begin; kb < kb_end; ++kb) {
         const uint32_t k0 = kb * ATT_BK;
         char* ldsK = lds + (kb & 1u) * ATT_BLK_BYTES;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");          // this wave's part of block kb has landed
@@ -160,7 +187,7 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
             }
         }
         __syncthreads();   // V^T complete; the raw V rows and the other K buffer are free again
-        if (kb + 1 < nblk) fetch(kb + 1);
+        if (kb + 1 < kb_end) fetch(kb + 1);
 
         if (k0 <= cached + wave_q_last) {   // blocks entirely above this wave's diagonal contribute nothing
             // ---- S^T for the two 32-key halves of the block ----
@@ -236,8 +263,76 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     }
 
     dr.peek();   // the look at the dispatch queues for the next tile travels while the result is stored
+    // ---- keys split over several workgroups: leave the part, carry on only as the last to arrive ----
+    bool finish = true;
+    if (nparts > 1) {
+        const uint32_t tile_lin = qblk * heads + head;
+        float* const parts = s.partials + (size_t)tile_lin * KS * ATT_PART_FLOATS;
+        float* const mine = parts + (size_t)part * ATT_PART_FLOATS;
+        // fragment order, 16 bytes per lane next to its neighbours', written through to memory so
+        // that the count below can follow
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                typedef float f32x2 __attribute__((ext_vector_type(2)));
+                const f32x2 v2 = {o[i][2 * q], o[i][2 * q + 1]};
+                uint64_t bits;
+                __builtin_memcpy(&bits, &v2, 8);
+                __hip_atomic_store(reinterpret_cast<uint64_t*>(mine + (((i * 8 + q) * 256 + tid) << 1)), bits, __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT);
+            }
+        __hip_atomic_store(mine + 256 * 64 + 2 * tid, m_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(mine + 256 * 64 + 2 * tid + 1, l_run, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();                                           // every wave's part is in memory; the K and V buffers are done with
+        uint32_t* flag = reinterpret_cast<uint32_t*>(lds);
+        if (tid == 0) {
+            const uint32_t old = __hip_atomic_fetch_add(s.arrive + tile_lin * SYNC_WORD_STRIDE, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            flag[0] = old;
+        }
+        __syncthreads();
+        finish = __builtin_amdgcn_readfirstlane(flag[0]) == nparts - 1;
+        __syncthreads();
+        if (finish) {
+            // every part is in memory (each counted after its stores had completed): combine in key
+            // order, whoever came last, so that the result does not depend on the arrival order
+            if (tid == 0) __hip_atomic_store(s.arrive + tile_lin * SYNC_WORD_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            float m_all = -INFINITY;
+            for (uint32_t z = 0; z < nparts; ++z)
+                m_all = fmaxf(m_all, __hip_atomic_load(parts + (size_t)z * ATT_PART_FLOATS + 256 * 64 + 2 * tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+            const float m_use = (m_all == -INFINITY) ? 0.0f : m_all;
+            l_run = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) o[i][v] = 0.0f;
+            for (uint32_t z = 0; z < nparts; ++z) {
+                const float* pz = parts + (size_t)z * ATT_PART_FLOATS;
+                const float mz = __hip_atomic_load(pz + 256 * 64 + 2 * tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float lz = __hip_atomic_load(pz + 256 * 64 + 2 * tid + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                const float g = (mz == -INFINITY) ? 0.0f : __builtin_amdgcn_exp2f(mz - m_use);
+                l_run += lz * g;
+                uint64_t t2[32];                                   // agent-scope loads: what the parts wrote through, not a cached line
+#pragma unroll
+                for (int j = 0; j < 32; ++j)
+                    t2[j] = __hip_atomic_load(reinterpret_cast<const uint64_t*>(pz + ((j * 256 + tid) << 1)), __ATOMIC_RELAXED,
+                                              __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) {
+                        typedef float f32x2 __attribute__((ext_vector_type(2)));
+                        f32x2 v2;
+                        __builtin_memcpy(&v2, &t2[i * 8 + q], 8);
+                        o[i][2 * q] += v2[0] * g;
+                        o[i][2 * q + 1] += v2[1] * g;
+                    }
+            }
+        }
+    }
     // ---- normalise and store: lane owns query qi, d = 32*db + 8*(v/4) + 4*h2 + v%4 ----
-    if (wctx.ok && qi < seq) {
+    if (finish && wctx.ok && qi < seq) {
         const float inv = 1.0f / l_run;
         T* out = Tout + (size_t)(seq_row0 + qi) * ldt + head * ATT_D;
 #pragma unroll
@@ -259,10 +354,10 @@ __device__ __forceinline__ void attn_tile(const ChainArgs& args, const StageDesc
     }
 
     dr.grab();   // the increment for the next tile travels while the stores drain
-    if (SYNC) post_tile<true>(args, s, qblk * heads + head, head, qblk);
+    if (SYNC && finish) post_tile<true>(args, s, qblk * heads + head, head, qblk);
     if (tracing && tid == 0) {
         TraceRec r;
-        r.rel = rel_ticket; r.where = hw_where(2u); r.tx = head; r.ty = qblk;
+        r.rel = rel_ticket; r.where = hw_where(2u); r.tx = head; r.ty = tyz;
         r.t_enter = t_enter; r.t_start = t_start; r.t_ready = t_ready; r.t_end = now_ticks();
         args.trace[rel_ticket] = r;
     }

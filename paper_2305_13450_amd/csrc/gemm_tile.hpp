@@ -535,7 +535,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                 for (int q = 0; q < 4; ++q) {
                     f32x4 v4 = {acc[i][j][4 * q], acc[i][j][4 * q + 1], acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]};
                     float* dst = part + (size_t)kz * (TM * TN) + ((((i * FN + j) * 4 + q) * 256 + tid) << 2);
-                    asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v4) : "memory");
+                    // (the wait states a store of more than 8 bytes needs after a vector instruction has
+                    // written its data registers are not inserted for an asm statement: spelled out)
+                    asm volatile("s_nop 1\n\tglobal_store_dwordx4 %0, %1, off sc1" ::"v"(dst), "v"(v4) : "memory");
                 }
         // the partial is in memory before the count moves (every wave's stores, then the barrier)
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");

@@ -107,6 +107,36 @@ def test_ragged_sequence(ragged_sequence, tile, kind):
     pol.destroy()
 
 
+@pytest.fixture(scope="module")
+def long_sequences():
+    # two sequences of 1000 tokens: 16 key blocks for the last query block, ragged on both ends
+    return _case(batch=1, seq=1000, heads=2, K1=128, N2=256, seed=13)
+
+
+@pytest.mark.parametrize("ksplit", [0, 2, 3, 8])
+@pytest.mark.parametrize("kind", KINDS)
+def test_keys_of_long_causal_tiles_split_over_workgroups(long_sequences, ksplit, kind):
+    # A causal tile's key blocks are one dependent chain, so the attention stage splits every tile's
+    # keys over workgroups (0: the library's own choice); the last part to arrive combines the parts in
+    # key order, so every launch mode and timing gives the same bits.
+    t, ref = long_sequences
+    print(f"attn seq=1000 heads=2 ksplit={ksplit} kind={kind}", flush=True)
+    pol = ds.SyncPolicy(kind, ksplit=ksplit)
+    res = [run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 1, 1000, 2, pol, mode) for mode in MODES]
+    _check(res[0], ref, t)
+    for got in res[1:]:
+        for a, b, name in zip(res[0], got, ("QKV", "T", "Y")):
+            assert same(a, b, name)
+    # a delayed producer tile and the reversed order: the parts arrive in another order, same bits
+    slow = ds.SyncPolicy(kind, ksplit=ksplit, delay_tile=2, delay_iters=100000, flags=ds.FLAG_REVERSE_ORDER)
+    got = run_attn_chain(t["X"], t["Wqkv"], t["Wo"], 1, 1000, 2, slow, ds.MODE_FINE)
+    for a, b, name in zip(res[0], got, ("QKV", "T", "Y")):
+        assert same(a, b, name)
+    assert pol.status().timed_out == 0 and slow.status().timed_out == 0
+    pol.destroy()
+    slow.destroy()
+
+
 def test_fp16_chain_meets_the_whole_tensor_tolerance():
     # in the paper's precision (fp16) the chain meets max-abs / RMS <= 2e-2 over the whole tensors
     t, (QKVr, Tr, Yr) = _case(batch=2, seq=256, heads=2, K1=256, N2=320, seed=11, dtype=torch.float16)
