@@ -63,14 +63,14 @@ __global__ __launch_bounds__(256, Cfg::MINB) void chain_kernel(const ChainArgs a
     }
 }
 
-//                        TM   TN  WM WN  workgroups per CU, LDS stages of A (steps of 64, debug 0, spread 0 = default, LDS stages of B if fewer)
-using Cfg256x256 = TileCfg<256, 256, 2, 2, 1, 3, 64, 0, 0, 2>;   // 96 + 64 KB: three stages of A, two of B
+//                        TM   TN  WM WN  workgroups per CU, LDS stages of A (, of B if fewer)
+using Cfg256x256 = TileCfg<256, 256, 2, 2, 1, 3, 2>;   // 96 + 64 KB: three stages of A, two of B
 using Cfg256x128 = TileCfg<256, 128, 2, 2, 1, 3>;   // 144 KB
 using Cfg128x256 = TileCfg<128, 256, 2, 2, 1, 3>;   // 144 KB
 using Cfg128x128 = TileCfg<128, 128, 2, 2, 2, 2>;   // 2 x 64 KB
 using Cfg64x128 = TileCfg<64, 128, 2, 2, 2, 3>;     // 2 x 72 KB
 using Cfg64x64 = TileCfg<64, 64, 2, 2, 2, 4>;       // 2 x 64 KB
-using Cfg256x192 = TileCfg<256, 192, 2, 2, 1, 3, 64, 0, 0, 2>;   // 96 + 48 KB: three stages of A, two of B
+using Cfg256x192 = TileCfg<256, 192, 2, 2, 1, 3, 2>;   // 96 + 48 KB: three stages of A, two of B
 using Cfg128x192 = TileCfg<128, 192, 2, 2, 2, 2>;   // 2 x 80 KB
 using Cfg256x64 = TileCfg<256, 64, 4, 1, 2, 2>;     // 2 x 80 KB
 using Cfg64x64Deep = TileCfg<64, 64, 2, 2, 1, 8>;   // 128 KB: seven K steps in flight

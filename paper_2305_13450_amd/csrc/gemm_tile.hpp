@@ -25,12 +25,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-template <int TM_, int TN_, int WM_, int WN_, int MINB_, int NSTAGE_, int BK_ = 64, int DBG_ = 0, int NGD_ = 0, int NSTB_ = 0>
+template <int TM_, int TN_, int WM_, int WN_, int MINB_, int NSTAGE_, int NSTB_ = 0>
 struct TileCfg {
-    static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_, MINB = MINB_, DBG = DBG_;
-    static constexpr int NGD_OVERRIDE = NGD_;
-    static constexpr int BK = BK_;                    // K elements per pipeline step (64 or 32)
-    static constexpr int ROWB = BK * 2;               // bytes per LDS row
+    static constexpr int TM = TM_, TN = TN_, WM = WM_, WN = WN_, MINB = MINB_;
+    static constexpr int BK = 64;                     // K elements per pipeline step
+    static constexpr int ROWB = BK * 2;               // bytes per LDS row: one 128-byte line of the operand
     static constexpr int KK = BK / 16;                // 16-wide K slices (one MFMA deep) per step
     static constexpr int RPD = 1024 / ROWB;           // operand rows one 1 KB DMA instruction fills
     static constexpr int LPR = ROWB / 16;             // lanes (16-byte chunks) per row
@@ -42,7 +41,6 @@ struct TileCfg {
     static constexpr int A_BYTES = TM * ROWB, B_BYTES = TN * ROWB;
     static constexpr int B_BASE = NSTAGE * A_BYTES;      // the B stages follow the A stages
     static constexpr int LDS_BYTES = NSTAGE * A_BYTES + NSTB * B_BYTES;
-    static_assert(BK == 64 || BK == 32, "steps of 64 or 32 K elements");
     static_assert(WM * WN == 4, "four waves per workgroup");
     static_assert(NSTB >= 2 && NSTAGE >= NSTB && MINB * LDS_BYTES <= 160 * 1024, "stages must fit the 160 KB LDS");
     static_assert(WTM % 32 == 0 && WTN % 32 == 0, "wave tile is made of 32x32 blocks");
@@ -63,17 +61,11 @@ template <> struct Mma<_Float16> {
     }
 };
 
-// Position swizzle of the 16-byte chunks of LDS row r.  128-byte rows: any 8 consecutive rows
+// Position swizzle of the 16-byte chunks of LDS row r (128-byte rows).  Any 8 consecutive rows
 // get 8 distinct positions (32 banks), and any 16 consecutive rows get 16 distinct (position, row
-// parity) pairs (64 banks).  64-byte rows: four consecutive rows fill one 256-byte line of banks,
-// and the rows 4 apart that share a quarter of it get distinct positions, so 8 or 16 consecutive
-// rows read without conflict.  Both patterns repeat every 16 rows, so fragment blocks 32 rows
-// apart share one per-lane offset.
-template <int ROWB>
-__device__ __forceinline__ uint32_t swz(uint32_t r) {
-    if constexpr (ROWB == 128) return (r & 7u) ^ ((r >> 3) & 1u);
-    else return (r >> 2) & 3u;
-}
+// parity) pairs (64 banks).  The pattern repeats every 16 rows, so fragment blocks 32 rows apart
+// share one per-lane offset.
+__device__ __forceinline__ uint32_t swz(uint32_t r) { return (r & 7u) ^ ((r >> 3) & 1u); }
 
 typedef const __attribute__((address_space(1))) void* gptr_t;
 typedef __attribute__((address_space(3))) void* lptr_t;
@@ -178,10 +170,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const uint32_t S = uni(s.ksplit);                      // workgroups per output tile (split along K)
     const uint32_t ty = tyz / S, kz = tyz % S;
     const uint32_t m0 = ty * TM, n0 = tx * tn_out;
-    constexpr uint32_t BK = Cfg::BK, ROWB = Cfg::ROWB, SPK = 64 / Cfg::BK;   // SPK: pipeline steps per 64 K elements
-    const uint32_t KT64 = uni(s.K / 64);
-    const uint32_t kb64 = kz * (KT64 / S), ke64 = kb64 + KT64 / S;   // this workgroup's K range in units of 64 (what dependencies count in)
-    const uint32_t kb = kb64 * SPK, ke = ke64 * SPK;                 // ... and in pipeline steps
+    constexpr uint32_t BK = Cfg::BK, ROWB = Cfg::ROWB;
+    const uint32_t KT = uni(s.K / BK);
+    const uint32_t kb = kz * (KT / S), ke = kb + KT / S;   // this workgroup's K steps
     const char* const Abase = uni_ptr(s.A);
     const char* const Bbase = uni_ptr(s.B);
     const uint32_t bkstep = uni(s.b_kstep_bytes);
@@ -201,7 +192,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
 #pragma unroll
     for (int i = 0; i < NIA; ++i) {
         const uint32_t r = (wave * NIA + i) * Cfg::RPD + lrow;
-        const uint32_t c = lpos ^ swz<ROWB>(r);
+        const uint32_t c = lpos ^ swz(r);
         const uint32_t m = min(m0 + r, sM - 1);
         offA[i] = m * s.lda * 2u + c * 16u;
         if constexpr (AMODE == A_CONV3X3) {
@@ -212,7 +203,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
 #pragma unroll
     for (int i = 0; i < NIB; ++i) {
         const uint32_t q = (wave * NIB + i) * Cfg::RPD + lrow;
-        const uint32_t c = lpos ^ swz<ROWB>(q);
+        const uint32_t c = lpos ^ swz(q);
         uint32_t row;
         if (gate_up) {
             const uint32_t blk = q >> 5, within = q & 31u;
@@ -235,7 +226,6 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     } nx;
     // (A and B may be requested a different number of steps ahead, so each has its own "next")
     auto set_next_A = [&](uint32_t kt) __attribute__((always_inline)) {
-        if constexpr (Cfg::DBG == 1) kt &= 7u;
         nx.kbytes = kt * ROWB;
         if constexpr (AMODE == A_CONV3X3) {
             const uint32_t k0 = kt * BK;
@@ -245,15 +235,11 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         }
     };
     auto set_next_B = [&](uint32_t kt) __attribute__((always_inline)) {
-        if constexpr (Cfg::DBG == 1) kt &= 7u;
-        // B is addressed in blocks of 64 K elements (b_kstep_bytes apart); a step of 32 is half a block
-        nx.kbytes_b = BK == 64 ? kt * bkstep : (kt >> 1) * bkstep + (kt & 1u) * 64u;
+        nx.kbytes_b = kt * bkstep;
     };
     // One 1 KB DMA instruction of the B (weights) or A operand of the next K step into `stage`.
     auto dma_B = [&](uint32_t stage, int i) __attribute__((always_inline)) {
         char* l = lds + Cfg::B_BASE + stage * Cfg::B_BYTES + wave * (NIB * 1024);
-        if constexpr (Cfg::DBG == 3) { dma16(Bbase + lane * 16u + (i & 7) * 1024, l + i * 1024); return; }   // L1-resident source
-        if constexpr (Cfg::DBG == 4) { if (i & 1) return; }
         dma16(Bbase + nx.kbytes_b + offB[i], l + i * 1024);
     };
     auto dma_A = [&](uint32_t stage, int i) __attribute__((always_inline)) {
@@ -266,8 +252,6 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         } else {
             src = Abase + nx.kbytes + offA[i];
         }
-        if constexpr (Cfg::DBG == 3) src = Abase + lane * 16u + (i & 7) * 1024;
-        if constexpr (Cfg::DBG == 4) { if (i & 1) return; }
         dma16(src, l + i * 1024);
     };
     auto issue_B = [&](uint32_t stage) __attribute__((always_inline)) {
@@ -287,8 +271,8 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         const uint32_t h = lane >> 5;
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
-            aoff[kk] = ra * ROWB + ((((uint32_t)kk * 2u + h) ^ swz<ROWB>(ra)) << 4);
-            boff[kk] = rb * ROWB + ((((uint32_t)kk * 2u + h) ^ swz<ROWB>(rb)) << 4);
+            aoff[kk] = ra * ROWB + ((((uint32_t)kk * 2u + h) ^ swz(ra)) << 4);
+            boff[kk] = rb * ROWB + ((((uint32_t)kk * 2u + h) ^ swz(rb)) << 4);
         }
     }
 
@@ -303,9 +287,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     const bool reorder = !(args.flags & DS_FLAG_NO_REORDER);
 
     // Dependency segments start at multiples of seg_steps K steps (0: only at step 0).
-    uint32_t seg_steps = 0, seg_next = kb64;   // the host makes K ranges start on segment boundaries
+    uint32_t seg_steps = 0, seg_next = kb;   // the host makes K ranges start on segment boundaries
     if constexpr (DEP) seg_steps = uni(dep_seg_steps(s));
-    // Called before the A slice that starts 64-element K block k (< KT64) is requested into `stage`: if a dependency
+    // Called before the A slice of K step k (< KT) is requested into `stage`: if a dependency
     // segment starts there, make sure its producer tiles have posted.  The semaphores are looked
     // at 64 segments at a time (lane l tests the segment l places ahead, one load instruction
     // for the wave), so a tile whose producers are long done pays one round trip for its whole
@@ -318,13 +302,13 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
             if (k == seg_next) {
                 seg_next = seg_steps ? seg_next + seg_steps : 0xffffffffu;
                 DepRange dr;
-                if (!dep_segment(s, m0, TM, k, kb64, dr)) return;
+                if (!dep_segment(s, m0, TM, k, kb, dr)) return;
                 bool polled = false;
                 if (k >= ready_until) {
                     const uint32_t ka = k + lane * seg_steps;          // lane's segment start
                     bool ok = true;
                     DepRange la;
-                    if (ka < ke64 && (lane == 0 || seg_steps != 0) && dep_segment(s, m0, TM, ka, kb64, la)) {
+                    if (ka < ke && (lane == 0 || seg_steps != 0) && dep_segment(s, m0, TM, ka, kb, la)) {
                         const uint32_t target = s.sem_target_base + s.sem_value;
                         for (uint32_t y = la.y0; y <= la.y1; ++y) {
                             const uint32_t* sem = s.sems + policy_sem(s.dep_kind, la.x, y, s.prod_grid_y, s.stride) * SYNC_WORD_STRIDE;
@@ -362,7 +346,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // GPT-3 chain at M = 2048: 128x192 601 -> 581 us, 128x128 727 -> 669 us with all of them in
     // the first group; the 256-row tiles, with twice the requests per wave, do best with a
     // quarter of the groups: 256x192 714 -> 684 us)
-    constexpr int NGD = Cfg::NGD_OVERRIDE ? Cfg::NGD_OVERRIDE : (NSA > 2) ? NG : (FM <= 2 ? 1 : NG / 4);
+    constexpr int NGD = (NSA > 2) ? NG : (FM <= 2 ? 1 : NG / 4);
     // Tiles that have a CU to themselves (one wave per SIMD) read all fragments of the next
     // 16-wide K slice together, a whole slice of MFMAs before their first use, with the order
     // pinned: left to itself the compiler issues each read right before the wait for it (while
@@ -377,7 +361,6 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     constexpr int OUTSTANDING = (NSA > NSB ? NIA : 0) + (NSB - 2) * ND;
     static_assert(OUTSTANDING <= 48, "outstanding DMA instructions must fit the vmcnt counter");
     // the steps before the loop, in the order the loop itself would have issued them
-    // (a step of 32 that starts in the middle of a block of 64 belongs to the segment its first half started)
 #pragma unroll
     for (int p = 0; p < NSA - 1; ++p) {
         const int pb = p - (NSA - NSB);    // B's step issued alongside A's step p
@@ -386,7 +369,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         // the weights of the step go out before the look at the semaphores (the load/wait reordering
         // of Section IV-C), so the poll's round trip is not added to their latency
         if (reorder && pb >= 0) issue_B(pb);
-        if (kb + (uint32_t)p < ke && (p % SPK) == 0) dep_before_request((kb + p) / SPK, pb >= 0 ? pb : 0, false);
+        if (kb + (uint32_t)p < ke) dep_before_request(kb + p, pb >= 0 ? pb : 0, false);
         if (p == 0 && tracing) t_ready = now_ticks();
         if (!reorder && pb >= 0) issue_B(pb);
         issue_A(p);
@@ -412,7 +395,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     uint32_t reqA = NSA - 1, reqB = NSB - 1;                 // stages the next requests go into
     // DMA instructions of group g (counted from the barrier that released them)
     auto dma_group = [&](int g) __attribute__((always_inline)) {
-        if (g < NGD && Cfg::DBG != 2 && Cfg::DBG != 5 && Cfg::DBG != 6) {
+        if (g < NGD) {
 #pragma unroll
             for (int d = (g * ND) / NGD; d < ((g + 1) * ND) / NGD; ++d) {
                 if (d < NIB) dma_B(reqB, d);
@@ -448,7 +431,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                     // number m; a wave tile of fewer MFMAs than fragments reads the rest after the last
                     constexpr int NF = FM + FN, NM = FM * FN;
                     const int m0 = i * FN + j, m1 = (m0 == NM - 1 && NM < NF) ? NF : m0 + 1;
-                    if (nkk >= 0 && Cfg::DBG != 5) {
+                    if (nkk >= 0) {
 #pragma unroll
                         for (int m = m0; m < m1; ++m) {
                             if (m == 0) af[n][0] = *(const V8*)(nla + aoff[nkk]);
@@ -479,12 +462,11 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     // and every wave has finished reading the stage of step k-1.  Then point the requests at the
     // steps ahead of k (after waiting for what the A slice depends on, if a dependency segment starts).
     auto hand_over = [&](uint32_t k) __attribute__((always_inline)) {
-        if constexpr (Cfg::DBG == 6) asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(OUTSTANDING) : "memory");
-        else asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(OUTSTANDING) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(OUTSTANDING) : "memory");
         const uint32_t kreq = k + (NSA - 1);
         set_next_A(min(kreq, ke - 1));
         set_next_B(min(k + (NSB - 1), ke - 1));
-        if (kreq < ke && (kreq % SPK) == 0) dep_before_request(kreq / SPK, reqB, true);
+        if (kreq < ke) dep_before_request(kreq, reqB, true);
     };
     auto advance = [&](uint32_t& st, uint32_t n) __attribute__((always_inline)) { st = (st + 1 == n) ? 0 : st + 1; };
     static_assert(KK % 2 == 0, "fragment buffers alternate with the slices");
