@@ -69,6 +69,9 @@ def parse():
     ap.add_argument("--sweep-set", default="paper", choices=["paper", "resnet", "vgg_layers", "generation"],
                     help="rows of --sweep: the five configurations of the headline table, ResNet-38's conv pairs, or "
                          "VGG-19's layer groups of four convolutions")
+    ap.add_argument("--policy-table", default=None, metavar="FILE",
+                    help="Row / Tile / Strided latency per chain size and the kind the library's policy search keeps "
+                         "(Section IV-A's search, Section V-C's crossover), markdown table")
     ap.add_argument("--ablation", default=None, metavar="FILE",
                     help="time the chosen workload with the optimisations of Section IV-C switched off one at a time")
     return ap.parse_args()
@@ -375,6 +378,58 @@ def sweep(args, torch, ds, inputs):
     print(json.dumps({"sweep": args.sweep, "rows": len(lines) - 2}))
 
 
+def policy_table(args, torch, ds, inputs):
+    """For every GeMM-chain size of the paper: run the library's policy search (each kind autotuned, fastest
+    remembered), then time each kind and an AUTOSYNC policy in interleaved blocks, one dispatch per chain."""
+    sp, sc = torch.cuda.Stream(), torch.cuda.Stream()
+    kinds = [("row", ds.ROWSYNC), ("tile", ds.TILESYNC), ("strided", ds.STRIDEDSYNC)]
+    cases = [("gpt3_mlp", dict(M=m)) for m in inputs.CFG2["Ms"]]
+    cases += [("llama_mlp", dict(M=m)) for m in inputs.CFG3["Ms"]]
+    cases += [("gpt3_attn", dict(M=m)) for m in inputs.CFG4["Ms"]]
+    lines = ["| workload | Row us (tile) | Tile us (tile) | Strided us (tile) | search keeps | AUTOSYNC us | waits per chain Row / Tile |",
+             "|---|---|---|---|---|---|---|"]
+    for kind, kw in cases:
+        wl = Workload(torch, ds, inputs, kind, **kw)
+        auto = ds.SyncPolicy(ds.AUTOSYNC)
+        kept, kept_tile, _ = ds.gemm_chain_autotune_policy(wl.X, wl.W1t, wl.H, wl.W2t, wl.Y, auto, mid=wl.mid, stream=sp, **wl.extra)
+        pols, calls, tiles = {}, {}, {}
+        for pn, k in kinds:
+            if pn == "strided" and not wl.attn:
+                continue
+            pols[pn] = ds.SyncPolicy(k)
+            tiles[pn] = wl.plan(pols[pn]).tile_prod          # the tile the search remembered for this kind
+            calls[pn] = wl.caller(pols[pn], ds.MODE_FUSED, 0, sp, sc)
+        pols["auto"] = auto
+        calls["auto"] = wl.caller(auto, ds.MODE_FUSED, 0, sp, sc)
+        for c in calls.values():
+            for _ in range(args.warmup):
+                c()
+        blocks = {k: [] for k in calls}
+        for _ in range(args.rounds):
+            for k, c in calls.items():
+                blocks[k].append(time_block(torch, c, sp, args.steps))
+        med = {k: sorted(b)[len(b) // 2] for k, b in blocks.items()}
+        waits = []
+        for pn, k in kinds[:2]:                              # counted in one extra launch of a counting policy
+            cp = ds.SyncPolicy(k, flags=ds.FLAG_COUNT)
+            wl.caller(cp, ds.MODE_FUSED, 0, sp, sc)()
+            torch.cuda.synchronize()
+            waits.append(str(cp.status().waits))
+            cp.destroy()
+        cell = lambda pn: f"{med[pn]:.1f} ({tile_label(ds, tiles[pn])})" if pn in med else "-"
+        names = {ds.ROWSYNC: "Row", ds.TILESYNC: "Tile", ds.STRIDEDSYNC: "Strided"}
+        lines.append(f"| {wl.name} | {cell('row')} | {cell('tile')} | {cell('strided')} | {names[kept]} ({tile_label(ds, kept_tile)}) | "
+                     f"{med['auto']:.1f} | {' / '.join(waits)} |")
+        print(lines[-1], file=sys.stderr, flush=True)
+        for pol in pols.values():
+            pol.destroy()
+        del wl
+        torch.cuda.empty_cache()
+    with open(args.policy_table, "w") as f:
+        f.write("\n".join(lines) + "\n")
+    print(json.dumps({"policy_table": args.policy_table, "rows": len(lines) - 2}))
+
+
 def ablation(args, torch, ds, wl):
     """Latency of the workload under each launch mode and with the paper's optimisations (Section IV-C:
     load/wait reordering, custom tile order) switched off, interleaved blocks, markdown table."""
@@ -525,6 +580,8 @@ def main():
         return sweep(args, torch, ds, inputs)
     if args.sync_overhead:
         return sync_overhead(args, torch, ds, n_cu)
+    if args.policy_table:
+        return policy_table(args, torch, ds, inputs)
 
     wl = Workload(torch, ds, inputs, args.workload, M=args.m, hw=args.hw, channels=args.channels, batch=args.batch,
                   w_layout=args.w_layout, cached=args.cached)

@@ -233,7 +233,14 @@ typedef struct {
     void* Y;         int64_t ldy;   /* [M x N2]                                              */
     void* T;         int64_t ldt;   /* CAUSAL_ATTN only: [M x heads*head_dim]                */
     int32_t batch, seq, heads, head_dim; /* CAUSAL_ATTN only; batch > 1 needs seq % 128 == 0 or seq < 128 */
-    int32_t tile_prod, tile_cons;   /* depsync_tile; 0 = chosen by the library               */
+    int32_t tile_prod, tile_cons;   /* depsync_tile of the first and of the last GeMM; 0 = chosen by
+                                     * the library.  They may differ (the consumer waits by the rows
+                                     * and columns of the producer's tiles, Section III-C): each stage
+                                     * is then a launch of its own kernel, so MODE_FUSED returns
+                                     * DEPSYNC_ENOTIMPL, and MODE_FINE holds the consumer's launch
+                                     * back with the wait kernel of Section III-B until the
+                                     * producer's workgroups are resident.  CAUSAL_ATTN chains take
+                                     * one shape for all three stages (else DEPSYNC_ENOTIMPL).     */
     int32_t w_layout;               /* depsync_w_layout of W1t and W2t                       */
     /* CAUSAL_ATTN, token generation (Fig. 2b, cached keys and values): `cached` earlier tokens
      * per sequence whose keys and values are read from k_cache / v_cache, [batch][cached] rows of
@@ -260,7 +267,7 @@ typedef struct {
     void* mid;        /* [B,H,W,K1]  */
     const void* w2;   /* [K2,3,3,K1] */
     void* out;        /* [B,H,W,K2]  */
-    int32_t tile_prod, tile_cons;
+    int32_t tile_prod, tile_cons;   /* as in depsync_gemm_chain_desc: may differ (not in MODE_FUSED) */
 } depsync_conv_chain_desc;
 
 /*
@@ -280,7 +287,9 @@ typedef struct {
     const void* in;
     const void* w[4];
     void* out[4];
-    int32_t tile_prod, tile_cons;   /* one macro-tile for every stage: equal, or 0 = library's choice */
+    int32_t tile_prod, tile_cons;   /* 0 = library's choice; for n = 2 they may differ as in
+                                     * depsync_conv_chain_desc, for n > 2 one shape serves every
+                                     * stage (else DEPSYNC_ENOTIMPL)                              */
 } depsync_conv_chain_n_desc;
 
 /* ---- policy objects (CuStage + policy of Fig. 4; init of Section III-D) ------------- */

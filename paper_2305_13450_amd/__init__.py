@@ -188,6 +188,14 @@ def _stream_handle(stream) -> Optional[int]:
     return int(stream) or None
 
 
+def _tile_pair(tile):
+    """A macro-tile id for every stage, or a (producer, consumer) pair of ids."""
+    if isinstance(tile, (tuple, list)):
+        prod, cons = tile
+        return int(prod), int(cons)
+    return int(tile), int(tile)
+
+
 def _dtype_code(t) -> int:
     import torch
     if t.dtype == torch.bfloat16:
@@ -308,7 +316,7 @@ def _gemm_desc(X, W1t, H, W2t, Y, mid, tile, T=None, batch=0, seq=0, heads=0, he
             raise ValueError("k_cache and v_cache must have the same shape and strides")
         d.k_cache, d.v_cache = k_cache.data_ptr(), v_cache.data_ptr()
         d.ld_cache, d.cached = k_cache.stride(1), k_cache.shape[1]
-    d.tile_prod = d.tile_cons = tile
+    d.tile_prod, d.tile_cons = _tile_pair(tile)
     rows1 = 2 * d.N1 if mid == MID_SWIGLU else d.N1
     k2 = heads * head_dim if mid == MID_CAUSAL_ATTN else d.N1
     if (w1n, w1k) != (rows1, d.K1) or (w2n, w2k) != (d.N2, k2) or H.shape[0] != d.M or Y.shape[0] != d.M:
@@ -434,7 +442,7 @@ def _conv_desc(x, w1, mid, w2, out, tile) -> ConvChainDesc:
         raise ValueError("operand shapes do not form a conv chain")
     d.dtype = _dtype_code(x)
     d.inp, d.w1, d.mid, d.w2, d.out = x.data_ptr(), w1.data_ptr(), mid.data_ptr(), w2.data_ptr(), out.data_ptr()
-    d.tile_prod = d.tile_cons = tile
+    d.tile_prod, d.tile_cons = _tile_pair(tile)
     return d
 
 
@@ -472,7 +480,7 @@ def _conv_n_desc(x, ws, outs, tile) -> ConvChainNDesc:
             raise ValueError(f"conv {i}: weights [K,3,3,{cin}] and output [B,H,W,K] of the input's type expected")
         d.K[i], d.w[i], d.out[i] = w.shape[0], w.data_ptr(), o.data_ptr()
         cin = w.shape[0]
-    d.tile_prod = d.tile_cons = tile
+    d.tile_prod, d.tile_cons = _tile_pair(tile)
     return d
 
 

@@ -118,7 +118,8 @@ struct Plan {
     uint32_t n_arrive;               // arrival counters the chain needs
     uint32_t part_floats[4];         // floats one part of a split tile of the stage leaves in the scratch buffer (0: rows x columns of its tile)
     uint32_t n_sems;
-    int slots;
+    int slots;                       // workgroups of the first stage's tile shape that fit on the chip
+    int stage_slots[4];              // ... of each stage's own shape (they differ when producer and consumer tiles do)
     double flops, bytes;
     uint32_t amode;
     int dtype;
@@ -151,6 +152,7 @@ double tile_cost_factor(int tile, bool conv) {
             case DEPSYNC_TILE_64x128: return 1.3;
             case DEPSYNC_TILE_128x192_DEEP: return 1.3;
             case DEPSYNC_TILE_64x64_DEEP: return 5.0;
+            case DEPSYNC_TILE_256x192: return 1.18;
             default: break;
         }
     }
@@ -161,7 +163,7 @@ double tile_cost_factor(int tile, bool conv) {
         case DEPSYNC_TILE_128x128: return 1.20;
         case DEPSYNC_TILE_64x128: return 1.6;
         case DEPSYNC_TILE_64x64: return 2.3;
-        case DEPSYNC_TILE_256x192: return 1.18;
+        case DEPSYNC_TILE_256x192: return 0.93;   // one workgroup per CU, three stages of A: ahead once its tiles fill the chip
         case DEPSYNC_TILE_128x192: return 1.00;
         case DEPSYNC_TILE_256x64: return 1.3;
         case DEPSYNC_TILE_64x64_DEEP: return 4.0;   // one workgroup per CU: only ever worth it when tiles are few
@@ -356,7 +358,10 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     if (d->tile_prod < 0 || d->tile_prod >= DEPSYNC_TILE__COUNT || d->tile_cons < 0 ||
         d->tile_cons >= DEPSYNC_TILE__COUNT)
         return DEPSYNC_EINVAL;
-    if (d->tile_prod && d->tile_cons && d->tile_prod != d->tile_cons) return DEPSYNC_ENOTIMPL;
+    // Producer and consumer may use different macro-tile shapes (each stage is then a launch of its
+    // own kernel: not in one dispatch); the attention chain's three stages share one.
+    const bool mixed = d->tile_prod && d->tile_cons && d->tile_prod != d->tile_cons;
+    if (mixed && attn) return DEPSYNC_ENOTIMPL;
 
     const int cus = device_cus(n_cu);
     if (cus <= 0) return DEPSYNC_EHIP;
@@ -369,8 +374,9 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
         if (v) { tuned_off = (v & 0x100) != 0; order_pref = (v & 0x200) ? 1 : 0; }
     }
     if (!tile) tile = choose_tile(d->M, d->N1, d->K1, d->N2, K2, gate_up, cus, 0);
-    const TileShape* ts = tile_shape(tile);
-    if (!ts) return DEPSYNC_EINVAL;
+    const TileShape* ts = tile_shape(tile);                               // the producer's shape
+    const TileShape* tsc = mixed ? tile_shape(d->tile_cons) : ts;         // the consumer's
+    if (!ts || !tsc) return DEPSYNC_EINVAL;
     if (gate_up && ts->wave_cols % 64) return DEPSYNC_EINVAL;   // a wave needs whole gate/up pairs of 32-column blocks
     // a K step of the next stage (64 columns of the intermediate) must not straddle two producer
     // tiles: the per-tile waits are issued per producer column tile as the K loop reaches it
@@ -382,12 +388,15 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     p.amode = A_DENSE;
     p.dtype = d->dtype;
     p.order_pref = order_pref;
-    for (int s = 0; s < p.n_stages; ++s) p.tile[s] = tile;
+    for (int s = 0; s < p.n_stages; ++s) { p.tile[s] = tile; p.stage_slots[s] = cus * ts->occupancy; }
+    if (mixed) { p.tile[last] = d->tile_cons; p.stage_slots[last] = cus * tsc->occupancy; }
     const uint32_t tn1 = gate_up ? ts->cols / 2 : ts->cols;
-    p.grid_y[0] = p.grid_y[last] = cdiv(d->M, ts->rows);
+    p.grid_y[0] = cdiv(d->M, ts->rows);
+    p.grid_y[last] = cdiv(d->M, tsc->rows);
     p.grid_x[0] = cdiv(d->N1, tn1);
-    p.grid_x[last] = cdiv(d->N2, ts->cols);
+    p.grid_x[last] = cdiv(d->N2, tsc->cols);
     p.out_tm[0] = ts->rows; p.out_tn[0] = tn1;
+    p.out_tm[last] = tsc->rows; p.out_tn[last] = tsc->cols;
     if (attn) {   // middle stage: one tile per (head, block of 128 query rows)
         p.grid_x[1] = d->heads;
         p.grid_y[1] = (uint32_t)d->batch * cdiv(d->seq, 128);
@@ -459,7 +468,7 @@ int plan_gemm(const depsync_gemm_chain_desc* d, const sync_policy* pol, int n_cu
     {
         const uint32_t dk = p.dep_kind[last];
         const uint32_t seg = (dk == DEP_ROW) ? 1u : p.out_tn[last - 1] / 64;
-        p.ksplit[last] = choose_split(pol, tuned_off, p.n_tiles[last], p.slots, K2 / 64, seg);
+        p.ksplit[last] = choose_split(pol, tuned_off, p.n_tiles[last], p.stage_slots[last], K2 / 64, seg);
     }
     if (int rc = finish_split(p); rc != DEPSYNC_OK) return rc;
     const double M = d->M, w1c = gate_up ? 2.0 * d->N1 : d->N1;
@@ -511,7 +520,10 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
     if (d->tile_prod < 0 || d->tile_prod >= DEPSYNC_TILE__COUNT || d->tile_cons < 0 ||
         d->tile_cons >= DEPSYNC_TILE__COUNT)
         return DEPSYNC_EINVAL;
-    if (d->tile_prod && d->tile_cons && d->tile_prod != d->tile_cons) return DEPSYNC_ENOTIMPL;
+    // differing producer and consumer shapes: chains of two convolutions only (each stage then is a
+    // launch of its own kernel)
+    const bool mixed = d->tile_prod && d->tile_cons && d->tile_prod != d->tile_cons;
+    if (mixed && n != 2) return DEPSYNC_ENOTIMPL;
     const int cus = device_cus(n_cu);
     if (cus <= 0) return DEPSYNC_EHIP;
     const uint32_t M = (uint32_t)Mpix;
@@ -527,8 +539,7 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
         // halo: a consumer row tile reads W+1 rows beyond each end (modelled on the first two stages)
         tile = choose_tile(M, d->K[0], 9 * d->C, d->K[1], 9 * d->K[0], false, cus, 1);
     }
-    const TileShape* ts = tile_shape(tile);
-    if (!ts) return DEPSYNC_EINVAL;
+    if (!tile_shape(tile) || (mixed && !tile_shape(d->tile_cons))) return DEPSYNC_EINVAL;
 
     std::memset(&p, 0, sizeof(p));
     p.n_stages = n;
@@ -536,20 +547,22 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
     p.dtype = d->dtype;
     p.order_pref = order_pref;
     const int kind = effective_kind(d, pol, DEPSYNC_STRIDEDSYNC);
-    p.slots = cus * ts->occupancy;
     for (int s = 0; s < n; ++s) {
-        p.tile[s] = tile;
+        p.tile[s] = (mixed && s == n - 1) ? d->tile_cons : tile;
+        const TileShape* ts = tile_shape(p.tile[s]);
+        p.stage_slots[s] = cus * ts->occupancy;
         p.grid_y[s] = cdiv(M, ts->rows);
         p.grid_x[s] = cdiv(d->K[s], ts->cols);
         p.out_tm[s] = ts->rows; p.out_tn[s] = ts->cols;
         p.n_tiles[s] = p.grid_x[s] * p.grid_y[s];
         p.ksplit[s] = 1;
     }
+    p.slots = p.stage_slots[0];
     for (int s = 1; s < n; ++s) {
         p.dep_kind[s] = policy_dep_kind_conv(kind);
         p.sem_off[s] = p.n_sems;
         if (p.dep_kind[s] == DEP_CONV_TILE) {
-            if (ts->cols % 64) return DEPSYNC_EINVAL;
+            if (p.out_tn[s - 1] % 64) return DEPSYNC_EINVAL;
             p.sem_count[s] = p.n_tiles[s - 1];
             p.sem_value[s] = 1;
         } else {
@@ -558,13 +571,13 @@ int plan_conv_n(const depsync_conv_chain_n_desc* d, const sync_policy* pol, int 
         }
         p.n_sems += p.sem_count[s];
     }
-    p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.slots, 9u * d->C / 64, 1);
+    p.ksplit[0] = choose_split(pol, tuned_off, p.n_tiles[0], p.stage_slots[0], 9u * d->C / 64, 1);
     for (int s = 1; s < n; ++s) {
         uint32_t seg = 1;                                   // CONV_ROW: the whole halo is waited for by every part
         // per filter row or per (filter row, channel tile): the wait at a filter row's first tap
         // also covers its other two taps, so parts must be whole filter rows
         if (p.dep_kind[s] != DEP_CONV_ROW) seg = 3u * cin[s] / 64;
-        p.ksplit[s] = choose_split(pol, tuned_off, p.n_tiles[s], p.slots, 9u * cin[s] / 64, seg);
+        p.ksplit[s] = choose_split(pol, tuned_off, p.n_tiles[s], p.stage_slots[s], 9u * cin[s] / 64, seg);
     }
     if (int rc = finish_split(p); rc != DEPSYNC_OK) return rc;
     const double Md = (double)M;
@@ -610,6 +623,7 @@ int plan_copy(const depsync_copy_chain_desc* d, const sync_policy* pol, int n_cu
     p.sem_value[1] = row ? tiles : 1u;
     p.n_sems = p.sem_count[1];
     p.slots = cus * 8;                     // 256 threads, no LDS to speak of: eight workgroups per CU
+    p.stage_slots[0] = p.stage_slots[1] = p.slots;
     p.flops = 0.0;
     p.bytes = 4.0 * (double)d->bytes;      // each stage reads the buffer once and writes it once
     p.amode = A_COPY;
@@ -635,7 +649,7 @@ void fill_plan_info(const Plan& p, depsync_plan_info* o) {
     o->slots = p.slots;
     uint32_t total = 0;
     int ws = 0;
-    for (int s = 0; s < p.n_stages; ++s) { ws += cdiv(p.n_tiles[s], p.slots); total += p.n_tiles[s]; }
+    for (int s = 0; s < p.n_stages; ++s) { ws += cdiv(p.n_tiles[s], p.stage_slots[s]); total += p.n_tiles[s]; }
     o->waves_streamsync = ws;
     o->waves_fine = cdiv(total, p.slots);
     o->flops = p.flops;
@@ -805,7 +819,9 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     // choice (DEPSYNC_FLAG_HW_ORDER), backed by the bounded wait.
     const bool want_queues = (pol->params.flags & (DEPSYNC_FLAG_QUEUE_ORDER | DEPSYNC_FLAG_REVERSE_ORDER)) != 0;
     const bool caller_hw = (pol->params.flags & DEPSYNC_FLAG_HW_ORDER) != 0;
-    const bool all_resident = total <= (uint32_t)p.slots;
+    bool mixed = false;   // stages of differing macro-tile shapes: one launch (one kernel) per stage
+    for (int s = 1; s < p.n_stages; ++s) mixed = mixed || p.tile[s] != p.tile[0];
+    const bool all_resident = !mixed && total <= (uint32_t)p.slots;
     if (pol->force_order == 1 && !all_resident && !caller_hw) return DEPSYNC_EINVAL;   // not a candidate for the autotuner
     bool hw;
     if (pol->force_order >= 0) hw = pol->force_order == 1;
@@ -820,12 +836,11 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
     // each keeps drawing tiles.  With tiles named by the block index (PLAIN, HW_ORDER) a launch
     // has one workgroup per tile.
     const bool queues = sync && !(a.flags & DEPSYNC_FLAG_HW_ORDER);
-    auto blocks = [&](uint32_t tiles) { return queues ? std::min<uint32_t>(tiles, (uint32_t)p.slots) : tiles; };
+    auto blocks = [&](uint32_t tiles, int s = 0) { return queues ? std::min<uint32_t>(tiles, (uint32_t)p.stage_slots[s]) : tiles; };
     const int last = p.n_stages - 1;
     if (mode == DEPSYNC_MODE_FUSED) {
         // all stages in one dispatch; needs one macro-tile shape for the whole chain
-        for (int s = 1; s < p.n_stages; ++s)
-            if (p.tile[s] != p.tile[0]) return DEPSYNC_ENOTIMPL;
+        if (mixed) return DEPSYNC_ENOTIMPL;
         a.block_offset = 0;
         a.stage_lo = 0; a.stage_hi = (uint32_t)last;
         HIP_TRY(launch_chain_kernel(p.tile[0], p.dtype, p.amode, true, blocks(total), sp, a));
@@ -843,6 +858,28 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
         if (!pol->ev_fork) return DEPSYNC_EINVAL;          // a policy without streams of its own
         hipStream_t side[3] = {sc_ ? static_cast<hipStream_t>(sc_) : pol->own_stream, pol->third_stream, pol->fourth_stream};
         if (sc_) pol->last_side = static_cast<hipStream_t>(sc_);
+        if (mixed) {
+            // Two stages of differing tile shapes are two kernels, and neither launch can run the
+            // other's tiles.  The producer goes on the side stream, the consumer on the caller's,
+            // behind Section III-B's wait kernel: the consumer's workgroups are not started before
+            // the producer's persistent workgroups hold their slots, so consumers that then fill
+            // the rest of the chip wait for tiles that resident workgroups are working through.
+            if (!queues || p.n_stages != 2) return DEPSYNC_EINVAL;
+            HIP_TRY(hipEventRecord(pol->ev_fork, sp));
+            HIP_TRY(hipStreamWaitEvent(side[0], pol->ev_fork, 0));
+            const uint32_t nb0 = blocks(p.n_tiles[0], 0);
+            a.block_offset = 0u; a.stage_lo = a.stage_hi = 0u; a.draw_cas = 1u;
+            HIP_TRY(launch_chain_kernel(p.tile[0], p.dtype, p.amode, true, nb0, side[0], a));
+            a.draw_cas = 0u;
+            HIP_TRY(launch_wait_draws(a, 0u, nb0, sp));
+            a.block_offset = p.n_tiles[0]; a.stage_lo = a.stage_hi = 1u;
+            HIP_TRY(launch_chain_kernel(p.tile[1], p.dtype, p.amode, true, blocks(p.n_tiles[1], 1), sp, a));
+            pol->side_used = true;
+            pol->epoch += 1;
+            pol->queue_epoch += 1;
+            pol->launches += 1;
+            return DEPSYNC_OK;
+        }
         // When the last stage's launch has a workgroup of its own for every tile of the chain, all
         // of them resident at once, a side launch could only ever find its tiles taken (it starts
         // when the event has crossed streams, later than the caller's launch): it is left out, as
@@ -875,7 +912,7 @@ int launch_chain(sync_policy* pol, const Plan& p, ChainArgs& a, depsync_mode mod
         for (int s = 0; s < p.n_stages; ++s) {   // one launch per stage on the caller's stream
             a.block_offset = off;
             a.stage_lo = a.stage_hi = (uint32_t)s;
-            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, blocks(p.n_tiles[s]), sp, a));
+            HIP_TRY(launch_chain_kernel(p.tile[s], p.dtype, p.amode, sync, blocks(p.n_tiles[s], s), sp, a));
             off += p.n_tiles[s];
         }
     }

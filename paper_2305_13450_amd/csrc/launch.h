@@ -22,6 +22,12 @@ hipError_t launch_chain_kernel(int tile, int dtype, uint32_t amode, bool sync, u
 
 hipError_t launch_fill_u32(uint32_t* p, uint32_t value, uint32_t n, hipStream_t stream);
 
+// The wait kernel of Section III-B: one wave that ends when `want` tiles of stage `stage` have been
+// drawn from the chain's dispatch queues (i.e. the producer launch, on another stream, holds its
+// workgroup slots), or when the chain's spin limit expires (counted as a time-out in the status
+// block).  Launches queued behind it on `stream` start after that.
+hipError_t launch_wait_draws(const ChainArgs& a, uint32_t stage, uint32_t want, hipStream_t stream);
+
 // Register-only MFMA loop: n_blocks workgroups of 256 threads, 8 * iters MFMAs (32x32x16 bf16)
 // per wave; src holds 1 MiB of operand bits, out n_blocks * 256 floats (practically never written).
 hipError_t launch_mfma_calibration(const void* src, float* out, int n_blocks, int iters, hipStream_t stream);

@@ -2,6 +2,7 @@
 // the table of macro-tile shapes.
 #include <hip/hip_runtime.h>
 #include "launch.h"
+#include "sync_device.hpp"
 
 namespace depsync {
 
@@ -74,6 +75,48 @@ hipError_t launch_chain_kernel(int tile, int dtype, uint32_t amode, bool sync, u
                           : launch_f16_gemm_attn(tile, sync, n_blocks, stream, a);
     return dtype == 0 ? launch_bf16_gemm(tile, sync, n_blocks, stream, a)
                       : launch_f16_gemm(tile, sync, n_blocks, stream, a);
+}
+
+// Section III-B: a consumer kernel whose workgroups took every slot before the producer's had
+// started would wait for ever; the paper holds the consumer's launch back with a one-thread
+// kernel until the producer's thread blocks are on the GPU.  Here the producer's persistent
+// workgroups each draw a tile as their first action, so "stage has handed out `want` tiles"
+// says that they are resident (or that fewer of them have already done more: either way a
+// workgroup that keeps drawing the stage's tiles holds a slot).  Lanes 0..7 read one queue
+// counter each; the wave sums what has been drawn in this chain's epoch.
+__global__ __launch_bounds__(64) void wait_draws_kernel(const ChainArgs a, uint32_t stage, uint32_t want) {
+    const uint32_t lane = threadIdx.x;
+    const StageDesc& st = a.st[stage];
+    const uint32_t len = lane < 8 ? queue_len(st, lane) : 0u;
+    uint32_t spins = 0;
+    for (;;) {
+        uint32_t drawn = 0;
+        if (lane < 8 && len != 0) {
+            const uint32_t c = __hip_atomic_load(a.ticket + (8u * stage + lane) * SYNC_WORD_STRIDE, __ATOMIC_RELAXED,
+                                                 __HIP_MEMORY_SCOPE_AGENT);
+            const int32_t i = (int32_t)(c - a.queue_epoch * len);   // (may overshoot for a moment: draws past the end are undone)
+            drawn = i < 0 ? 0u : ((uint32_t)i > len ? len : (uint32_t)i);
+        }
+#pragma unroll
+        for (int off = 4; off > 0; off >>= 1) drawn += __shfl_down(drawn, off, 8);
+        drawn = __builtin_amdgcn_readfirstlane(drawn);
+        if (drawn >= want) return;
+        if (a.spin_limit != 0 && ++spins >= a.spin_limit) {
+            if (lane == 0) {
+                const int prev = __hip_atomic_fetch_add(&a.status->timed_out, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (prev == 0)
+                    __hip_atomic_store(&a.status->first_timeout, (int32_t)a.first_ticket[stage], __ATOMIC_RELAXED,
+                                       __HIP_MEMORY_SCOPE_AGENT);
+            }
+            return;
+        }
+        __builtin_amdgcn_s_sleep(16);
+    }
+}
+
+hipError_t launch_wait_draws(const ChainArgs& a, uint32_t stage, uint32_t want, hipStream_t stream) {
+    hipLaunchKernelGGL(wait_draws_kernel, dim3(1), dim3(64), 0, stream, a, stage, want);
+    return hipGetLastError();
 }
 
 hipError_t launch_fill_u32(uint32_t* p, uint32_t value, uint32_t n, hipStream_t stream) {

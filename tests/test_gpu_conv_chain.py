@@ -266,3 +266,23 @@ def test_conv_chain_n_delayed_middle_stage_and_bad_arguments():
     d.K[1] = 72                                                          # an intermediate that is not a multiple of 64
     assert ds._lib().dep_conv_chain_n(d, pol.handle, ds.MODE_FINE, None, None) == ds.EINVAL
     pol.destroy()
+
+
+@pytest.mark.parametrize("kind", KINDS)
+def test_conv_pair_with_different_producer_and_consumer_tiles(kind):
+    # the consumer's halo waits are computed from the producer's row tiles (Section III-C, Fig. 5c):
+    # 128-row producer tiles under 64-row consumer tiles and the other way round
+    t = inputs.conv(3, 13, 11, 64, 128, 64, seed=23)
+    mid_ref, out_ref = _oracle(t)
+    for pair in ((ds.TILE_128x128, ds.TILE_64x64), (ds.TILE_64x128, ds.TILE_256x64)):
+        print(f"conv mixed tiles pair={pair} kind={kind}", flush=True)
+        pol = ds.SyncPolicy(kind)
+        res = [run_conv_chain(t["x"], t["w1"], t["w2"], pol, mode, tile=pair)
+               for mode in (ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN, ds.MODE_FINE)]
+        for mid, out in res:
+            assert mid_err(mid, mid_ref) <= TOL_MID
+            assert rel_err(out, out_ref) <= TOL_BF16
+        for mid, out in res[1:]:
+            assert torch.equal(res[0][0], mid) and torch.equal(res[0][1], out)
+        assert pol.status().timed_out == 0
+        pol.destroy()

@@ -455,3 +455,57 @@ def test_mfma_calibration_reports_a_plausible_rate():
     assert 500.0 < rnd <= zero * 1.05 and zero < 2600.0, (zero, rnd)
     with pytest.raises(ds.DepsyncError):
         ds.mfma_calibration(False, 0)
+
+
+MIXED_MODES = [ds.MODE_FINE, ds.MODE_STREAMSYNC, ds.MODE_PLAIN]
+
+
+@pytest.mark.parametrize("kind", [ds.ROWSYNC, ds.TILESYNC])
+@pytest.mark.parametrize("pair", [(ds.TILE_128x128, ds.TILE_64x64), (ds.TILE_64x128, ds.TILE_256x128),
+                                  (ds.TILE_256x192, ds.TILE_128x256), (ds.TILE_64x64, ds.TILE_128x192)])
+def test_producer_and_consumer_tiles_of_different_shapes(kind, pair):
+    # Section III-C: a consumer tile waits by the rows and columns of the PRODUCER's tiles, whatever
+    # its own shape.  Ragged sizes; two streams (behind the wait kernel of Section III-B), stream
+    # sync and plain launches agree bit for bit; one dispatch cannot hold two kernels.
+    M, K1, N1, N2 = 300, 192, 576, 328
+    print(f"mixed tiles pair={pair} kind={kind}", flush=True)
+    t = inputs.mlp(M, K1, N1, N2, seed=17)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pol = ds.SyncPolicy(kind)
+    res = [run_gemm_chain(t["X"], t["W1"], t["W2"], pol, mode, tile=pair) for mode in MIXED_MODES + [ds.MODE_FINE]]
+    for H, Y in res:
+        assert mid_err(H, Href) <= TOL_MID
+        assert rel_err(Y, Yref) <= TOL_BF16
+    for H, Y in res[1:]:
+        assert torch.equal(res[0][0], H) and torch.equal(res[0][1], Y)
+    with pytest.raises(ds.DepsyncError) as e:
+        run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_FUSED, tile=pair)
+    assert e.value.status == ds.ENOTIMPL
+    assert pol.status().timed_out == 0
+    pol.destroy()
+
+
+def test_different_tile_shapes_with_more_producer_tiles_than_slots():
+    # 1024 producer tiles of 64x64 on 512 slots, 128 consumer tiles of 128x128: on two streams the
+    # consumer's workgroups start behind the wait kernel, next to the producer's persistent ones,
+    # and wait for tiles those are still working through; launched back to back several times on
+    # the same policy (the producer's launch of one chain may still be ending when the next begins)
+    M, K1, N1, N2 = 4096, 256, 1024, 512
+    t = inputs.mlp(M, K1, N1, N2, seed=19)
+    Href, Yref = oracle.gemm_chain(inputs.to_f64(t["X"]), inputs.to_f64(t["W1"]), inputs.to_f64(t["W2"]), oracle.ACT_GELU)
+    pair = (ds.TILE_64x64, ds.TILE_128x128)
+    pol = ds.SyncPolicy(ds.ROWSYNC)
+    ref = run_gemm_chain(t["X"], t["W1"], t["W2"], pol, ds.MODE_STREAMSYNC, tile=pair)
+    assert mid_err(ref[0], Href) <= TOL_MID and rel_err(ref[1], Yref) <= TOL_BF16
+    Xd, W1t, W2t = t["X"].cuda(), t["W1"].t().contiguous().cuda(), t["W2"].t().contiguous().cuda()
+    H = torch.empty((M, N1), dtype=Xd.dtype, device="cuda")
+    Y = torch.empty((M, N2), dtype=Xd.dtype, device="cuda")
+    for rep in range(5):
+        print(f"mixed tiles, two streams, launch {rep}", flush=True)
+        H.fill_(float("nan")); Y.fill_(float("nan"))
+        ds.dep_gemm_chain(Xd, W1t, H, W2t, Y, pol, mode=ds.MODE_FINE, tile=pair)
+        ds.dep_gemm_chain(Xd, W1t, H, W2t, Y, pol, mode=ds.MODE_FINE, tile=pair)
+        torch.cuda.synchronize()
+        assert torch.equal(H, ref[0]) and torch.equal(Y, ref[1])
+    assert pol.status().timed_out == 0
+    pol.destroy()

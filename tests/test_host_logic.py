@@ -131,8 +131,8 @@ def test_planner_auto_tile_prefers_more_tiles_for_small_m():
     (12288, 6144, 12288, ds.MID_GELU, 64, ds.TILE_64x192),
     (12288, 6144, 12288, ds.MID_GELU, 256, ds.TILE_128x192_DEEP),
     (12288, 6144, 12288, ds.MID_GELU, 512, ds.TILE_128x192_DEEP),
-    (12288, 6144, 12288, ds.MID_GELU, 1024, ds.TILE_128x192),
-    (12288, 6144, 12288, ds.MID_GELU, 2048, ds.TILE_128x192),
+    (12288, 6144, 12288, ds.MID_GELU, 1024, ds.TILE_256x192),
+    (12288, 6144, 12288, ds.MID_GELU, 2048, ds.TILE_256x192),
     (8192, 2752, 8192, ds.MID_SWIGLU, 1, ds.TILE_64x128),
     (8192, 2752, 8192, ds.MID_SWIGLU, 256, ds.TILE_128x128_DEEP),
     (8192, 2752, 8192, ds.MID_SWIGLU, 1024, ds.TILE_256x128),
@@ -222,6 +222,52 @@ def test_every_slice_a_consumer_tile_loads_is_covered_by_a_wait(kind):
                 assert n == 0, (tile, M, K1, N1, N2, mid, ksplit)
                 checked += 1
     assert checked > 100
+
+
+def test_producer_and_consumer_may_use_different_tile_shapes():
+    # Section III-C: the consumer maps its rows and K steps onto the PRODUCER's tiles, so the two
+    # stages need not share a macro-tile shape.  Grids, slots and waves follow each stage's own shape.
+    d = _fake_gemm_desc(2048, 12288, 6144, 12288)
+    d.tile_prod, d.tile_cons = ds.TILE_256x192, ds.TILE_128x128
+    info = ds.PlanInfo()
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.OK
+    assert (info.tile_prod, info.tile_cons) == (ds.TILE_256x192, ds.TILE_128x128)
+    assert (info.prod_grid_x, info.prod_grid_y) == (32, 8)
+    assert (info.cons_grid_x, info.cons_grid_y) == (96, 16)
+    assert info.waves_streamsync == 1 + 3          # 256 tiles on 256 slots, 1536 tiles on 512 slots
+    # every slice a consumer tile loads is covered by a wait, for every pair of shapes and policy
+    checked = 0
+    for tp in ALL_TILES:
+        for tc in ALL_TILES:
+            if tp == tc:
+                continue
+            for (M, K1, N1, N2, mid) in ((300, 192, 576, 328, ds.MID_GELU), (2048, 1024, 1536, 768, ds.MID_NONE),
+                                         (150, 256, 192, 200, ds.MID_SWIGLU)):
+                for kind in (ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC):
+                    d = _fake_gemm_desc(M, K1, N1, N2, mid=mid)
+                    d.tile_prod, d.tile_cons = tp, tc
+                    try:
+                        n = ds.gemm_chain_check_waits(d, kind, n_cu=256)
+                    except ds.DepsyncError as e:
+                        assert e.status in (ds.EINVAL, ds.ENOTIMPL)
+                        continue
+                    assert n == 0, (tp, tc, M, K1, N1, N2, mid, kind)
+                    checked += 1
+    assert checked > 300
+    # the attention chain's three stages share one shape
+    d = _fake_gemm_desc(256, 512, 3 * 256, 512, mid=ds.MID_CAUSAL_ATTN)
+    d.T, d.ldt, d.ldw2 = 0x1000, 256, 256
+    d.batch, d.seq, d.heads, d.head_dim = 1, 256, 2, 128
+    d.tile_prod, d.tile_cons = ds.TILE_128x128, ds.TILE_64x64
+    assert ds._lib().depsync_gemm_chain_plan(ctypes.byref(d), None, 256, ctypes.byref(info)) == ds.ENOTIMPL
+    # convolutions: pairs may differ, longer chains may not
+    c = _fake_conv_n_desc(2, 28, 28, 128, (128, 64), tile=0)
+    c.tile_prod, c.tile_cons = ds.TILE_128x128, ds.TILE_64x64
+    for kind in (ds.ROWSYNC, ds.TILESYNC, ds.STRIDEDSYNC):
+        assert ds.conv_chain_n_check_waits(c, kind, n_cu=256) == 0
+    c = _fake_conv_n_desc(1, 56, 56, 64, (64, 64, 64), tile=0)
+    c.tile_prod, c.tile_cons = ds.TILE_128x128, ds.TILE_64x64
+    assert ds._lib().depsync_conv_chain_n_plan(ctypes.byref(c), None, 256, ctypes.byref(info)) == ds.ENOTIMPL
 
 
 def test_gated_mlp_rejects_tiles_whose_producer_half_is_narrower_than_a_k_step():
