@@ -24,9 +24,9 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
 # HBM-side bytes of one chain from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by what the
 # same counter reads for a 1 GiB copy), per workload and launch mode; see profiles/*.md for the runs.
 MEASURED_TRAFFIC_BYTES = {
-    ("gpt3_mlp", 2048, "fused"): (1154153 + 76049) * 1024,
-    ("gpt3_attn", 2048, "fused"): (1369160 + 129401) * 1024,
-    ("vgg_conv", 50176, "fused"): (352359 + 55037) * 1024,    # 56x56x256, batch 16 (the default conv shape)
+    ("gpt3_mlp", 2048, "fused"): (1035502 + 74913) * 1024,
+    ("gpt3_attn", 2048, "fused"): (1279942 + 82269) * 1024,
+    ("vgg_conv", 50176, "fused"): (334774 + 52044) * 1024,    # 56x56x256, batch 16 (the default conv shape)
 }
 
 
@@ -349,6 +349,9 @@ def sweep(args, torch, ds, inputs):
         cases = [("cfg1", dict())]
         cases += [("gpt3_mlp", dict(M=m)) for m in inputs.CFG2["Ms"]]
         cases += [("llama_mlp", dict(M=m)) for m in inputs.CFG3["Ms"]]
+        # the weight-streaming sizes once more with the weights packed K-blocked (a static, one-off repack)
+        cases += [("gpt3_mlp", dict(M=m, w_layout="kblocked")) for m in inputs.CFG2["Ms"] if m <= 64]
+        cases += [("llama_mlp", dict(M=m, w_layout="kblocked")) for m in inputs.CFG3["Ms"] if m <= 64]
         cases += [("gpt3_attn", dict(M=m)) for m in inputs.CFG4["Ms"]]
         cases += [("vgg_conv", dict(hw=hw, channels=ch, batch=b)) for hw, ch in inputs.CFG5["stages"] for b in (1, 16)]
     lines = ["| workload | tile | P / (mid) / C tiles | slots | waves ss / fine | best fine-grained us (policy/launch) | two streams us | "

@@ -29,12 +29,16 @@ __device__ __forceinline__ void run_tile(const ChainArgs& args, const TileId t, 
         }
     }
     if constexpr (SYNC) {
-        if (s.dep_kind != DEP_NONE) {
-            gemm_tile<Cfg, T, true, AMODE, true>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+        if (s.dep_kind == DEP_ROW || s.dep_kind == DEP_CONV_ROW) {   // one wait, before the first slice
+            gemm_tile<Cfg, T, true, AMODE, 1>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+            return;
+        }
+        if (s.dep_kind != DEP_NONE) {                                // waits inside the K loop as well
+            gemm_tile<Cfg, T, true, AMODE, 2>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
             return;
         }
     }
-    gemm_tile<Cfg, T, SYNC, AMODE, false>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+    gemm_tile<Cfg, T, SYNC, AMODE, 0>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
 }
 
 template <class Cfg, typename T, bool SYNC, uint32_t AMODE, int MIDK>
