@@ -127,7 +127,7 @@ class Workload:
             self.name = f"GPT-3 MLP shard X[{M}x12288] W1[12288x6144] GeLU W2[6144x12288] bf16"
         elif kind == "llama_mlp":
             t = inputs.swiglu(M=M, K1=8192, Nh=2752, N2=8192); self.mid = ds.MID_SWIGLU; W1 = t["Wgu"]
-            self.name = f"LLaMA-65B MLP shard X[{M}x8192] [Wg|Wu][8192x5504] SwiGLU W2[2752x8192] bf16"
+            self.name = f"LLaMA-65B MLP shard X[{M}x8192] [Wg,Wu][8192x5504] SwiGLU W2[2752x8192] bf16"
         elif kind == "gpt3_attn_gen":
             # token generation (Fig. 2b): one new token per sequence over `cached` earlier ones
             c = inputs.CFG4; self.mid = ds.MID_CAUSAL_ATTN

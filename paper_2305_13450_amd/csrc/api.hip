@@ -283,6 +283,10 @@ int policy_dep_kind_conv(int kind) {
 // of the slots idle, as far as one wave of slots allows, keeping every part at least 16 steps
 // long (the partial tiles and the arrival count cost about 10 us per stage) and starting on a
 // segment boundary.  `tuned_off`: the autotuner found this chain faster without.
+// (Splitting a stage of more tiles than slots so that it ends in a fuller last round was measured
+// and is not done: LLaMA MLP at 2048 tokens, 344 producer tiles on 256 slots as 688 halves, three
+// rounds of 64 steps instead of two of 128: 275 -> 283 us; the 88 MB of partial tiles and the
+// finishing workgroups cost more than the shorter last round gains.)
 uint32_t choose_split(const sync_policy* pol, bool tuned_off, uint32_t tiles, uint32_t slots, uint32_t kt, uint32_t seg) {
     const uint32_t want = pol ? pol->params.ksplit : 0;
     if (want == 1 || seg == 0 || (want == 0 && tuned_off)) return 1;

@@ -29,16 +29,26 @@ __device__ __forceinline__ void run_tile(const ChainArgs& args, const TileId t, 
         }
     }
     if constexpr (SYNC) {
+        // a dependent stage that is itself waited for exists only in chains of three or four
+        // convolutions (the middle stage of a GeMM chain is the attention tile)
+        constexpr bool MID = AMODE == A_CONV3X3;
+        const bool posts = s.post_kind != DEP_NONE;
         if (s.dep_kind == DEP_ROW || s.dep_kind == DEP_CONV_ROW) {   // one wait, before the first slice
-            gemm_tile<Cfg, T, true, AMODE, 1>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+            if constexpr (MID) {
+                if (posts) { gemm_tile<Cfg, T, true, AMODE, 1, true>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr); return; }
+            }
+            gemm_tile<Cfg, T, true, AMODE, 1, false>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
             return;
         }
         if (s.dep_kind != DEP_NONE) {                                // waits inside the K loop as well
-            gemm_tile<Cfg, T, true, AMODE, 2>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+            if constexpr (MID) {
+                if (posts) { gemm_tile<Cfg, T, true, AMODE, 2, true>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr); return; }
+            }
+            gemm_tile<Cfg, T, true, AMODE, 2, false>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
             return;
         }
     }
-    gemm_tile<Cfg, T, SYNC, AMODE, 0>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
+    gemm_tile<Cfg, T, SYNC, AMODE, 0, SYNC>(args, s, t.tx, t.ty, t.rel, lds, t_enter, dr);
 }
 
 template <class Cfg, typename T, bool SYNC, uint32_t AMODE, int MIDK>

@@ -150,7 +150,8 @@ __device__ __forceinline__ const char* uni_ptr(const void* p) {
 // for before its first slice (RowSync, and the convolution's whole-halo wait), so the K loop is
 // the one of a tile without dependencies; DEP == 2: new dependency segments start inside the K
 // loop (TileSync, StridedSync, the convolution's per-filter-row waits).
-template <class Cfg, typename T, bool SYNC, uint32_t AMODE, int DEP, class DR>
+// THROUGH: the tile's output is waited for by a later stage and is stored write-through.
+template <class Cfg, typename T, bool SYNC, uint32_t AMODE, int DEP, bool THROUGH, class DR>
 __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc& s, uint32_t tx, uint32_t tyz,
                                           uint32_t rel_ticket, char* lds, uint64_t t_enter, DR& dr) {
     using M = Mma<T>;
@@ -158,11 +159,11 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
     constexpr int TM = Cfg::TM, TN = Cfg::TN, FM = Cfg::FM, FN = Cfg::FN;
     constexpr int NIA = Cfg::NIA, NIB = Cfg::NIB;
     static_assert(!DEP || SYNC, "dependencies exist only with the synchronisation hooks compiled in");
-    // A tile without a dependency is a chain's first stage, whose output the next stage waits
-    // for: it is stored write-through so that the post needs no L2 write-back.  A dependent GeMM
-    // tile is the last stage of every chain built here and stores normally (should it ever have
-    // to post, post_tile writes the L2 back for it).
-    constexpr bool THROUGH = SYNC && !DEP;
+    // A tile whose output a later stage waits for stores it write-through, so that the post needs
+    // no write-back of the L2: a chain's first stage, and the middle stages of a chain of three or
+    // four convolutions.  The last stage stores normally.  (A posting tile instantiated without
+    // THROUGH still works: post_tile then writes the L2 back for it.)
+    static_assert(!THROUGH || SYNC, "write-through stores belong to the synchronised kernels");
 
     const uint32_t tid = threadIdx.x, lane = tid & 63u;
     const uint32_t wave = uni(tid >> 6);
