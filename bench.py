@@ -24,9 +24,9 @@ PEAK_BF16_TFLOPS = 2516.6   # 256 CU x 4096 flop/clk/CU x 2.4 GHz, dense
 # HBM-side bytes of one chain from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (each scaled by what the
 # same counter reads for a 1 GiB copy), per workload and launch mode; see profiles/*.md for the runs.
 MEASURED_TRAFFIC_BYTES = {
-    ("gpt3_mlp", 2048, "fused"): (1035502 + 74913) * 1024,
-    ("gpt3_attn", 2048, "fused"): (1279942 + 82269) * 1024,
-    ("vgg_conv", 50176, "fused"): (334774 + 52044) * 1024,    # 56x56x256, batch 16 (the default conv shape)
+    ("gpt3_mlp", 2048, "fused"): (1035398 + 74933) * 1024,
+    ("gpt3_attn", 2048, "fused"): (1278478 + 82272) * 1024,
+    ("vgg_conv", 50176, "fused"): (327659 + 52046) * 1024,    # 56x56x256, batch 16 (the default conv shape)
 }
 
 

@@ -331,6 +331,9 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         ready_until = k + 1;
                     } else {
                         ready_until = seg_steps ? k + n_ready * seg_steps : 0xffffffffu;
+                        // the segments seen posted need no further look: the next check is due where
+                        // they end (unless every wait is being counted)
+                        if (!(args.flags & DS_FLAG_COUNT)) seg_next = ready_until;
                     }
                 }
                 if (args.flags & DS_FLAG_COUNT) {
