@@ -3,13 +3,14 @@
 //
 //  * Dispatch.  The paper relies on CUDA issuing the blocks of the earlier-launched kernel
 //    first and adds a one-thread "wait kernel" to order the launches (Section III-B).  HIP
-//    makes no such promise across hardware queues, so here EVERY workgroup of every launch of
-//    a chain draws its tile from shared dispatch queues in which all producer tiles come
+//    makes no such promise across hardware queues, so here the workgroups of every launch of
+//    a chain draw their tiles from shared dispatch queues in which all producer tiles come
 //    before the consumer tiles, each stage in row-major order (Section III-C); see Drawer.
 //    A workgroup can only be spinning while it holds a consumer tile, and the producer tiles
 //    it waits for are held by resident workgroups that never wait or are still ahead of every
 //    consumer in their queue, so every semaphore is eventually posted whatever the dispatcher
-//    does.
+//    does.  (Tiles named by the block index instead, hw_order_tile, are for launches whose
+//    tiles are all resident at once, or at the caller's explicit request.)
 //  * post: every wave drains its write-through stores, the workgroup meets at a barrier, one
 //    lane increments the tile's semaphore at agent scope (Section III-D).
 //  * wait: every wave polls the same semaphore word (all lanes read one address, the result
