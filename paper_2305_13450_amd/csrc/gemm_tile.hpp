@@ -323,6 +323,11 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
                         }
                     }
                     const uint64_t mask = __ballot(ok);
+                    // the requests for the dependent slice stay behind the look at its semaphores:
+                    // a compiler fence (the loads are relaxed atomics, which the compiler may
+                    // otherwise reorder with ordinary memory operations); the hardware returns
+                    // loads in issue order, and the wave acts on the values only after they arrived
+                    __atomic_signal_fence(__ATOMIC_ACQUIRE);
                     const uint32_t n_ready = (~mask == 0) ? 64u : (uint32_t)__builtin_ctzll(~mask);
                     if (n_ready == 0) {
                         if (reorder && b_due) issue_B(stage);

@@ -30,8 +30,14 @@ namespace depsync {
 #define DS_FLAG_HW_ORDER 8u
 #define DS_FLAG_TRACE 16u
 
+// One look at a semaphore.  The load is a relaxed atomic; the compiler fence behind it keeps
+// every later memory operation of the wave (the requests for the tiles being waited for) behind
+// the look.  On the hardware side loads return in issue order and the wave acts on the value
+// only after it has arrived, caches are invalidated at kernel start, and a line of an
+// intermediate is never read before its producer has posted: no cache invalidate is needed.
 __device__ __forceinline__ uint32_t sem_load(const uint32_t* sem) {
     uint32_t v = __hip_atomic_load(sem, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __atomic_signal_fence(__ATOMIC_ACQUIRE);
     return __builtin_amdgcn_readfirstlane(v);
 }
 
