@@ -445,7 +445,7 @@ def ablation(args, torch, ds, wl):
     tuner.destroy()
     for pn in wl.policies:
         # "one dispatch" here means persistent workgroups drawing from the dispatch queues, so that
-        # the last row of each group isolates the block-index order (the library's default otherwise)
+        # the last row of each group isolates the block-index order
         for label, flags, mn in ((f"{pn}, one dispatch", ds.FLAG_QUEUE_ORDER, "fused"), (f"{pn}, two streams", 0, "fine"),
                                  (f"{pn}, one dispatch, wait before the weights are requested",
                                   ds.FLAG_NO_REORDER | ds.FLAG_QUEUE_ORDER, "fused"),

@@ -3,8 +3,8 @@
 // 256 threads = 4 wave64s in a WM x WN grid; each wave owns a (TM/WM) x (TN/WN) sub-tile built
 // from 32x32 accumulator blocks of v_mfma_f32_32x32x16 (bf16 or f16 in, fp32 accumulate).
 // Operand tiles of 64 K-elements (128-byte rows) are DMA'd from global memory straight into
-// LDS (global_load_lds_dwordx4), double-buffered, with the 16-byte chunks of every row XOR
-// swizzled so that the 128-bit fragment reads are free of bank conflicts.
+// LDS (global_load_lds_dwordx4), two to eight stages deep (a ring per operand), with the 16-byte
+// chunks of every row XOR swizzled so that the 128-bit fragment reads are free of bank conflicts.
 //
 // The tile is the unit the synchronisation subsystem works on (Fig. 4a of the paper): a
 // consumer tile waits before loading the slice of A that an earlier stage produces, and a
