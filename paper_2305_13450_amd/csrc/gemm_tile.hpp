@@ -572,8 +572,7 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
         if (finish) {
             // Every part's partial is in memory (each counted after its stores had completed) and none of
             // these lines has been read on this XCD since the kernel started.  Sum in K order,
-            // whoever came last, so that the result does not depend on the arrival order.  All
-            // loads of one part and one row of blocks are issued before the first is added.
+            // whoever came last, so that the result does not depend on the arrival order.
             if (tid == 0) __hip_atomic_store(s.arrive + tile_lin * SYNC_WORD_STRIDE, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             // The sum is p0 + p1 + p2 + ... from the left.  A finisher that holds part 0 or
             // part 1 starts from its registers (p1 + p0 and p0 + p1 are the same number) and
@@ -587,22 +586,61 @@ __device__ __forceinline__ void gemm_tile(const ChainArgs& args, const StageDesc
 #pragma unroll
                         for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
             }
-            for (uint32_t z = 0; z < S; ++z) {
-                if (own && z == kz) continue;
-                const float* src = part + (size_t)z * (TM * TN) + (tid << 2);
+            // The partials were written on other XCDs and come from memory: a read costs a round
+            // trip of a couple of microseconds whatever its size, and a skinny chain's tile has
+            // little else left to do.  So the loads of as many whole parts as the registers
+            // beside the accumulators hold (PARTS_IN_FLIGHT) are issued before the first of them
+            // is added; the adds stay in K order.
+            constexpr int ACCF = FM * FN * 16;                                   // accumulator floats per lane
+            constexpr int ROOM = Cfg::MINB == 1 ? (472 - ACCF < 192 ? 472 - ACCF : 192) : 216 - ACCF;
+            constexpr int PARTS_IN_FLIGHT = ROOM / ACCF > 8 ? 8 : ROOM / ACCF;
+            if constexpr (PARTS_IN_FLIGHT >= 1) {
+                constexpr int NV = FM * FN * 4;                                  // 16-byte loads per lane and part
+                for (uint32_t z0 = 0; z0 < S; z0 += PARTS_IN_FLIGHT) {
+                    f32x4 t4[PARTS_IN_FLIGHT][NV];
+                    // (parts past the end read the last part again and are not added: the loads stay
+                    // unconditional, so that all of a batch are in flight together)
 #pragma unroll
-                for (int i = 0; i < FM; ++i) {
-                    f32x4 t4[FN][4];
+                    for (int d = 0; d < PARTS_IN_FLIGHT; ++d) {
+                        const uint32_t z = min(z0 + d, S - 1);
+                        const float* src = part + (size_t)z * (TM * TN) + (tid << 2);
 #pragma unroll
-                    for (int j = 0; j < FN; ++j)
+                        for (int u = 0; u < NV; ++u) t4[d][u] = *(const f32x4*)(src + ((u * 256) << 2));
+                    }
 #pragma unroll
-                        for (int q = 0; q < 4; ++q) t4[j][q] = *(const f32x4*)(src + ((((i * FN + j) * 4 + q) * 256) << 2));
+                    for (int d = 0; d < PARTS_IN_FLIGHT; ++d) {
+                        const uint32_t z = z0 + d;
+                        if (z < S && !(own && z == kz)) {
 #pragma unroll
-                    for (int j = 0; j < FN; ++j)
+                            for (int i = 0; i < FM; ++i)
 #pragma unroll
-                        for (int q = 0; q < 4; ++q)
+                                for (int j = 0; j < FN; ++j)
 #pragma unroll
-                            for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += t4[j][q][e];
+                                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                                        for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += t4[d][(i * FN + j) * 4 + q][e];
+                        }
+                    }
+                }
+            } else {
+                // no room for a whole part: one row of blocks of one part at a time
+                for (uint32_t z = 0; z < S; ++z) {
+                    if (own && z == kz) continue;
+                    const float* src = part + (size_t)z * (TM * TN) + (tid << 2);
+#pragma unroll
+                    for (int i = 0; i < FM; ++i) {
+                        f32x4 t4[FN][4];
+#pragma unroll
+                        for (int j = 0; j < FN; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q) t4[j][q] = *(const f32x4*)(src + ((((i * FN + j) * 4 + q) * 256) << 2));
+#pragma unroll
+                        for (int j = 0; j < FN; ++j)
+#pragma unroll
+                            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                                for (int e = 0; e < 4; ++e) acc[i][j][4 * q + e] += t4[j][q][e];
+                    }
                 }
             }
         }
