@@ -252,17 +252,30 @@ struct Drawer {
         looked = true;
     }
 
-    // When the tile's main loop ends: near the end of the queue, start reading its counter (the
+    // When the tile's main loop ends.  Away from the end of the queue the increment for the next
+    // tile starts here already: it is served at the memory side, one workgroup of the XCD after
+    // the other, and the tile's stores are followed by a wait for everything the wave has in
+    // flight, so an increment started during the stores holds up the post (measured on the GPT-3
+    // chain at 2048 tokens: the tiles of a queue-order launch ended 1-2 us later than the same
+    // tiles named by the block index).  Near the end of the queue only its counter is read (the
     // value is not looked at here, so the load stays in flight behind what the wave does next).
     __device__ __forceinline__ void peek() {
-        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi || !near_end()) return;
+        if (threadIdx.x != DRAW_THREAD || open > a.stage_hi) return;
+        if (!near_end()) { start_increment(); return; }
         c0 = __hip_atomic_load(counter(cur_q), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         peeked = true;
     }
 
-    // A while later (during the tile's stores): start the increment for the next tile on the
-    // queue drawn from last; near its end only if the counter read by peek() shows entries,
-    // else start reading all eight counters for draw().
+    __device__ __forceinline__ void start_increment() {
+        if (pending || a.draw_cas || queue_len(a.st[open], cur_q) == 0) return;
+        pend_q = cur_q;
+        pend_val = __hip_atomic_fetch_add(counter(cur_q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        pending = true;
+    }
+
+    // A while later (before the tile's stores): near the end of the queue, start the increment for
+    // the next tile on the queue drawn from last if the counter read by peek() shows entries,
+    // else start reading all eight counters for draw().  (Elsewhere peek() has started it.)
     __device__ __forceinline__ void grab() {
         if (threadIdx.x != DRAW_THREAD || open > a.stage_hi || pending || a.draw_cas) return;
         const uint32_t len = queue_len(a.st[open], cur_q);
@@ -271,10 +284,7 @@ struct Drawer {
             peeked = false;
             if (c0 - base(len) >= len) { look(); return; }    // empty: draw() picks another queue or moves on
         }
-        if (len == 0) return;
-        pend_q = cur_q;
-        pend_val = __hip_atomic_fetch_add(counter(cur_q), 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        pending = true;
+        start_increment();
     }
 
     __device__ __forceinline__ bool take(uint32_t q, uint32_t val, uint32_t& stage, uint32_t& tx, uint32_t& ty) {
